@@ -1,0 +1,189 @@
+/* libtlt: the speculative-decoding step of a long-tail rollout on one MI355X (gfx950).
+ *
+ * One step = drafter tree expansion -> target verification forward -> lossless acceptance ->
+ * commit of the accepted path into the paged KV cache (the rollout workflow steps 1-4 of the
+ * paper's system overview, Section 3 "Architecture & Workflow"; the mechanism is stated in
+ * Section 2.2 "Mechanism of Speculative Decoding").
+ *
+ * Conventions
+ *  - Plain C ABI.  Every pointer is either HOST or DEVICE memory as marked.  The caller owns all
+ *    device memory (weights, KV pools, block tables, workspace, inputs, outputs); the context
+ *    owns only host-side descriptors.  No entry point allocates or frees device memory.
+ *  - Every entry point enqueues its kernels on the caller's stream (`hipStream_t` passed as
+ *    void*) and returns without waiting; outputs are valid once that stream has been synchronised.
+ *  - Return value: TLT_OK or a negative error code; nothing has been enqueued when an error code
+ *    other than TLT_EHIP is returned.  Host-side arguments are validated; device contents
+ *    (page ids, lengths) are additionally range-checked inside the kernels, which skip a row
+ *    rather than touch memory outside the pools.
+ *  - Matrices are row-major [out_features][in_features].  `dtype` selects the storage type of
+ *    weights, KV cache and intermediate activations (fp32 or bf16); accumulation, the residual
+ *    stream, softmax, logits and hidden-state outputs are always fp32.
+ *  - Shapes: B sequences, n tree nodes per sequence (node 0 = root = last emitted token, not yet
+ *    in the cache; parents precede children), h = hidden, V = vocab.
+ */
+#ifndef TLT_H
+#define TLT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TLT_OK = 0,
+    TLT_EINVAL = -1,   /* NULL / out-of-range argument */
+    TLT_ESHAPE = -2,   /* size exceeds what tlt_create was told, or workspace too small */
+    TLT_ENOPAGES = -3, /* block table cannot hold seq_len_bound + new rows */
+    TLT_EHIP = -4,     /* a HIP call failed (see tlt_last_hip_error) */
+    TLT_ENOTIMPL = -5
+};
+
+enum { TLT_F32 = 0, TLT_BF16 = 1 };
+enum { TLT_MAX_TREE = 64, TLT_MAX_TOPK = 16, TLT_MAX_DEPTH = 16 };
+
+typedef struct tlt_model_cfg {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp, vocab;
+    float rms_eps, rope_theta;
+    int32_t dtype;     /* TLT_F32 or TLT_BF16 */
+    int32_t page_size; /* tokens per KV page (16) */
+} tlt_model_cfg;
+
+/* DEVICE pointers to one decoder block's parameters, all of the model dtype.
+ * wqkv [(Hq+2Hkv)*d][h] stacks q heads, k heads, v heads; wo [h][Hq*d]; wg, wu [F][h]; wd [h][F]. */
+typedef struct tlt_layer_weights {
+    const void *attn_norm, *wqkv, *wo, *mlp_norm, *wg, *wu, *wd;
+} tlt_layer_weights;
+
+/* embed, lm_head [V][h], final_norm [h]: DEVICE.  layers: HOST array of n_layers entries (copied by
+ * tlt_create).  fc [h][2h] (DEVICE) is the drafter's input projection (columns 0..h-1 act on the
+ * token embedding, h..2h-1 on the hidden state) and is NULL for the target.  The drafter reuses
+ * the target's embed / lm_head / final_norm (Section 4.1 "Model Architecture"). */
+typedef struct tlt_weights {
+    const void *embed, *lm_head, *final_norm;
+    const tlt_layer_weights *layers;
+    const void *fc;
+} tlt_weights;
+
+/* Paged KV cache of one model.  k_pool, v_pool: DEVICE [n_layers][n_pages][n_kv_heads][page_size][d]
+ * in the model dtype.  block_table: DEVICE [B][max_pages] page ids; slot s of sequence b lives in
+ * page block_table[b][s / page_size] at row s % page_size.  seq_len: DEVICE [B] committed tokens.
+ * seq_len_bound: HOST-known upper bound of max_b seq_len[b] (sizes the attention grid and is
+ * checked against the block table; a bound that is too small drops the excess context rows). */
+typedef struct tlt_kv {
+    void *k_pool, *v_pool;
+    int64_t n_pages;
+    const int32_t *block_table;
+    int32_t *seq_len;
+    int32_t max_pages;
+    int32_t seq_len_bound;
+} tlt_kv;
+
+/* Token tree, DEVICE arrays [B][n] each.  anc_mask bit j of node i = node j is i or an ancestor of
+ * i.  score = sum of draft log-probabilities from the root (0 for the root). */
+typedef struct tlt_tree {
+    int32_t *token, *parent, *depth;
+    uint64_t *anc_mask;
+    float *score;
+    int32_t n;
+} tlt_tree;
+
+typedef struct tlt_ctx tlt_ctx;
+
+const char *tlt_strerror(int code);
+/* hipError_t value of the last failing HIP call seen by this context (0 if none). */
+int tlt_last_hip_error(const tlt_ctx *ctx);
+
+/* Bytes of DEVICE workspace needed for the given limits (max_ctx = largest seq_len_bound + n). */
+size_t tlt_workspace_bytes(const tlt_model_cfg *cfg, int max_batch, int max_n, int max_depth, int max_topk,
+                           int max_ctx);
+
+/* Creates a context.  `draft` may be NULL (then tlt_draft_expand returns TLT_EINVAL).  The
+ * workspace must stay allocated until tlt_destroy; calls on one context must not overlap. */
+int tlt_create(tlt_ctx **out, const tlt_model_cfg *cfg, const tlt_weights *target, const tlt_weights *draft,
+               int max_batch, int max_n, int max_depth, int max_topk, int max_ctx, void *workspace,
+               size_t workspace_bytes);
+int tlt_destroy(tlt_ctx *ctx);
+
+/* Drafter: catch up on newly committed positions, then expand and prune the token tree
+ * (Section 4.1 "Model Architecture": single decoder block fed with the target's hidden state and
+ * the token embedding through a linear layer; Section 5.1 "Tree-based Drafting": topK options per
+ * step for Draft_Depth steps, keep the Tokens_to_Verify most confident nodes).
+ *
+ * Extend: for sequence b and j < n_new[b], drafter cache entry draft_kv.seq_len[b]+j is built from
+ * token new_tokens[b][j] and hidden-state row hidden[b][new_src[b][j]]; draft_kv.seq_len[b] +=
+ * n_new[b].  After a step, new_tokens = tlt_accept's out_tokens, new_src = its path_idx, n_new =
+ * its n_out, hidden = tlt_verify_forward's out_hidden.  0 <= n_new[b] <= new_stride <= 64; at
+ * least one call with n_new[b] >= 1 must precede the first expansion of sequence b.
+ * Expand (skipped when depth == 0 or out_tree == NULL): level 0 takes the topk most likely tokens
+ * after the root; each further level runs the topk frontier nodes through the drafter, takes
+ * each one's topk children and keeps the topk best of the topk^2 by path score as next frontier;
+ * finally the n_verify-1 candidates of highest path score plus the root form the tree, in creation
+ * order.  The root's token is root_tokens[b], or, when root_tokens is NULL, the last new token of
+ * sequence b (new_tokens[b][n_new[b]-1]: the bonus token of the previous step).  Ties prefer the candidate created first / the lower token.
+ * out_tree->n must equal min(n_verify, 1 + topk + (depth-1)*topk^2).
+ * Provisional drafter entries use rows seq_len .. seq_len + (depth-1)*topk - 1 of draft_kv.
+ * All pointers DEVICE except the structs themselves.  mode must be 0 (deterministic top-k). */
+int tlt_draft_expand(tlt_ctx *ctx, void *stream, int B, int depth, int topk, int n_verify, int mode,
+                     const int32_t *new_tokens, const int32_t *new_src, const int32_t *n_new, int new_stride,
+                     const float *hidden, int hidden_n, const int32_t *root_tokens, tlt_kv *draft_kv,
+                     tlt_tree *out_tree);
+
+/* Fills depth and anc_mask of a caller-made tree from token/parent (parents must precede
+ * children; parent[0] = -1). */
+int tlt_tree_finalize(tlt_ctx *ctx, void *stream, int B, tlt_tree *tree);
+
+/* Target verification of all tree nodes in one forward pass (Section 2.2): node i attends to the
+ * seq_len[b] committed tokens and to its ancestors-or-self, with rotary position seq_len[b] +
+ * depth[i]; its key/value are written to provisional slot seq_len[b] + i.  seq_len is unchanged.
+ * Outputs (DEVICE, any may be NULL): out_logits [B][n][V] fp32; out_argmax [B][n] (lowest index on
+ * ties); out_hidden [B][n][h] fp32 = last block's output before the final norm. */
+int tlt_verify_forward(tlt_ctx *ctx, void *stream, int B, const tlt_tree *tree, tlt_kv *kv, float *out_logits,
+                       int32_t *out_argmax, float *out_hidden);
+
+/* Lossless acceptance (Section 2.2: keep the drafted prefix up to the first disagreement plus the
+ * target's own token; Section 1 / Section 3 principle (a): output distributed exactly as the
+ * target's).
+ * mode 0, greedy: from the root follow the child whose token equals the target's argmax at the
+ *   current node (target_argmax if non-NULL, else argmax of target_logits).
+ * mode 1, sampling at `temperature`: recursive rejection sampling; draft_q [B][n][V] row i is the
+ *   distribution node i's children were drawn from without replacement, u_accept [B][n] and
+ *   u_final [B] are caller-supplied 32-bit uniforms.  Integer/double arithmetic as documented in
+ *   the design notes makes every decision reproducible bit for bit.
+ * Outputs (DEVICE): accept_len [B] (drafted tokens kept, without the bonus token); path_idx
+ * [B][stride] node indices root..last accepted; out_tokens [B][stride] accepted tokens then the
+ * bonus token; n_out [B] = accept_len+1; unused entries = -1.  stride >= 1 caps accept_len+1. */
+int tlt_accept(tlt_ctx *ctx, void *stream, int B, int mode, float temperature, const tlt_tree *tree,
+               const float *target_logits, const int32_t *target_argmax, const float *draft_q,
+               const uint32_t *u_accept, const uint32_t *u_final, int stride, int32_t *accept_len,
+               int32_t *path_idx, int32_t *out_tokens, int32_t *n_out);
+
+/* Keeps the accepted path: in every layer and kv head, row seq_len[b]+path_idx[b][j] moves to row
+ * seq_len[b]+j for j <= accept_len[b]; then seq_len[b] += accept_len[b]+1 (the bonus token is not
+ * cached: it is the next root).  kv->seq_len_bound is NOT updated (host field: the caller adds
+ * its own bound, e.g. stride). */
+int tlt_kv_commit(tlt_ctx *ctx, void *stream, int B, tlt_kv *kv, const int32_t *accept_len,
+                  const int32_t *path_idx, int stride);
+
+/* ---- auxiliary entry points (unit tests, per-kernel measurement) ---- */
+
+/* C[M][N] (op)= A[M][K] . W[N][K]^T on DEVICE buffers of dtype (TLT_F32/TLT_BF16).
+ * out_mode 0: C stored in dtype; 1: C stored as fp32; 2: fp32 C += product. */
+int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const void *A, const void *W, void *C);
+
+/* Attention kernel choice for cross-checks: -1 automatic (default), 0 wave-per-row kernel,
+ * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
+int tlt_set_attention_impl(tlt_ctx *ctx, int impl);
+
+/* Per-kernel-class timing with HIP events on the launch stream.  Classes: 0 GEMM, 1 attention,
+ * 2 KV commit, 3 everything else.  tlt_profile_read synchronises the recorded events and returns,
+ * per class, summed milliseconds, launches, algorithmic flops and algorithmic bytes since the last
+ * tlt_profile_begin.  Arrays are HOST, 4 entries each. */
+int tlt_profile_begin(tlt_ctx *ctx, int enable);
+int tlt_profile_read(tlt_ctx *ctx, double *ms, int64_t *launches, double *flops, double *bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,257 @@
+"""Thin ctypes binding of libtlt.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory and streams; every step of the path runs in the library's HIP
+kernels.  There is no CPU fallback: loading fails loudly when the library has not been built
+(`python -m paper_2511_16665_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import dataclasses
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtlt.so")
+
+TLT_F32, TLT_BF16 = 0, 1
+ERRORS = {0: "TLT_OK", -1: "TLT_EINVAL", -2: "TLT_ESHAPE", -3: "TLT_ENOPAGES", -4: "TLT_EHIP", -5: "TLT_ENOTIMPL"}
+
+EXPORTS = [
+    "tlt_strerror", "tlt_last_hip_error", "tlt_workspace_bytes", "tlt_create", "tlt_destroy", "tlt_draft_expand",
+    "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
+    "tlt_profile_begin", "tlt_profile_read",
+]
+
+
+class TltError(RuntimeError):
+    def __init__(self, code, where, hip=0):
+        self.code = code
+        super().__init__(f"{where}: {ERRORS.get(code, code)}" + (f" (hipError {hip})" if hip else ""))
+
+
+class ModelCfgC(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "mlp", "vocab")] + \
+        [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("page_size", C.c_int32)]
+
+
+class LayerWeightsC(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("attn_norm", "wqkv", "wo", "mlp_norm", "wg", "wu", "wd")]
+
+
+class WeightsC(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("layers", C.POINTER(LayerWeightsC)), ("fc", C.c_void_p)]
+
+
+class KVC(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("n_pages", C.c_int64), ("block_table", C.c_void_p),
+                ("seq_len", C.c_void_p), ("max_pages", C.c_int32), ("seq_len_bound", C.c_int32)]
+
+
+class TreeC(C.Structure):
+    _fields_ = [("token", C.c_void_p), ("parent", C.c_void_p), ("depth", C.c_void_p), ("anc_mask", C.c_void_p),
+                ("score", C.c_void_p), ("n", C.c_int32)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads libtlt.so; raises if it is missing (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2511_16665_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    lib.tlt_strerror.restype = C.c_char_p
+    lib.tlt_workspace_bytes.restype = C.c_size_t
+    lib.tlt_workspace_bytes.argtypes = [C.POINTER(ModelCfgC)] + [C.c_int] * 5
+    lib.tlt_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(ModelCfgC), C.POINTER(WeightsC), C.POINTER(WeightsC)] + \
+        [C.c_int] * 5 + [C.c_void_p, C.c_size_t]
+    lib.tlt_destroy.argtypes = [C.c_void_p]
+    lib.tlt_last_hip_error.argtypes = [C.c_void_p]
+    lib.tlt_draft_expand.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p, C.c_int,
+                                                                                         C.c_void_p, C.POINTER(KVC),
+                                                                                         C.POINTER(TreeC)]
+    lib.tlt_tree_finalize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC)]
+    lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 3
+    lib.tlt_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 5 + \
+        [C.c_int] + [C.c_void_p] * 4
+    lib.tlt_kv_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(KVC), C.c_void_p, C.c_void_p, C.c_int]
+    lib.tlt_gemm.argtypes = [C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3
+    lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
+    lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
+    lib.tlt_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_double)]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA/HIP tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def torch_dtype(dtype_code: int):
+    return torch.float32 if dtype_code == TLT_F32 else torch.bfloat16
+
+
+@dataclasses.dataclass
+class KV:
+    """Paged KV cache of one model: pools [L, n_pages, Hkv, page, d], block_table [B, max_pages] int32,
+    seq_len [B] int32 (device), seq_len_bound = host-known upper bound of seq_len."""
+    k_pool: torch.Tensor
+    v_pool: torch.Tensor
+    block_table: torch.Tensor
+    seq_len: torch.Tensor
+    seq_len_bound: int
+
+    def c(self) -> KVC:
+        assert self.block_table.dtype == torch.int32 and self.seq_len.dtype == torch.int32
+        return KVC(_ptr(self.k_pool), _ptr(self.v_pool), self.k_pool.shape[1], _ptr(self.block_table), _ptr(self.seq_len),
+                   self.block_table.shape[1], int(self.seq_len_bound))
+
+
+@dataclasses.dataclass
+class Tree:
+    """Token tree, device tensors [B, n]: token/parent/depth int32, anc_mask int64 (bit pattern), score fp32."""
+    token: torch.Tensor
+    parent: torch.Tensor
+    depth: torch.Tensor
+    anc_mask: torch.Tensor
+    score: torch.Tensor
+
+    @staticmethod
+    def empty(B: int, n: int, device="cuda") -> "Tree":
+        i32 = lambda: torch.zeros((B, n), dtype=torch.int32, device=device)
+        return Tree(i32(), i32(), i32(), torch.zeros((B, n), dtype=torch.int64, device=device),
+                    torch.zeros((B, n), dtype=torch.float32, device=device))
+
+    @property
+    def n(self) -> int:
+        return self.token.shape[1]
+
+    def c(self) -> TreeC:
+        return TreeC(_ptr(self.token), _ptr(self.parent), _ptr(self.depth), _ptr(self.anc_mask), _ptr(self.score), self.n)
+
+
+def _weights_c(w: dict, n_layers: int, fc=None, keep=None):
+    layers = (LayerWeightsC * n_layers)()
+    src = w["layers"] if "layers" in w else [w["layer"]]
+    for i in range(n_layers):
+        for k, _ in LayerWeightsC._fields_:
+            setattr(layers[i], k, src[i][k].data_ptr())
+    keep.append(layers)
+    return layers
+
+
+class Context:
+    """tlt_create / tlt_destroy plus the step's calls as methods with the C names."""
+
+    def __init__(self, cfg, dtype_code: int, target: dict, draft: Optional[dict], max_batch: int, max_n: int,
+                 max_depth: int, max_topk: int, max_ctx: int):
+        lib = load()
+        self.lib = lib
+        self.cfg = cfg
+        self.dtype_code = dtype_code
+        self.ccfg = ModelCfgC(cfg.n_layers, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.mlp, cfg.vocab,
+                              cfg.rms_eps, cfg.rope_theta, dtype_code, cfg.page_size)
+        nbytes = lib.tlt_workspace_bytes(C.byref(self.ccfg), max_batch, max_n, max_depth, max_topk, max_ctx)
+        if nbytes == 0:
+            raise TltError(-1, "tlt_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self._keep = [target, draft]
+        tl = _weights_c(target, cfg.n_layers, keep=self._keep)
+        tw = WeightsC(target["embed"].data_ptr(), target["lm_head"].data_ptr(), target["final_norm"].data_ptr(), tl, None)
+        dw_ref = None
+        if draft is not None:
+            dl = _weights_c(draft, 1, keep=self._keep)
+            dw = WeightsC(target["embed"].data_ptr(), target["lm_head"].data_ptr(), target["final_norm"].data_ptr(), dl,
+                          draft["fc"].data_ptr())
+            dw_ref = C.byref(dw)
+        self.handle = C.c_void_p()
+        rc = lib.tlt_create(C.byref(self.handle), C.byref(self.ccfg), C.byref(tw), dw_ref, max_batch, max_n, max_depth,
+                            max_topk, max_ctx, _ptr(self.workspace), nbytes)
+        if rc:
+            raise TltError(rc, "tlt_create")
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            self.lib.tlt_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc, where):
+        if rc:
+            raise TltError(rc, where, self.lib.tlt_last_hip_error(self.handle))
+
+    def draft_expand(self, B, depth, topk, n_verify, new_tokens, new_src, n_new, hidden, root_tokens, draft_kv: KV,
+                     out_tree: Optional[Tree], mode=0):
+        new_stride = 0 if new_tokens is None else new_tokens.shape[1]
+        hidden_n = 0 if hidden is None else hidden.shape[1]
+        kvc = draft_kv.c()
+        tree_ref = None
+        if out_tree is not None:
+            tc = out_tree.c()
+            tree_ref = C.byref(tc)
+        self._check(self.lib.tlt_draft_expand(self.handle, _stream(), B, depth, topk, n_verify, mode, _ptr(new_tokens),
+                                              _ptr(new_src), _ptr(n_new), new_stride, _ptr(hidden), hidden_n,
+                                              _ptr(root_tokens), C.byref(kvc), tree_ref), "tlt_draft_expand")
+
+    def tree_finalize(self, B, tree: Tree):
+        tc = tree.c()
+        self._check(self.lib.tlt_tree_finalize(self.handle, _stream(), B, C.byref(tc)), "tlt_tree_finalize")
+
+    def verify_forward(self, B, tree: Tree, kv: KV, out_logits=None, out_argmax=None, out_hidden=None):
+        tc, kvc = tree.c(), kv.c()
+        self._check(self.lib.tlt_verify_forward(self.handle, _stream(), B, C.byref(tc), C.byref(kvc), _ptr(out_logits),
+                                                _ptr(out_argmax), _ptr(out_hidden)), "tlt_verify_forward")
+
+    def accept(self, B, mode, temperature, tree: Tree, target_logits, target_argmax, draft_q, u_accept, u_final, stride,
+               accept_len, path_idx, out_tokens, n_out):
+        tc = tree.c()
+        self._check(self.lib.tlt_accept(self.handle, _stream(), B, mode, temperature, C.byref(tc), _ptr(target_logits),
+                                        _ptr(target_argmax), _ptr(draft_q), _ptr(u_accept), _ptr(u_final), stride,
+                                        _ptr(accept_len), _ptr(path_idx), _ptr(out_tokens), _ptr(n_out)), "tlt_accept")
+
+    def kv_commit(self, B, kv: KV, accept_len, path_idx, stride):
+        kvc = kv.c()
+        self._check(self.lib.tlt_kv_commit(self.handle, _stream(), B, C.byref(kvc), _ptr(accept_len), _ptr(path_idx), stride),
+                    "tlt_kv_commit")
+
+    def set_attention_impl(self, impl: int):
+        self._check(self.lib.tlt_set_attention_impl(self.handle, impl), "tlt_set_attention_impl")
+
+    def profile_begin(self, enable=True):
+        self._check(self.lib.tlt_profile_begin(self.handle, int(enable)), "tlt_profile_begin")
+
+    def profile_read(self):
+        ms, n, fl, by = (C.c_double * 4)(), (C.c_int64 * 4)(), (C.c_double * 4)(), (C.c_double * 4)()
+        self._check(self.lib.tlt_profile_read(self.handle, ms, n, fl, by), "tlt_profile_read")
+        names = ("gemm", "attention", "kv_commit", "other")
+        return {k: {"ms": ms[i], "launches": n[i], "flops": fl[i], "bytes": by[i]} for i, k in enumerate(names)}
+
+
+def gemm(dtype_code, out_mode, A, W, Cout):
+    """tlt_gemm: Cout[M, N] (op)= A[M, K] . W[N, K]^T on device tensors."""
+    M, K = A.shape
+    N = W.shape[0]
+    rc = load().tlt_gemm(_stream(), dtype_code, out_mode, M, N, K, _ptr(A), _ptr(W), _ptr(Cout))
+    if rc:
+        raise TltError(rc, "tlt_gemm")

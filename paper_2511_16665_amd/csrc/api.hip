@@ -1,0 +1,529 @@
+// C ABI of libtlt (see include/tlt.h): argument validation, workspace carving, and the sequence of
+// kernel launches that makes up each of the four calls of the speculative-decoding step.
+#include "../../include/tlt.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace tlt;
+
+namespace {
+
+enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_COMMIT = 2, CLS_OTHER = 3, CLS_N = 4 };
+
+struct ProfRec {
+    int cls;
+    double flops, bytes;
+};
+
+struct Plan {  // byte offsets into the workspace
+    size_t x, xn, qkv, att, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
+        pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, total;
+    size_t attn_ws_bytes;
+    int max_rows, pool_cap, feat_rows;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_ctx, Plan& p) {
+    if (B < 1 || n < 1 || n > TLT_MAX_TREE || D < 0 || D > TLT_MAX_DEPTH || K < 1 || K > TLT_MAX_TOPK || max_ctx < 1)
+        return false;
+    const size_t esz = c.dtype == TLT_F32 ? 4 : 2;
+    const size_t R = (size_t)B * std::max(n, K);
+    const size_t h = c.hidden, F = c.mlp, V = c.vocab;
+    const size_t qkv_dim = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    p.max_rows = (int)R;
+    p.pool_cap = K + std::max(0, D - 1) * K * K;
+    p.feat_rows = 1 + std::max(0, D - 1) * K;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    p.x = take(R * h * 4);
+    p.xn = take(R * 2 * h * esz);
+    p.qkv = take(R * qkv_dim * esz);
+    p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
+    p.g = take(R * F * esz);
+    p.u = take(R * F * esz);
+    p.act = take(R * F * esz);
+    p.logits = take(R * V * 4);
+    p.argmax = take(R * 4);
+    p.feat = take((size_t)B * p.feat_rows * h * 4);
+    p.top_tok = take((size_t)B * K * K * 4);
+    p.top_logp = take((size_t)B * K * K * 4);
+    p.pool_token = take((size_t)B * p.pool_cap * 4);
+    p.pool_score = take((size_t)B * p.pool_cap * 4);
+    p.pool_parent = take((size_t)B * p.pool_cap * 4);
+    p.pool_depth = take((size_t)B * p.pool_cap * 4);
+    p.pool_mask = take((size_t)B * p.pool_cap * 16);
+    p.fr_token = take((size_t)B * K * 4);
+    p.fr_src = take((size_t)B * K * 4);
+    p.fr_pool = take((size_t)B * K * 4);
+    p.fr_mask = take((size_t)B * K * 16);
+    p.row_map = take((size_t)B * 4);
+    p.attn_ws_bytes = attention_workspace_bytes(B, std::max(n, K), c.n_q_heads, c.n_kv_heads, c.head_dim, max_ctx);
+    p.attn_ws = take(p.attn_ws_bytes);
+    p.accept_ws = take(accept_sample_workspace_bytes(B, c.vocab));
+    p.total = o;
+    return true;
+}
+
+bool cfg_ok(const tlt_model_cfg* c) {
+    if (!c) return false;
+    if (c->n_layers < 1 || c->hidden < 4 || c->hidden % 4 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
+        c->n_q_heads % c->n_kv_heads || c->head_dim < 64 || c->head_dim % 64 || c->head_dim > 256 || c->mlp < 1 ||
+        c->vocab < 1 || c->page_size < 1 || !(c->rms_eps > 0.f) || !(c->rope_theta > 0.f))
+        return false;
+    if (c->dtype != TLT_F32 && c->dtype != TLT_BF16) return false;
+    // 16-byte row chunks in the cache and the activations
+    const int esz = c->dtype == TLT_F32 ? 4 : 2;
+    if ((c->head_dim * esz) % 16) return false;
+    return true;
+}
+
+}  // namespace
+
+struct tlt_ctx {
+    tlt_model_cfg cfg;
+    tlt_weights target, draft;
+    std::vector<tlt_layer_weights> target_layers, draft_layers;
+    bool have_draft = false;
+    int max_batch, max_n, max_depth, max_topk, max_ctx;
+    char* ws = nullptr;
+    Plan plan;
+    int hip_error = 0;
+    int attn_impl = -1;  // -1: pick by dtype/shape
+    // profiling
+    bool prof_on = false;
+    std::vector<hipEvent_t> events;
+    std::vector<ProfRec> recs;
+};
+
+namespace {
+
+int fail(tlt_ctx* ctx, hipError_t e) {
+    if (ctx) ctx->hip_error = (int)e;
+    return TLT_EHIP;
+}
+
+struct Scope {  // brackets one launch with events when profiling is on
+    tlt_ctx* ctx;
+    hipStream_t s;
+    bool on;
+    Scope(tlt_ctx* c, hipStream_t st, int cls, double flops, double bytes) : ctx(c), s(st), on(c && c->prof_on) {
+        if (!on) return;
+        size_t need = (ctx->recs.size() + 1) * 2;
+        while (ctx->events.size() < need) {
+            hipEvent_t ev;
+            if (hipEventCreate(&ev) != hipSuccess) {
+                on = false;
+                return;
+            }
+            ctx->events.push_back(ev);
+        }
+        ctx->recs.push_back({cls, flops, bytes});
+        (void)hipEventRecord(ctx->events[need - 2], s);
+    }
+    ~Scope() {
+        if (on) (void)hipEventRecord(ctx->events[ctx->recs.size() * 2 - 1], s);
+    }
+};
+
+#define TLT_RUN(ctx, s, cls, flops, bytes, expr)          \
+    do {                                                  \
+        hipError_t e__;                                   \
+        {                                                 \
+            Scope sc__(ctx, s, cls, flops, bytes);        \
+            e__ = (expr);                                 \
+        }                                                 \
+        if (e__ != hipSuccess) return fail(ctx, e__);     \
+    } while (0)
+
+size_t esz_of(const tlt_ctx* c) { return c->cfg.dtype == TLT_F32 ? 4 : 2; }
+
+int run_gemm(tlt_ctx* ctx, hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
+    const double e = (double)esz_of(ctx);
+    const double out_b = out_mode == OUT_T ? e : (out_mode == OUT_F32 ? 4.0 : 8.0);
+    TLT_RUN(ctx, s, CLS_GEMM, 2.0 * M * N * K, ((double)M * K + (double)N * K) * e + (double)M * N * out_b,
+            gemm(s, ctx->cfg.dtype, out_mode, M, N, K, A, W, C));
+    return TLT_OK;
+}
+
+KVLayer kv_layer(const tlt_ctx* ctx, const tlt_kv* kv, int layer) {
+    const tlt_model_cfg& c = ctx->cfg;
+    KVLayer k;
+    const size_t per_layer = (size_t)kv->n_pages * c.n_kv_heads * c.page_size * c.head_dim * esz_of(ctx);
+    k.k = (char*)kv->k_pool + per_layer * layer;
+    k.v = (char*)kv->v_pool + per_layer * layer;
+    k.n_pages = kv->n_pages;
+    k.block_table = kv->block_table;
+    k.seq_len = kv->seq_len;
+    k.max_pages = kv->max_pages;
+    k.page_size = c.page_size;
+    k.n_kv = c.n_kv_heads;
+    k.d = c.head_dim;
+    k.seq_len_bound = kv->seq_len_bound;
+    return k;
+}
+
+// One decoder block over M = rows.B * rows.n rows whose residual stream sits in the workspace's x.
+int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const Rows& rows, const KVLayer& kv) {
+    const tlt_model_cfg& c = ctx->cfg;
+    const Plan& p = ctx->plan;
+    char* ws = ctx->ws;
+    const int M = rows.B * rows.n, h = c.hidden, F = c.mlp, dt = c.dtype;
+    const int q_dim = c.n_q_heads * c.head_dim, qkv_dim = q_dim + 2 * c.n_kv_heads * c.head_dim;
+    const double e = (double)esz_of(ctx);
+    float* x = (float*)(ws + p.x);
+    int rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr));
+    if ((rc = run_gemm(ctx, s, OUT_T, M, qkv_dim, h, ws + p.xn, w.wqkv, ws + p.qkv))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2, rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta));
+    {
+        // algorithmic traffic: one pass over the cached K and V of every sequence (bounded by the
+        // host-known length) plus q in / out; flops: 4 * d per (query row, head, key)
+        const double keys = (double)rows.B * ((double)kv.seq_len_bound + rows.n_region);
+        const double bytes = keys * 2.0 * c.n_kv_heads * c.head_dim * e + 2.0 * M * q_dim * e;
+        const double flops = 4.0 * c.head_dim * c.n_q_heads * (double)rows.n * keys;
+        TLT_RUN(ctx, s, CLS_ATTN, flops, bytes,
+                attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl));
+    }
+    if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
+    if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wg, ws + p.g))) return rc;
+    if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wu, ws + p.u))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * F * e * 3, swiglu(s, dt, (int64_t)M * F, ws + p.g, ws + p.u, ws + p.act));
+    if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, F, ws + p.act, w.wd, x))) return rc;
+    return TLT_OK;
+}
+
+int check_kv(const tlt_ctx* ctx, const tlt_kv* kv, int new_rows) {
+    if (!kv || !kv->k_pool || !kv->v_pool || !kv->block_table || !kv->seq_len || kv->n_pages < 1 || kv->max_pages < 1 ||
+        kv->seq_len_bound < 0)
+        return TLT_EINVAL;
+    if ((int64_t)kv->seq_len_bound + new_rows > (int64_t)kv->max_pages * ctx->cfg.page_size) return TLT_ENOPAGES;
+    if (kv->seq_len_bound + new_rows > ctx->max_ctx) return TLT_ESHAPE;
+    return TLT_OK;
+}
+
+bool tree_ok(const tlt_tree* t) { return t && t->token && t->parent && t->depth && t->anc_mask && t->n >= 1 && t->n <= TLT_MAX_TREE; }
+
+}  // namespace
+
+extern "C" {
+
+const char* tlt_strerror(int code) {
+    switch (code) {
+        case TLT_OK: return "ok";
+        case TLT_EINVAL: return "invalid argument";
+        case TLT_ESHAPE: return "size exceeds the limits given to tlt_create (or workspace too small)";
+        case TLT_ENOPAGES: return "block table too short for seq_len_bound + new rows";
+        case TLT_EHIP: return "HIP call failed";
+        case TLT_ENOTIMPL: return "not implemented";
+        default: return "unknown error";
+    }
+}
+
+int tlt_last_hip_error(const tlt_ctx* ctx) { return ctx ? ctx->hip_error : 0; }
+
+size_t tlt_workspace_bytes(const tlt_model_cfg* cfg, int max_batch, int max_n, int max_depth, int max_topk, int max_ctx) {
+    Plan p;
+    if (!cfg_ok(cfg) || !plan_workspace(*cfg, max_batch, max_n, max_depth, max_topk, max_ctx, p)) return 0;
+    return p.total;
+}
+
+int tlt_create(tlt_ctx** out, const tlt_model_cfg* cfg, const tlt_weights* target, const tlt_weights* draft, int max_batch,
+               int max_n, int max_depth, int max_topk, int max_ctx, void* workspace, size_t workspace_bytes) {
+    if (!out || !cfg_ok(cfg) || !target || !target->embed || !target->lm_head || !target->final_norm || !target->layers ||
+        !workspace)
+        return TLT_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return TLT_EINVAL;
+    Plan p;
+    if (!plan_workspace(*cfg, max_batch, max_n, max_depth, max_topk, max_ctx, p)) return TLT_EINVAL;
+    if (workspace_bytes < p.total) return TLT_ESHAPE;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const tlt_layer_weights& w = target->layers[l];
+        if (!w.attn_norm || !w.wqkv || !w.wo || !w.mlp_norm || !w.wg || !w.wu || !w.wd) return TLT_EINVAL;
+    }
+    if (draft) {
+        if (!draft->fc || !draft->layers) return TLT_EINVAL;
+        const tlt_layer_weights& w = draft->layers[0];
+        if (!w.attn_norm || !w.wqkv || !w.wo || !w.mlp_norm || !w.wg || !w.wu || !w.wd) return TLT_EINVAL;
+    }
+    tlt_ctx* c = new (std::nothrow) tlt_ctx();
+    if (!c) return TLT_EINVAL;
+    c->cfg = *cfg;
+    c->target = *target;
+    c->target_layers.assign(target->layers, target->layers + cfg->n_layers);
+    c->target.layers = c->target_layers.data();
+    if (draft) {
+        c->have_draft = true;
+        c->draft = *draft;
+        c->draft_layers.assign(draft->layers, draft->layers + 1);
+        c->draft.layers = c->draft_layers.data();
+    }
+    c->max_batch = max_batch;
+    c->max_n = max_n;
+    c->max_depth = max_depth;
+    c->max_topk = max_topk;
+    c->max_ctx = max_ctx;
+    c->ws = (char*)workspace;
+    c->plan = p;
+    *out = c;
+    return TLT_OK;
+}
+
+int tlt_destroy(tlt_ctx* ctx) {
+    if (!ctx) return TLT_EINVAL;
+    for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+    delete ctx;
+    return TLT_OK;
+}
+
+int tlt_set_attention_impl(tlt_ctx* ctx, int impl) {
+    if (!ctx) return TLT_EINVAL;
+    ctx->attn_impl = impl;
+    return TLT_OK;
+}
+
+int tlt_tree_finalize(tlt_ctx* ctx, void* stream, int B, tlt_tree* tree) {
+    if (!ctx || !tree_ok(tree) || B < 1) return TLT_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, tree_finalize(s, B, tree->n, tree->parent, tree->depth, tree->anc_mask));
+    return TLT_OK;
+}
+
+int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, tlt_kv* kv, float* out_logits,
+                       int32_t* out_argmax, float* out_hidden) {
+    if (!ctx || !tree_ok(tree) || B < 1) return TLT_EINVAL;
+    if (B > ctx->max_batch || tree->n > ctx->max_n) return TLT_ESHAPE;
+    int rc = check_kv(ctx, kv, tree->n);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const tlt_model_cfg& c = ctx->cfg;
+    const Plan& p = ctx->plan;
+    char* ws = ctx->ws;
+    const int n = tree->n, M = B * n, h = c.hidden, V = c.vocab;
+    const double e = (double)esz_of(ctx);
+    float* x = (float*)(ws + p.x);
+
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (e + 4), embed_rows(s, c.dtype, M, h, V, tree->token, ctx->target.embed, x));
+    Rows rows;
+    rows.B = B;
+    rows.n = n;
+    rows.pos_off = tree->depth;
+    rows.mask = tree->anc_mask;
+    rows.mask_words = 1;
+    rows.n_region = n;
+    for (int l = 0; l < c.n_layers; ++l) {
+        rc = layer_forward(ctx, s, ctx->target.layers[l], rows, kv_layer(ctx, kv, l));
+        if (rc) return rc;
+    }
+    if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));
+    if (out_logits || out_argmax) {
+        float* logits = out_logits ? out_logits : (float*)(ws + p.logits);
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
+                rmsnorm(s, c.dtype, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+        if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
+    }
+    return TLT_OK;
+}
+
+int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int n_verify, int mode,
+                     const int32_t* new_tokens, const int32_t* new_src, const int32_t* n_new, int new_stride,
+                     const float* hidden, int hidden_n, const int32_t* root_tokens, tlt_kv* draft_kv, tlt_tree* out_tree) {
+    if (!ctx || !ctx->have_draft || B < 1 || depth < 0 || new_stride < 0) return TLT_EINVAL;
+    if (mode != 0) return TLT_ENOTIMPL;
+    const bool do_extend = new_stride > 0;
+    const bool do_expand = depth >= 1 && out_tree != nullptr;
+    if (do_extend && (!new_tokens || !new_src || !n_new || !hidden || hidden_n < 1)) return TLT_EINVAL;
+    if (do_expand && (!tree_ok(out_tree) || !out_tree->score || (!root_tokens && !do_extend) || topk < 1 || n_verify < 1))
+        return TLT_EINVAL;
+    if (B > ctx->max_batch || new_stride > std::max(ctx->max_n, ctx->max_topk)) return TLT_ESHAPE;
+    if (do_expand && (depth > ctx->max_depth || topk > ctx->max_topk || n_verify > ctx->max_n)) return TLT_ESHAPE;
+    const int pool_n = do_expand ? topk + (depth - 1) * topk * topk : 0;
+    if (do_expand && out_tree->n != std::min(n_verify, 1 + pool_n)) return TLT_EINVAL;
+    const int prov_rows = do_expand ? (depth - 1) * topk : 0;
+    int rc = check_kv(ctx, draft_kv, new_stride + prov_rows);
+    if (rc) return rc;
+
+    hipStream_t s = (hipStream_t)stream;
+    const tlt_model_cfg& c = ctx->cfg;
+    const Plan& p = ctx->plan;
+    char* ws = ctx->ws;
+    const int h = c.hidden, V = c.vocab, dt = c.dtype;
+    const double e = (double)esz_of(ctx);
+    float* x = (float*)(ws + p.x);
+    float* feat = (float*)(ws + p.feat);
+    float* logits = (float*)(ws + p.logits);
+    int32_t* top_tok = (int32_t*)(ws + p.top_tok);
+    float* top_logp = (float*)(ws + p.top_logp);
+    int32_t* row_map = (int32_t*)(ws + p.row_map);
+    const int FR = p.feat_rows;
+    const tlt_layer_weights& lw = ctx->draft.layers[0];
+    KVLayer kvl = kv_layer(ctx, draft_kv, 0);
+
+    if (do_extend) {
+        const int M = B * new_stride;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
+                draft_input(s, dt, B, new_stride, h, V, new_tokens, new_src, n_new, hidden_n, (int64_t)B * hidden_n, hidden,
+                            ctx->target.embed, ws + p.xn));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+        Rows rows;
+        rows.B = B;
+        rows.n = new_stride;
+        rows.n_valid = n_new;
+        rows.pos_stride = 1;
+        rows.n_region = new_stride;
+        if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * 8, gather_last_rows(s, B, new_stride, h, n_new, x, feat, FR));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0, add_i32(s, B, draft_kv->seq_len, n_new, 0));
+        kvl.seq_len_bound += new_stride;
+    }
+    if (!do_expand) return TLT_OK;
+
+    DraftState st;
+    st.P = p.pool_cap;
+    st.pool_token = (int32_t*)(ws + p.pool_token);
+    st.pool_score = (float*)(ws + p.pool_score);
+    st.pool_parent = (int32_t*)(ws + p.pool_parent);
+    st.pool_depth = (int32_t*)(ws + p.pool_depth);
+    st.pool_mask = (uint64_t*)(ws + p.pool_mask);
+    st.fr_token = (int32_t*)(ws + p.fr_token);
+    st.fr_src = (int32_t*)(ws + p.fr_src);
+    st.fr_pool = (int32_t*)(ws + p.fr_pool);
+    st.fr_mask = (uint64_t*)(ws + p.fr_mask);
+
+    // root distribution: feature row 0 of every sequence -> final norm -> LM head -> top-k
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, iota_scaled(s, B, row_map, FR));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * (4 + e),
+            rmsnorm(s, dt, B, h, feat, ctx->target.final_norm, c.rms_eps, ws + p.xn, row_map));
+    if ((rc = run_gemm(ctx, s, OUT_F32, B, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * V * 4, row_topk_logp(s, B, V, topk, logits, top_tok, top_logp));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, draft_level0(s, B, topk, top_tok, top_logp, st, FR));
+
+    for (int level = 1; level < depth; ++level) {
+        const int M = B * topk;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
+                draft_input(s, dt, B, topk, h, V, st.fr_token, st.fr_src, nullptr, FR, (int64_t)B * FR, feat,
+                            ctx->target.embed, ws + p.xn));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+        Rows rows;
+        rows.B = B;
+        rows.n = topk;
+        rows.pos_base = level - 1;
+        rows.pos_stride = 0;
+        rows.slot_base = (level - 1) * topk;
+        rows.mask = st.fr_mask;
+        rows.mask_words = 2;
+        rows.n_region = level * topk;
+        if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, scatter_rows(s, M, topk, h, x, feat, FR, 1 + (level - 1) * topk));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
+                rmsnorm(s, dt, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_topk_logp(s, M, V, topk, logits, top_tok, top_logp));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0, draft_level_select(s, B, topk, level, top_tok, top_logp, st, FR));
+    }
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
+            draft_prune(s, B, pool_n, out_tree->n, root_tokens, new_tokens, n_new, new_stride, st, out_tree->token, out_tree->parent, out_tree->depth,
+                        out_tree->anc_mask, out_tree->score));
+    return TLT_OK;
+}
+
+int tlt_accept(tlt_ctx* ctx, void* stream, int B, int mode, float temperature, const tlt_tree* tree,
+               const float* target_logits, const int32_t* target_argmax, const float* draft_q, const uint32_t* u_accept,
+               const uint32_t* u_final, int stride, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
+               int32_t* n_out) {
+    if (!ctx || B < 1 || !tree || !tree->token || !tree->parent || tree->n < 1 || tree->n > TLT_MAX_TREE || stride < 1 ||
+        !accept_len || !path_idx || !out_tokens || !n_out)
+        return TLT_EINVAL;
+    if (B > ctx->max_batch || tree->n > ctx->max_n) return TLT_ESHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    const int n = tree->n, V = ctx->cfg.vocab;
+    if (mode == 0) {
+        if (!target_argmax && !target_logits) return TLT_EINVAL;
+        const int32_t* am = target_argmax;
+        if (!am) {
+            int32_t* tmp = (int32_t*)(ctx->ws + ctx->plan.argmax);
+            TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * n * V * 4, row_argmax(s, B * n, V, target_logits, tmp));
+            am = tmp;
+        }
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
+                accept_greedy(s, B, n, V, stride, tree->token, tree->parent, target_logits, am, accept_len, path_idx,
+                              out_tokens, n_out));
+        return TLT_OK;
+    }
+    if (mode == 1) {
+        if (!target_logits || !draft_q || !u_accept || !u_final || !(temperature > 0.f)) return TLT_EINVAL;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
+                accept_sample(s, B, n, V, stride, temperature, tree->token, tree->parent, target_logits, draft_q, u_accept,
+                              u_final, accept_len, path_idx, out_tokens, n_out, ctx->ws + ctx->plan.accept_ws));
+        return TLT_OK;
+    }
+    return TLT_EINVAL;
+}
+
+int tlt_kv_commit(tlt_ctx* ctx, void* stream, int B, tlt_kv* kv, const int32_t* accept_len, const int32_t* path_idx,
+                  int stride) {
+    if (!ctx || B < 1 || !accept_len || !path_idx || stride < 1) return TLT_EINVAL;
+    if (!kv || !kv->k_pool || !kv->v_pool || !kv->block_table || !kv->seq_len || kv->n_pages < 1 || kv->max_pages < 1)
+        return TLT_EINVAL;
+    if (B > ctx->max_batch) return TLT_ESHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    const tlt_model_cfg& c = ctx->cfg;
+    // algorithmic bytes are data dependent (accept lengths live on the device): callers that want
+    // a bandwidth figure compute 2 * sum(accept_len) * kv_bytes_per_token themselves
+    TLT_RUN(ctx, s, CLS_COMMIT, 0, 0,
+            kv_commit(s, c.dtype, B, c.n_layers, kv->k_pool, kv->v_pool, kv->n_pages, kv->block_table, kv->seq_len,
+                      kv->max_pages, c.page_size, c.n_kv_heads, c.head_dim, accept_len, path_idx, stride));
+    return TLT_OK;
+}
+
+int tlt_gemm(void* stream, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
+    if (M < 0 || N < 1 || K < 1 || !A || !W || !C || (dtype != TLT_F32 && dtype != TLT_BF16) || out_mode < 0 || out_mode > 2)
+        return TLT_EINVAL;
+    return gemm((hipStream_t)stream, dtype, out_mode, M, N, K, A, W, C) == hipSuccess ? TLT_OK : TLT_EHIP;
+}
+
+int tlt_profile_begin(tlt_ctx* ctx, int enable) {
+    if (!ctx) return TLT_EINVAL;
+    ctx->prof_on = enable != 0;
+    ctx->recs.clear();
+    return TLT_OK;
+}
+
+int tlt_profile_read(tlt_ctx* ctx, double* ms, int64_t* launches, double* flops, double* bytes) {
+    if (!ctx || !ms || !launches || !flops || !bytes) return TLT_EINVAL;
+    for (int i = 0; i < CLS_N; ++i) {
+        ms[i] = 0;
+        launches[i] = 0;
+        flops[i] = 0;
+        bytes[i] = 0;
+    }
+    for (size_t r = 0; r < ctx->recs.size(); ++r) {
+        hipError_t e = hipEventSynchronize(ctx->events[2 * r + 1]);
+        if (e != hipSuccess) return fail(ctx, e);
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, ctx->events[2 * r], ctx->events[2 * r + 1]);
+        if (e != hipSuccess) return fail(ctx, e);
+        const ProfRec& rec = ctx->recs[r];
+        ms[rec.cls] += t;
+        launches[rec.cls] += 1;
+        flops[rec.cls] += rec.flops;
+        bytes[rec.cls] += rec.bytes;
+    }
+    ctx->recs.clear();
+    return TLT_OK;
+}
+
+}  // extern "C"

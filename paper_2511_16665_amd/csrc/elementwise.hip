@@ -1,0 +1,248 @@
+// Row-wise kernels of the decoder block: embedding gather, RMSNorm, rotary embedding fused with the
+// write of new keys/values into the paged cache, SiLU gating, the drafter's input rows.
+// All are HBM-bound streaming kernels: one workgroup per row, 16-byte accesses where the layout allows.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace tlt {
+
+template <typename T>
+__global__ void embed_rows_k(int M, int h, int V, const int32_t* __restrict__ tokens, const T* __restrict__ embed,
+                             float* __restrict__ x) {
+    int r = blockIdx.x;
+    int t = tokens[r];
+    bool ok = t >= 0 && t < V;
+    const T* e = embed + (int64_t)(ok ? t : 0) * h;
+    for (int c = threadIdx.x; c < h; c += blockDim.x) x[(int64_t)r * h + c] = ok ? to_float(e[c]) : 0.f;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_k(int h, const float* __restrict__ x, const T* __restrict__ gamma,
+                                                 float eps, T* __restrict__ out, const int32_t* __restrict__ row_map) {
+    __shared__ float red[4];
+    int r = blockIdx.x;
+    int64_t src = row_map ? row_map[r] : r;
+    T* o = out + (int64_t)r * h;
+    if (src < 0) {
+        for (int c = threadIdx.x; c < h; c += 256) o[c] = from_float<T>(0.f);
+        return;
+    }
+    const float* xr = x + src * h;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < h; c += 256) {
+        float v = xr[c];
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = red[0] + red[1] + red[2] + red[3];
+    float inv = 1.0f / sqrtf(tot / (float)h + eps);
+    for (int c = threadIdx.x; c < h; c += 256) o[c] = from_float<T>(xr[c] * inv * to_float(gamma[c]));
+}
+
+// One workgroup per row.  Angles are formed in double (positions reach 32K, where an fp32 product
+// pos * inv_freq already carries ~1e-3 rad of rounding), once per (row, pair index), then reused by
+// every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T* __restrict__ qkv, int n_q_heads,
+                                                       float theta) {
+    extern __shared__ float cs[];  // [d/2] cos, [d/2] sin
+    const int d = kv.d, half = d >> 1;
+    int r = blockIdx.x;
+    int b = r / rows.n, i = r - b * rows.n;
+    if (rows.n_valid && i >= rows.n_valid[b]) return;
+    int ctx = kv.seq_len[b];
+    int pos = ctx + rows.pos_base + (rows.pos_off ? rows.pos_off[r] : rows.pos_stride * i);
+    int slot = ctx + rows.slot_base + i;
+    for (int j = threadIdx.x; j < half; j += 256) {
+        double inv_freq = pow((double)theta, -2.0 * (double)j / (double)d);
+        double sn, c;
+        sincos((double)pos * inv_freq, &sn, &c);
+        cs[j] = (float)c;
+        cs[half + j] = (float)sn;
+    }
+    __syncthreads();
+    const int qkv_dim = (n_q_heads + 2 * kv.n_kv) * d;
+    T* row = qkv + (int64_t)r * qkv_dim;
+    PageRef pr;
+    bool have = locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, slot, pr);
+    T* kc = (T*)kv.k;
+    T* vc = (T*)kv.v;
+    const int n_rot = (n_q_heads + kv.n_kv) * half;
+    for (int e = threadIdx.x; e < n_rot; e += 256) {
+        int hd = e / half, j = e - hd * half;
+        T* p = row + (int64_t)hd * d;
+        float x1 = to_float(p[j]), x2 = to_float(p[j + half]);
+        float c = cs[j], sn = cs[half + j];
+        T y1 = from_float<T>(x1 * c - x2 * sn), y2 = from_float<T>(x2 * c + x1 * sn);
+        if (hd < n_q_heads) {
+            p[j] = y1;
+            p[j + half] = y2;
+        } else if (have) {
+            int kh = hd - n_q_heads;
+            int64_t o = ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d;
+            kc[o + j] = y1;
+            kc[o + j + half] = y2;
+        }
+    }
+    if (have) {
+        const T* vsrc = row + (int64_t)(n_q_heads + kv.n_kv) * d;
+        for (int e = threadIdx.x; e < kv.n_kv * d; e += 256) {
+            int kh = e / d, j = e - kh * d;
+            vc[((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d + j] = vsrc[e];
+        }
+    }
+}
+
+template <typename T>
+__global__ void swiglu_k(int64_t count, const T* __restrict__ g, const T* __restrict__ u, T* __restrict__ out) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) {
+        float a = to_float(g[i]);
+        out[i] = from_float<T>(a / (1.0f + expf(-a)) * to_float(u[i]));
+    }
+}
+
+template <typename T>
+__global__ void draft_input_k(int n, int h, int V, const int32_t* __restrict__ tok, const int32_t* __restrict__ src,
+                              const int32_t* __restrict__ n_valid, int src_seq_stride, int64_t hidden_rows,
+                              const float* __restrict__ hidden, const T* __restrict__ embed, T* __restrict__ xin) {
+    int r = blockIdx.x;
+    int b = r / n, i = r - b * n;
+    int t = tok[r];
+    int64_t sr = src[r];
+    bool ok = t >= 0 && t < V && sr >= 0 && (!n_valid || i < n_valid[b]);
+    if (ok && src_seq_stride > 0) {
+        ok = sr < src_seq_stride;
+        sr += (int64_t)b * src_seq_stride;
+    }
+    ok = ok && sr < hidden_rows;
+    T* o = xin + (int64_t)r * 2 * h;
+    for (int c = threadIdx.x; c < h; c += blockDim.x) {
+        o[c] = ok ? embed[(int64_t)t * h + c] : from_float<T>(0.f);
+        o[h + c] = ok ? from_float<T>(hidden[sr * h + c]) : from_float<T>(0.f);
+    }
+}
+
+__global__ void add_i32_k(int n, int32_t* dst, const int32_t* a, int add_const) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] += (a ? a[i] : 0) + add_const;
+}
+
+__global__ void copy_f32_k(int64_t count, const float4* __restrict__ src, float4* __restrict__ dst) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) dst[i] = src[i];
+}
+
+// dst row (r / n) * dst_seq_stride + dst_base + r % n  <-  src row r   (h floats, h % 4 == 0)
+__global__ void scatter_rows_k(int n, int h4, const float4* __restrict__ src, float4* __restrict__ dst, int dst_seq_stride,
+                               int dst_base) {
+    int r = blockIdx.x;
+    int64_t d = (int64_t)(r / n) * dst_seq_stride + dst_base + (r % n);
+    for (int c = threadIdx.x; c < h4; c += blockDim.x) dst[d * h4 + c] = src[(int64_t)r * h4 + c];
+}
+
+// Per sequence: last active row of x [B][n][h] -> dst row b * dst_seq_stride; nothing when n_valid[b] <= 0.
+__global__ void gather_last_rows_k(int n, int h4, const int32_t* __restrict__ n_valid, const float4* __restrict__ src,
+                                   float4* __restrict__ dst, int dst_seq_stride) {
+    int b = blockIdx.x;
+    int nv = n_valid ? n_valid[b] : n;
+    if (nv > n) nv = n;
+    if (nv <= 0) return;
+    int64_t sr = (int64_t)b * n + nv - 1, d = (int64_t)b * dst_seq_stride;
+    for (int c = threadIdx.x; c < h4; c += blockDim.x) dst[d * h4 + c] = src[sr * h4 + c];
+}
+
+__global__ void iota_scaled_k(int n, int32_t* out, int scale) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = i * scale;
+}
+
+#define DISPATCH_T(dtype, ...)              \
+    if ((dtype) == F32) {                   \
+        using T = float;                    \
+        __VA_ARGS__;                        \
+    } else {                                \
+        using T = bf16;                     \
+        __VA_ARGS__;                        \
+    }
+
+hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x) {
+    if (M <= 0) return hipSuccess;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(embed_rows_k<T>, dim3(M), dim3(256), 0, s, M, h, V, tokens, (const T*)embed, x));
+    return hipGetLastError();
+}
+
+hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
+                   const int32_t* row_map) {
+    if (M <= 0) return hipSuccess;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+    return hipGetLastError();
+}
+
+hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
+                         float theta) {
+    int M = rows.B * rows.n;
+    if (M <= 0) return hipSuccess;
+    size_t lds = sizeof(float) * kv.d;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta));
+    return hipGetLastError();
+}
+
+hipError_t swiglu(hipStream_t s, int dtype, int64_t count, const void* g, const void* u, void* out) {
+    if (count <= 0) return hipSuccess;
+    int blocks = (int)((count + 255) / 256);
+    if (blocks > 16384) blocks = 16384;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(swiglu_k<T>, dim3(blocks), dim3(256), 0, s, count, (const T*)g, (const T*)u, (T*)out));
+    return hipGetLastError();
+}
+
+hipError_t draft_input(hipStream_t s, int dtype, int B, int n, int h, int V, const int32_t* tok, const int32_t* src,
+                       const int32_t* n_valid, int src_seq_stride, int64_t hidden_rows, const float* hidden,
+                       const void* embed, void* xin) {
+    if (B * n <= 0) return hipSuccess;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(draft_input_k<T>, dim3(B * n), dim3(256), 0, s, n, h, V, tok, src, n_valid,
+                                         src_seq_stride, hidden_rows, hidden, (const T*)embed, (T*)xin));
+    return hipGetLastError();
+}
+
+hipError_t add_i32(hipStream_t s, int n, int32_t* dst, const int32_t* a, int add_const) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(add_i32_k, dim3((n + 255) / 256), dim3(256), 0, s, n, dst, a, add_const);
+    return hipGetLastError();
+}
+
+hipError_t copy_f32(hipStream_t s, int64_t count, const float* src, float* dst) {
+    if (count <= 0) return hipSuccess;
+    int64_t c4 = count / 4;  // callers pass multiples of 4 floats (hidden sizes are)
+    int blocks = (int)((c4 + 255) / 256);
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(copy_f32_k, dim3(blocks), dim3(256), 0, s, c4, (const float4*)src, (float4*)dst);
+    return hipGetLastError();
+}
+
+hipError_t scatter_rows(hipStream_t s, int R, int n, int h, const float* src, float* dst, int dst_seq_stride, int dst_base) {
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_rows_k, dim3(R), dim3(256), 0, s, n, h / 4, (const float4*)src, (float4*)dst, dst_seq_stride,
+                       dst_base);
+    return hipGetLastError();
+}
+
+hipError_t gather_last_rows(hipStream_t s, int B, int n, int h, const int32_t* n_valid, const float* src, float* dst,
+                            int dst_seq_stride) {
+    if (B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_last_rows_k, dim3(B), dim3(256), 0, s, n, h / 4, n_valid, (const float4*)src, (float4*)dst,
+                       dst_seq_stride);
+    return hipGetLastError();
+}
+
+hipError_t iota_scaled(hipStream_t s, int n, int32_t* out, int scale) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(iota_scaled_k, dim3((n + 255) / 256), dim3(256), 0, s, n, out, scale);
+    return hipGetLastError();
+}
+
+}  // namespace tlt

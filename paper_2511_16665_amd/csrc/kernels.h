@@ -1,0 +1,106 @@
+// Host-side launchers of the HIP kernels behind libtlt's C ABI.  Internal header.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tlt {
+
+enum { F32 = 0, BF16 = 1 };
+enum { OUT_T = 0, OUT_F32 = 1, OUT_ADD_F32 = 2 };
+
+// Rows of a layer forward, laid out [B][n].  Row (b, i) is active when i < n_valid[b] (all rows
+// when n_valid is null).  Its rotary position is seq_len[b] + pos_base + (pos_off ? pos_off[b*n+i]
+// : pos_stride*i); its key/value go to cache slot seq_len[b] + slot_base + i.  It attends to every
+// slot < seq_len[b] and to region slot seq_len[b] + j (j < n_region) when bit j of its mask is set;
+// a null mask means causal within the rows (bit j set for j <= i, with slot_base = 0).
+struct Rows {
+    int B = 0, n = 0;
+    const int32_t* n_valid = nullptr;
+    const int32_t* pos_off = nullptr;
+    int pos_base = 0, pos_stride = 0;
+    int slot_base = 0;
+    const uint64_t* mask = nullptr;
+    int mask_words = 1;
+    int n_region = 0;
+};
+
+struct KVLayer {
+    void* k = nullptr;  // this layer's [n_pages][n_kv][page][d]
+    void* v = nullptr;
+    int64_t n_pages = 0;
+    const int32_t* block_table = nullptr;
+    const int32_t* seq_len = nullptr;
+    int max_pages = 0, page_size = 16, n_kv = 0, d = 0;
+    int seq_len_bound = 0;
+};
+
+// ---- gemm.hip
+hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C);
+
+// ---- elementwise.hip
+hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x);
+// out[r] = rmsnorm(x[row_map ? row_map[r] : r]) * gamma, stored in dtype.  Rows with row_map < 0 give zeros.
+hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
+                   const int32_t* row_map);
+hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
+                         float theta);
+hipError_t swiglu(hipStream_t s, int dtype, int64_t count, const void* g, const void* u, void* out);
+// Rows [B][n]: xin[r] = [embed[tok[r]] ; hidden[src row]] in dtype (2h wide).  The hidden row is
+// b*src_seq_stride + src[r] when src_seq_stride > 0, else src[r].  Rows with tok < 0, src < 0,
+// i >= n_valid[b] or an out-of-range source give zeros.
+hipError_t draft_input(hipStream_t s, int dtype, int B, int n, int h, int V, const int32_t* tok, const int32_t* src,
+                       const int32_t* n_valid, int src_seq_stride, int64_t hidden_rows, const float* hidden,
+                       const void* embed, void* xin);
+hipError_t add_i32(hipStream_t s, int n, int32_t* dst, const int32_t* a, int add_const);
+hipError_t copy_f32(hipStream_t s, int64_t count, const float* src, float* dst);
+hipError_t scatter_rows(hipStream_t s, int R, int n, int h, const float* src, float* dst, int dst_seq_stride, int dst_base);
+hipError_t gather_last_rows(hipStream_t s, int B, int n, int h, const int32_t* n_valid, const float* src, float* dst,
+                            int dst_seq_stride);
+hipError_t iota_scaled(hipStream_t s, int n, int32_t* out, int scale);
+
+// ---- attn.hip
+size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx);
+hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
+                     int n_q_heads, void* ws, size_t ws_bytes, int impl);
+
+// ---- sample.hip
+hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
+// per row: log-softmax statistics and the K best (token, log-prob) pairs, best first.
+hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp);
+
+struct DraftState {  // device arrays owned by the workspace; P = pool capacity per sequence
+    int P = 0;
+    int32_t* pool_token = nullptr;   // [B][P]
+    float* pool_score = nullptr;     // [B][P]
+    int32_t* pool_parent = nullptr;  // [B][P] pool index or -1
+    int32_t* pool_depth = nullptr;   // [B][P]
+    int32_t* fr_token = nullptr;     // [B][K] frontier of the level about to run
+    int32_t* fr_src = nullptr;       // [B][K] row of the feature buffer holding the parent's output
+    int32_t* fr_pool = nullptr;      // [B][K] pool index of each frontier node
+    uint64_t* fr_mask = nullptr;     // [B][K][2] visibility over provisional drafter rows
+    uint64_t* pool_mask = nullptr;   // [B][P][2] mask of expanded candidates (valid for frontier members)
+};
+// level 0: root candidates -> pool[0..K) and first frontier (all of them, in rank order).
+hipError_t draft_level0(hipStream_t s, int B, int K, const int32_t* top_tok, const float* top_logp, DraftState st,
+                        int feat_rows_per_seq);
+// level >= 1: K*K children of the frontier -> pool, next frontier = K best by path score.
+hipError_t draft_level_select(hipStream_t s, int B, int K, int level, const int32_t* top_tok, const float* top_logp,
+                              DraftState st, int feat_rows_per_seq);
+hipError_t draft_prune(hipStream_t s, int B, int pool_n, int n_tree, const int32_t* root_tokens,
+                       const int32_t* new_tokens, const int32_t* n_new, int new_stride, DraftState st, int32_t* token, int32_t* parent, int32_t* depth, uint64_t* anc_mask, float* score);
+hipError_t tree_finalize(hipStream_t s, int B, int n, const int32_t* parent, int32_t* depth, uint64_t* anc_mask);
+
+hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const int32_t* token, const int32_t* parent,
+                         const float* logits, const int32_t* argmax, int32_t* accept_len, int32_t* path_idx,
+                         int32_t* out_tokens, int32_t* n_out);
+size_t accept_sample_workspace_bytes(int B, int V);
+hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
+                         const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
+                         const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
+                         int32_t* n_out, void* ws);
+hipError_t kv_commit(hipStream_t s, int dtype, int B, int n_layers, void* k_pool, void* v_pool, int64_t n_pages,
+                     const int32_t* block_table, int32_t* seq_len, int max_pages, int page_size, int n_kv, int d,
+                     const int32_t* accept_len, const int32_t* path_idx, int stride);
+
+}  // namespace tlt

@@ -1,0 +1,597 @@
+// Vocabulary-row reductions (argmax, log-softmax + top-k), the drafter's tree bookkeeping
+// (candidate pool, frontier selection, pruning), the acceptance rules and the KV-cache commit.
+//
+// Ordering rule used wherever a "best" element is picked: larger value first, lower index on ties.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace tlt {
+
+// ------------------------------------------------------------------------------------------------
+// block-wide helpers (256 threads = 4 waves)
+__device__ __forceinline__ void block_best(float& v, int& i, float* sv, int* si) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(v, o, 64);
+        int oi = __shfl_xor(i, o, 64);
+        if (better(ov, oi, v, i)) {
+            v = ov;
+            i = oi;
+        }
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        sv[threadIdx.x >> 6] = v;
+        si[threadIdx.x >> 6] = i;
+    }
+    __syncthreads();
+    v = sv[0];
+    i = si[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+        if (better(sv[w], si[w], v, i)) {
+            v = sv[w];
+            i = si[w];
+        }
+}
+
+__device__ __forceinline__ float block_sum_f(float v, float* sv) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sv[0] + sv[1] + sv[2] + sv[3];
+}
+
+__device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v, unsigned long long* sv) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sv[0] + sv[1] + sv[2] + sv[3];
+}
+
+__device__ __forceinline__ double block_max_d(double v, double* sv) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmax(fmax(sv[0], sv[1]), fmax(sv[2], sv[3]));
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restrict__ logits, int32_t* __restrict__ out) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const float* row = logits + (int64_t)blockIdx.x * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += 256) {
+        float v = row[j];
+        if (better(v, j, bv, bi)) {
+            bv = v;
+            bi = j;
+        }
+    }
+    block_best(bv, bi, sv, si);
+    if (threadIdx.x == 0) out[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
+}
+
+// One workgroup per row: max, log-sum-exp, then K rounds of "best element after the previous
+// winner" in the (value desc, index asc) order.  The row (<= 600 KB) is re-read from L2.
+__global__ __launch_bounds__(256) void row_topk_logp_k(int V, int K, const float* __restrict__ logits,
+                                                       int32_t* __restrict__ tok, float* __restrict__ logp) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const float* row = logits + (int64_t)blockIdx.x * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += 256) {
+        float v = row[j];
+        if (better(v, j, bv, bi)) {
+            bv = v;
+            bi = j;
+        }
+    }
+    block_best(bv, bi, sv, si);
+    const float mx = bv;
+    float se = 0.f;
+    for (int j = threadIdx.x; j < V; j += 256) se += expf(row[j] - mx);
+    se = block_sum_f(se, sv);
+    const float lse = mx + logf(se);
+    float pv = bv;
+    int pi = bi;
+    for (int k = 0; k < K; ++k) {
+        if (k > 0) {
+            float cv = -INFINITY;
+            int ci = 0x7fffffff;
+            for (int j = threadIdx.x; j < V; j += 256) {
+                float v = row[j];
+                bool after = v < pv || (v == pv && j > pi);
+                if (after && better(v, j, cv, ci)) {
+                    cv = v;
+                    ci = j;
+                }
+            }
+            block_best(cv, ci, sv, si);
+            pv = cv;
+            pi = ci;
+        }
+        if (threadIdx.x == 0) {
+            bool have = pi != 0x7fffffff;
+            tok[(int64_t)blockIdx.x * K + k] = have ? pi : -1;
+            logp[(int64_t)blockIdx.x * K + k] = have ? pv - lse : -INFINITY;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Drafter tree bookkeeping.  Feature-buffer rows per sequence: 0 = output of the entry holding the
+// root token; 1 + (level-1)*K + r = output of frontier node r of `level`.  Provisional drafter
+// cache row of that node = (level-1)*K + r past the committed length; masks are over those rows.
+__global__ void draft_level0_k(int B, int K, const int32_t* __restrict__ top_tok, const float* __restrict__ top_logp,
+                               DraftState st) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * K) return;
+    int b = idx / K, r = idx - b * K;
+    int64_t p = (int64_t)b * st.P + r;
+    st.pool_token[p] = top_tok[idx];
+    st.pool_score[p] = top_logp[idx];
+    st.pool_parent[p] = -1;
+    st.pool_depth[p] = 1;
+    uint64_t m0 = r < 64 ? (1ull << r) : 0ull, m1 = r >= 64 ? (1ull << (r - 64)) : 0ull;
+    st.pool_mask[2 * p] = m0;
+    st.pool_mask[2 * p + 1] = m1;
+    st.fr_token[idx] = top_tok[idx];
+    st.fr_src[idx] = 0;
+    st.fr_pool[idx] = r;
+    st.fr_mask[2 * idx] = m0;
+    st.fr_mask[2 * idx + 1] = m1;
+}
+
+__global__ __launch_bounds__(256) void draft_level_select_k(int K, int level, const int32_t* __restrict__ top_tok,
+                                                            const float* __restrict__ top_logp, DraftState st) {
+    __shared__ float sc[256];
+    __shared__ int par_pool[16];
+    __shared__ uint64_t par_mask[16][2];
+    const int b = blockIdx.x, c = threadIdx.x, KK = K * K;
+    if (c < K) {
+        int pp = st.fr_pool[b * K + c];
+        par_pool[c] = pp;
+        par_mask[c][0] = st.pool_mask[2 * ((int64_t)b * st.P + pp)];
+        par_mask[c][1] = st.pool_mask[2 * ((int64_t)b * st.P + pp) + 1];
+    }
+    __syncthreads();
+    float score = -INFINITY;
+    int token = -1, fr = 0;
+    if (c < KK) {
+        fr = c / K;
+        int64_t src = ((int64_t)b * K + fr) * K + (c - fr * K);
+        token = top_tok[src];
+        score = st.pool_score[(int64_t)b * st.P + par_pool[fr]] + top_logp[src];
+        int64_t p = (int64_t)b * st.P + K + (int64_t)(level - 1) * KK + c;
+        st.pool_token[p] = token;
+        st.pool_score[p] = score;
+        st.pool_parent[p] = par_pool[fr];
+        st.pool_depth[p] = level + 1;
+    }
+    sc[c] = score;
+    __syncthreads();
+    if (c < KK) {
+        int rank = 0;
+        for (int j = 0; j < KK; ++j) rank += better(sc[j], j, score, c) ? 1 : 0;
+        if (rank < K) {
+            int slot = level * K + rank;  // provisional row of this node when it runs at level+1
+            uint64_t m0 = par_mask[fr][0] | (slot < 64 ? (1ull << slot) : 0ull);
+            uint64_t m1 = par_mask[fr][1] | (slot >= 64 ? (1ull << (slot - 64)) : 0ull);
+            int pool_idx = K + (level - 1) * KK + c;
+            int64_t p = (int64_t)b * st.P + pool_idx;
+            st.pool_mask[2 * p] = m0;
+            st.pool_mask[2 * p + 1] = m1;
+            int o = b * K + rank;
+            st.fr_token[o] = token;
+            st.fr_src[o] = 1 + (level - 1) * K + fr;
+            st.fr_pool[o] = pool_idx;
+            st.fr_mask[2 * o] = m0;
+            st.fr_mask[2 * o + 1] = m1;
+        }
+    }
+}
+
+// One workgroup per sequence.  LDS: score[P], node_of[P] (node index or -1).
+__global__ __launch_bounds__(256) void draft_prune_k(int pool_n, int n_tree, const int32_t* __restrict__ root_tokens,
+                                                     const int32_t* __restrict__ new_tokens,
+                                                     const int32_t* __restrict__ n_new, int new_stride, DraftState st, int32_t* __restrict__ token,
+                                                     int32_t* __restrict__ parent, int32_t* __restrict__ depth,
+                                                     uint64_t* __restrict__ anc_mask, float* __restrict__ score) {
+    extern __shared__ float lds_f[];
+    float* sc = lds_f;
+    int* node_of = (int*)(lds_f + pool_n);
+    int* tpar = node_of + pool_n;  // [n_tree] parent node of each tree node
+    const int b = blockIdx.x;
+    const int64_t pb = (int64_t)b * st.P;
+    for (int i = threadIdx.x; i < pool_n; i += 256) sc[i] = st.pool_score[pb + i];
+    __syncthreads();
+    const int keep = n_tree - 1;
+    for (int i = threadIdx.x; i < pool_n; i += 256) {
+        float s = sc[i];
+        int rank = 0;
+        for (int j = 0; j < pool_n; ++j) rank += better(sc[j], j, s, i) ? 1 : 0;
+        node_of[i] = rank < keep ? 0 : -1;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < pool_n; i += 256) {
+        if (node_of[i] < 0) continue;
+        int before = 0;
+        for (int j = 0; j < i; ++j) before += node_of[j] >= 0 ? 1 : 0;  // flags are still 0 / -1 here
+        sc[i] = __int_as_float(before + 1);                             // stash; scores are re-read from global
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < pool_n; i += 256)
+        if (node_of[i] >= 0) node_of[i] = __float_as_int(sc[i]);
+    __syncthreads();
+    const int64_t tb = (int64_t)b * n_tree;
+    if (threadIdx.x == 0) {
+        int root = -1;  // explicit root, else the last token handed to the drafter's catch-up
+        if (root_tokens) {
+            root = root_tokens[b];
+        } else if (new_tokens && n_new) {
+            int nv = n_new[b] < new_stride ? n_new[b] : new_stride;
+            if (nv >= 1) root = new_tokens[(int64_t)b * new_stride + nv - 1];
+        }
+        token[tb] = root;
+        parent[tb] = -1;
+        depth[tb] = 0;
+        score[tb] = 0.f;
+        tpar[0] = -1;
+    }
+    for (int i = threadIdx.x; i < pool_n; i += 256) {
+        int nd = node_of[i];
+        if (nd < 0) continue;
+        int pp = st.pool_parent[pb + i];
+        int pn = pp < 0 ? 0 : node_of[pp];
+        token[tb + nd] = st.pool_token[pb + i];
+        parent[tb + nd] = pn;
+        depth[tb + nd] = st.pool_depth[pb + i];
+        score[tb + nd] = st.pool_score[pb + i];
+        tpar[nd] = pn;
+    }
+    __syncthreads();
+    for (int nd = threadIdx.x; nd < n_tree; nd += 256) {
+        uint64_t m = 0;
+        int a = nd, guard = 0;
+        while (a >= 0 && guard++ < 64) {
+            m |= 1ull << a;
+            a = tpar[a];
+        }
+        anc_mask[tb + nd] = m;
+    }
+}
+
+__global__ void tree_finalize_k(int B, int n, const int32_t* __restrict__ parent, int32_t* __restrict__ depth,
+                                uint64_t* __restrict__ anc_mask) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * n) return;
+    int b = idx / n, i = idx - b * n;
+    const int32_t* par = parent + (int64_t)b * n;
+    uint64_t m = 0;
+    int a = i, dep = -1, guard = 0;
+    while (a >= 0 && a < n && guard++ < 64) {
+        m |= 1ull << a;
+        ++dep;
+        int p = par[a];
+        a = p < a ? p : -1;  // parents precede children; anything else ends the walk
+    }
+    depth[idx] = dep;
+    anc_mask[idx] = m;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Acceptance.
+__global__ void accept_greedy_k(int B, int n, int stride, const int32_t* __restrict__ token,
+                                const int32_t* __restrict__ parent, const int32_t* __restrict__ argmax,
+                                int32_t* __restrict__ accept_len, int32_t* __restrict__ path_idx,
+                                int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_out) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int32_t* tok = token + (int64_t)b * n;
+    const int32_t* par = parent + (int64_t)b * n;
+    const int32_t* best = argmax + (int64_t)b * n;
+    int32_t* path = path_idx + (int64_t)b * stride;
+    int32_t* out = out_tokens + (int64_t)b * stride;
+    for (int j = 0; j < stride; ++j) {
+        path[j] = -1;
+        out[j] = -1;
+    }
+    int cur = 0, a = 0;
+    path[0] = 0;
+    for (;;) {
+        int t = best[cur];
+        out[a] = t;
+        int next = -1;
+        for (int c = cur + 1; c < n; ++c)
+            if (par[c] == cur && tok[c] == t) {
+                next = c;
+                break;
+            }
+        if (next < 0 || a + 1 >= stride) break;
+        cur = next;
+        path[++a] = cur;
+    }
+    accept_len[b] = a;
+    n_out[b] = a + 1;
+}
+
+// Recursive rejection sampling, one workgroup per sequence.  Integer weights W (target) and Qw
+// (draft) live in the workspace: [B][2][V] u64.  Every sum over the vocabulary is an exact integer
+// sum, every other operation a single IEEE double operation, so the decisions do not depend on the
+// reduction order.
+__device__ __forceinline__ double u64_to_d(unsigned long long x) { return (double)x; }
+
+__global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride, float temperature,
+                                                       const int32_t* __restrict__ token,
+                                                       const int32_t* __restrict__ parent,
+                                                       const float* __restrict__ logits,
+                                                       const float* __restrict__ draft_q,
+                                                       const uint32_t* __restrict__ u_accept,
+                                                       const uint32_t* __restrict__ u_final,
+                                                       int32_t* __restrict__ accept_len, int32_t* __restrict__ path_idx,
+                                                       int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_out,
+                                                       unsigned long long* __restrict__ ws) {
+    __shared__ unsigned long long su[4];
+    __shared__ double sd[4];
+    __shared__ unsigned long long scan[256];
+    __shared__ int pick_s;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int32_t* tok = token + (int64_t)b * n;
+    const int32_t* par = parent + (int64_t)b * n;
+    int32_t* path = path_idx + (int64_t)b * stride;
+    int32_t* out = out_tokens + (int64_t)b * stride;
+    unsigned long long* W = ws + (int64_t)b * 2 * V;
+    unsigned long long* Qw = W + V;
+    const double tau = (double)temperature;
+    for (int j = tid; j < stride; j += 256) {
+        path[j] = -1;
+        out[j] = -1;
+    }
+    __syncthreads();
+    int cur = 0, a = 0;
+    if (tid == 0) path[0] = 0;
+    unsigned long long S = 0, SQ = 0;
+    for (;;) {
+        const float* l = logits + ((int64_t)b * n + cur) * V;
+        const float* q = draft_q + ((int64_t)b * n + cur) * V;
+        double m = -INFINITY;
+        for (int j = tid; j < V; j += 256) m = fmax(m, (double)l[j] / tau);
+        m = block_max_d(m, sd);
+        unsigned long long s = 0, sq = 0;
+        for (int j = tid; j < V; j += 256) {
+            unsigned long long w = (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0);
+            unsigned long long qw = (unsigned long long)floor((double)q[j] * 4294967296.0);
+            W[j] = w;
+            Qw[j] = qw;
+            s += w;
+            sq += qw;
+        }
+        S = block_sum_u64(s, su);
+        SQ = block_sum_u64(sq, su);
+        int next = -1;
+        for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
+            if (par[c] != cur) continue;  // uniform: every thread reads the same tree
+            const int t = tok[c];
+            __syncthreads();  // W/Qw writes of other threads visible (same workgroup, global memory)
+            const double p = u64_to_d(W[t]) / u64_to_d(S);
+            const double qq = SQ > 0 ? u64_to_d(Qw[t]) / u64_to_d(SQ) : 0.0;
+            const double u = ((double)u_accept[(int64_t)b * n + c] + 0.5) / 4294967296.0;
+            if (u * qq < p) {
+                next = c;
+                break;
+            }
+            unsigned long long s2 = 0;
+            for (int j = tid; j < V; j += 256) {
+                double pj = u64_to_d(W[j]) / u64_to_d(S);
+                double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
+                double r = pj - qj;
+                if (r < 0.0) r = 0.0;
+                s2 += (unsigned long long)floor(r * 4294967296.0);
+            }
+            s2 = block_sum_u64(s2, su);
+            if (s2 > 0) {
+                for (int j = tid; j < V; j += 256) {
+                    double pj = u64_to_d(W[j]) / u64_to_d(S);
+                    double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
+                    double r = pj - qj;
+                    if (r < 0.0) r = 0.0;
+                    W[j] = (unsigned long long)floor(r * 4294967296.0);
+                }
+                S = s2;
+            }
+            __syncthreads();
+            if (tid == 0) Qw[t] = 0;
+            __syncthreads();
+            unsigned long long sq2 = 0;
+            for (int j = tid; j < V; j += 256) sq2 += Qw[j];
+            SQ = block_sum_u64(sq2, su);
+        }
+        if (next < 0) break;
+        if (tid == 0) out[a] = tok[next];
+        cur = next;
+        ++a;
+        if (tid == 0) path[a] = cur;
+        __syncthreads();
+    }
+    // final draw: first index whose running sum exceeds (u_final * S) >> 32
+    __syncthreads();
+    const unsigned long long thr =
+        (unsigned long long)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32);
+    const int chunk = (V + 255) / 256;
+    const int j0 = tid * chunk, j1 = min(V, j0 + chunk);
+    unsigned long long local = 0;
+    for (int j = j0; j < j1; ++j) local += W[j];
+    scan[tid] = local;
+    if (tid == 0) pick_s = V - 1;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long run = 0;
+        for (int t = 0; t < 256; ++t) {
+            unsigned long long v = scan[t];
+            scan[t] = run;
+            run += v;
+        }
+    }
+    __syncthreads();
+    const unsigned long long excl = scan[tid];
+    if (local > 0 && excl <= thr && thr < excl + local) {
+        unsigned long long run = excl;
+        for (int j = j0; j < j1; ++j) {
+            run += W[j];
+            if (run > thr) {
+                pick_s = j;
+                break;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        out[a] = pick_s;
+        accept_len[b] = a;
+        n_out[b] = a + 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// KV commit: row seq_len+path[j] -> row seq_len+j, j = 1..accept_len, for one (sequence, layer,
+// kv head) per workgroup.  A thread owns one 16-byte column chunk of K or V for all j and walks j
+// upward in batches of 8 (8 loads in flight, then 8 stores).  This order is hazard-free: a
+// destination row j can only be the source of an earlier j' (path[j'] >= j'), which has already been
+// read either in a previous batch or earlier in this batch's load phase.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+__global__ __launch_bounds__(64) void kv_commit_k(int n_layers, char* __restrict__ k_pool, char* __restrict__ v_pool,
+                                                  int64_t n_pages, const int32_t* __restrict__ block_table,
+                                                  const int32_t* __restrict__ seq_len, int max_pages, int page_size,
+                                                  int n_kv, int row_bytes, const int32_t* __restrict__ accept_len,
+                                                  const int32_t* __restrict__ path_idx, int stride) {
+    const int kh = blockIdx.x % n_kv, layer = blockIdx.x / n_kv, b = blockIdx.y;
+    int a = accept_len[b];
+    if (a > stride - 1) a = stride - 1;
+    if (a <= 0) return;
+    const int chunks = row_bytes / 16;
+    const int ctx = seq_len[b];
+    const int32_t* path = path_idx + (int64_t)b * stride;
+    const int64_t layer_off = (int64_t)layer * n_pages * n_kv * page_size * row_bytes;
+    for (int t = threadIdx.x; t < 2 * chunks; t += 64) {
+        char* pool = (t < chunks ? k_pool : v_pool) + layer_off;
+        const int col = (t < chunks ? t : t - chunks) * 16;
+        for (int j0 = 1; j0 <= a; j0 += 8) {
+            u32x4_t tmp[8];
+            bool ok[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int j = j0 + e;
+                ok[e] = false;
+                if (j <= a) {
+                    int p = path[j];
+                    PageRef pr;
+                    if (p > j && locate(block_table, max_pages, n_pages, page_size, b, ctx + p, pr)) {
+                        tmp[e] = *(const u32x4_t*)(pool + ((pr.page * n_kv + kh) * page_size + pr.row) * row_bytes + col);
+                        ok[e] = true;
+                    }
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int j = j0 + e;
+                PageRef pr;
+                if (ok[e] && locate(block_table, max_pages, n_pages, page_size, b, ctx + j, pr))
+                    *(u32x4_t*)(pool + ((pr.page * n_kv + kh) * page_size + pr.row) * row_bytes + col) = tmp[e];
+            }
+        }
+    }
+}
+
+__global__ void seq_len_advance_k(int B, int32_t* seq_len, const int32_t* accept_len, int stride) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int a = accept_len[b];
+    if (a > stride - 1) a = stride - 1;
+    if (a < 0) a = 0;
+    seq_len[b] += a + 1;
+}
+
+// ------------------------------------------------------------------------------------------------
+hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_argmax_k, dim3(M), dim3(256), 0, s, V, logits, out);
+    return hipGetLastError();
+}
+
+hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_topk_logp_k, dim3(M), dim3(256), 0, s, V, K, logits, tok, logp);
+    return hipGetLastError();
+}
+
+hipError_t draft_level0(hipStream_t s, int B, int K, const int32_t* top_tok, const float* top_logp, DraftState st,
+                        int feat_rows_per_seq) {
+    (void)feat_rows_per_seq;
+    hipLaunchKernelGGL(draft_level0_k, dim3((B * K + 255) / 256), dim3(256), 0, s, B, K, top_tok, top_logp, st);
+    return hipGetLastError();
+}
+
+hipError_t draft_level_select(hipStream_t s, int B, int K, int level, const int32_t* top_tok, const float* top_logp,
+                              DraftState st, int feat_rows_per_seq) {
+    (void)feat_rows_per_seq;
+    hipLaunchKernelGGL(draft_level_select_k, dim3(B), dim3(256), 0, s, K, level, top_tok, top_logp, st);
+    return hipGetLastError();
+}
+
+hipError_t draft_prune(hipStream_t s, int B, int pool_n, int n_tree, const int32_t* root_tokens,
+                       const int32_t* new_tokens, const int32_t* n_new, int new_stride, DraftState st, int32_t* token, int32_t* parent, int32_t* depth, uint64_t* anc_mask, float* score) {
+    size_t lds = sizeof(float) * (size_t)pool_n * 2 + sizeof(int) * (size_t)n_tree;
+    hipLaunchKernelGGL(draft_prune_k, dim3(B), dim3(256), lds, s, pool_n, n_tree, root_tokens, new_tokens, n_new,
+                       new_stride, st, token, parent, depth, anc_mask, score);
+    return hipGetLastError();
+}
+
+hipError_t tree_finalize(hipStream_t s, int B, int n, const int32_t* parent, int32_t* depth, uint64_t* anc_mask) {
+    hipLaunchKernelGGL(tree_finalize_k, dim3((B * n + 255) / 256), dim3(256), 0, s, B, n, parent, depth, anc_mask);
+    return hipGetLastError();
+}
+
+hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const int32_t* token, const int32_t* parent,
+                         const float* logits, const int32_t* argmax, int32_t* accept_len, int32_t* path_idx,
+                         int32_t* out_tokens, int32_t* n_out) {
+    (void)V; (void)logits;
+    hipLaunchKernelGGL(accept_greedy_k, dim3((B + 63) / 64), dim3(64), 0, s, B, n, stride, token, parent, argmax,
+                       accept_len, path_idx, out_tokens, n_out);
+    return hipGetLastError();
+}
+
+size_t accept_sample_workspace_bytes(int B, int V) { return (size_t)B * 2 * (size_t)V * sizeof(unsigned long long); }
+
+hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
+                         const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
+                         const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
+                         int32_t* n_out, void* ws) {
+    hipLaunchKernelGGL(accept_sample_k, dim3(B), dim3(256), 0, s, n, V, stride, temperature, token, parent, logits,
+                       draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out, (unsigned long long*)ws);
+    return hipGetLastError();
+}
+
+hipError_t kv_commit(hipStream_t s, int dtype, int B, int n_layers, void* k_pool, void* v_pool, int64_t n_pages,
+                     const int32_t* block_table, int32_t* seq_len, int max_pages, int page_size, int n_kv, int d,
+                     const int32_t* accept_len, const int32_t* path_idx, int stride) {
+    if (B <= 0) return hipSuccess;
+    const int row_bytes = d * (dtype == F32 ? 4 : 2);
+    hipLaunchKernelGGL(kv_commit_k, dim3(n_layers * n_kv, B), dim3(64), 0, s, n_layers, (char*)k_pool, (char*)v_pool,
+                       n_pages, block_table, seq_len, max_pages, page_size, n_kv, row_bytes, accept_len, path_idx, stride);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(seq_len_advance_k, dim3((B + 63) / 64), dim3(64), 0, s, B, seq_len, accept_len, stride);
+    return hipGetLastError();
+}
+
+}  // namespace tlt

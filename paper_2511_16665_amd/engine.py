@@ -1,0 +1,133 @@
+"""Host-side driver of the speculative-decoding step: owns the device buffers (torch tensors) and
+issues the four library calls per step.  No arithmetic of the method happens here.
+
+    draft_expand -> verify_forward -> accept -> kv_commit          (one SD step)
+
+The only host synchronisation per step is the read-back of accept_len / emitted tokens, which is
+also what the rollout loop's feedback needs (accept length and step latency, Section 3
+"Architecture & Workflow", and Algorithm 1's Record procedure).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as tlt
+
+
+def alloc_kv(cfg, dtype_code, n_layers, block_table: np.ndarray, n_pages: int, seq_len: np.ndarray, fill=None) -> tlt.KV:
+    dt = tlt.torch_dtype(dtype_code)
+    shape = (n_layers, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim)
+    if fill is None:
+        k = torch.zeros(shape, dtype=dt, device="cuda")
+        v = torch.zeros(shape, dtype=dt, device="cuda")
+    else:
+        k, v = fill
+    return tlt.KV(k, v, torch.from_numpy(np.ascontiguousarray(block_table, dtype=np.int32)).cuda(),
+                  torch.from_numpy(np.ascontiguousarray(seq_len, dtype=np.int32)).cuda(), int(np.max(seq_len)))
+
+
+class Engine:
+    def __init__(self, cfg, dtype_code, target_w, draft_w, batch, max_n, max_depth, max_topk, max_ctx, kv: tlt.KV,
+                 draft_kv: tlt.KV):
+        self.cfg, self.B = cfg, batch
+        self.ctx = tlt.Context(cfg, dtype_code, target_w, draft_w, batch, max_n, max_depth, max_topk, max_ctx)
+        self.kv, self.dkv = kv, draft_kv
+        self.max_n, self.max_depth = max_n, max_depth
+        dev = "cuda"
+        B = batch
+        self.stride = min(max_depth, max_n - 1) + 1      # longest accepted path + bonus token
+        i32 = lambda *s: torch.full(s, -1, dtype=torch.int32, device=dev)
+        self.accept_len, self.n_out = i32(B), i32(B)
+        self.path_idx, self.out_tokens = i32(B, self.stride), i32(B, self.stride)
+        self.pending_hidden, self.pending_max_new = None, 0
+        self.root = i32(B)
+        self._trees = {}
+        self.have_pending = False
+
+    def tree(self, n) -> tlt.Tree:
+        if n not in self._trees:
+            self._trees[n] = tlt.Tree.empty(self.B, n)
+        return self._trees[n]
+
+    # -- prompt ingestion: chain trees through the same verify / commit / extend calls
+    def prefill(self, prompts: np.ndarray, chunk=None):
+        """prompts [B, P] int32, equal lengths: prompts[:, :-1] goes into both caches, the last token
+        becomes the first root."""
+        B, P = prompts.shape
+        chunk = chunk or self.max_n
+        body = P - 1
+        for o in range(0, body, chunk):
+            m = min(chunk, body - o)
+            t = self.tree(m)
+            t.token.copy_(torch.from_numpy(np.ascontiguousarray(prompts[:, o:o + m])).cuda())
+            t.parent.copy_(torch.arange(-1, m - 1, dtype=torch.int32, device="cuda").expand(B, m))
+            self.ctx.tree_finalize(B, t)
+            hid = self._buf("hid", m)
+            self.ctx.verify_forward(B, t, self.kv, out_hidden=hid)
+            al = torch.full((B,), m - 1, dtype=torch.int32, device="cuda")
+            path = torch.arange(m, dtype=torch.int32, device="cuda").expand(B, m).contiguous()
+            self.ctx.kv_commit(B, self.kv, al, path, m)
+            self.kv.seq_len_bound += m
+            nxt = torch.from_numpy(np.ascontiguousarray(prompts[:, o + 1:o + 1 + m])).cuda()
+            n_new = torch.full((B,), m, dtype=torch.int32, device="cuda")
+            self.ctx.draft_expand(B, 0, 1, 1, nxt, path, n_new, hid, None, self.dkv, None)
+            self.dkv.seq_len_bound += m
+        self.root.copy_(torch.from_numpy(np.ascontiguousarray(prompts[:, -1])).cuda())
+        self.have_pending = False
+
+    def set_pending(self, new_tokens, new_src, n_new, hidden, max_new):
+        """Entries the drafter still has to catch up on at the start of the next step:
+        new_tokens/new_src [B, w] int32, n_new [B] int32, hidden [B, m, h] fp32 (device tensors);
+        max_new = host-known upper bound of n_new.  The next root is each sequence's last new token."""
+        self.out_tokens.fill_(-1)
+        self.path_idx.fill_(-1)
+        self.out_tokens[:, : new_tokens.shape[1]].copy_(new_tokens)
+        self.path_idx[:, : new_src.shape[1]].copy_(new_src)
+        self.n_out.copy_(n_new)
+        self.pending_hidden = hidden.contiguous()
+        self.pending_max_new = int(max_new)
+        self.have_pending = True
+
+    # -- one speculative-decoding step
+    def step(self, topk, depth, n_verify, sync=True, logits_out=None):
+        """Runs the four calls.  With sync=True returns (accept_len [B], out_tokens [B, stride]) as
+        numpy arrays and keeps the host-side length bounds exact; with sync=False nothing is read
+        back and the bounds advance by the largest possible accept length."""
+        B = self.B
+        pool = topk + (depth - 1) * topk * topk if depth >= 1 else 0
+        n = min(n_verify, 1 + pool)
+        t = self.tree(n)
+        if self.have_pending:
+            # root = last new token of each sequence (derived inside the library)
+            self.ctx.draft_expand(B, depth, topk, n_verify, self.out_tokens, self.path_idx, self.n_out,
+                                  self.pending_hidden, None, self.dkv, t)
+            self.dkv.seq_len_bound += self.pending_max_new
+        else:
+            self.ctx.draft_expand(B, depth, topk, n_verify, None, None, None, None, self.root, self.dkv, t)
+        hid, am = self._buf("hid", n), self._buf("am", n)
+        self.ctx.verify_forward(B, t, self.kv, out_logits=logits_out, out_argmax=am, out_hidden=hid)
+        self.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, self.stride, self.accept_len, self.path_idx,
+                        self.out_tokens, self.n_out)
+        self.ctx.kv_commit(B, self.kv, self.accept_len, self.path_idx, self.stride)
+        self.pending_hidden = hid
+        self.have_pending = True
+        if sync:
+            al = self.accept_len.cpu().numpy()
+            out = self.out_tokens.cpu().numpy()
+            inc = int(al.max()) + 1
+        else:
+            al = out = None
+            inc = min(depth, n - 1) + 1
+        self.kv.seq_len_bound += inc
+        self.pending_max_new = inc
+        return al, out
+
+    def _buf(self, kind, n):
+        key = (kind, n)
+        if key not in self._trees:
+            if kind == "hid":
+                self._trees[key] = torch.zeros((self.B, n, self.cfg.hidden), dtype=torch.float32, device="cuda")
+            else:
+                self._trees[key] = torch.zeros((self.B, n), dtype=torch.int32, device="cuda")
+        return self._trees[key]

@@ -1,0 +1,148 @@
+"""tlt_accept and tlt_kv_commit against the oracle, bit-exact on identical inputs."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import accept as oa
+from oracle import sd
+from paper_2511_16665_amd import binding as tlt
+from synth import TINY, make_decoder_weights, random_block_table, synthetic_logits, uniforms_u32
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(vocab, B, n, dtype=tlt.TLT_F32, cfg=TINY):
+    cfg = dataclasses.replace(cfg, vocab=vocab, n_layers=1)
+    dt = tlt.torch_dtype(dtype)
+    w = make_decoder_weights(cfg, 1, device="cuda", dtype=dt)
+    return cfg, tlt.Context(cfg, dtype, w, None, B, n, 8, 4, 4096)
+
+
+def _random_trees(rng, B, n, V, branching=3, dup=False):
+    token = rng.integers(0, V, size=(B, n)).astype(np.int32)
+    parent = np.full((B, n), -1, dtype=np.int32)
+    for b in range(B):
+        for i in range(1, n):
+            parent[b, i] = rng.integers(max(0, i - branching), i)
+    return token, parent
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _tree_dev(token, parent):
+    B, n = token.shape
+    t = tlt.Tree.empty(B, n)
+    t.token.copy_(_dev(token))
+    t.parent.copy_(_dev(parent))
+    return t
+
+
+def _run_accept(ctx, B, n, stride, mode, tree, **kw):
+    outs = [torch.full(s, -7, dtype=torch.int32, device="cuda") for s in ((B,), (B, stride), (B, stride), (B,))]
+    ctx.accept(B, mode, kw.get("temperature", 1.0), tree, kw.get("logits"), kw.get("argmax"), kw.get("draft_q"),
+               kw.get("u_accept"), kw.get("u_final"), stride, *outs)
+    torch.cuda.synchronize()
+    return [o.cpu().numpy() for o in outs]
+
+
+@pytest.mark.parametrize("B,n,V,stride", [(64, 12, 5, 12), (3, 64, 1024, 9), (1, 1, 17, 1), (32, 48, 4099, 7)])
+def test_greedy_accept_bit_exact(B, n, V, stride):
+    rng = np.random.default_rng(B * 1000 + n)
+    cfg, ctx = _ctx(V, B, n)
+    token, parent = _random_trees(rng, B, n, V)
+    logits = synthetic_logits((B, n, V), seed=n)
+    if V == 5:
+        logits = np.round(logits)                     # many exact ties: lowest index must win
+    want = oa.accept_greedy(token, parent, logits, stride)
+    print(f"greedy accept B={B} n={n} V={V}", flush=True)
+    tree = _tree_dev(token, parent)
+    got = _run_accept(ctx, B, n, stride, 0, tree, logits=_dev(logits))
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)
+    # same through the argmax fast path
+    am = torch.from_numpy(np.argmax(logits, axis=2).astype(np.int32)).cuda()
+    got2 = _run_accept(ctx, B, n, stride, 0, tree, argmax=am)
+    for g, w in zip(got2, want):
+        np.testing.assert_array_equal(g, w)
+    ctx.close()
+
+
+@pytest.mark.parametrize("B,n,V,tau,k", [(256, 4, 16, 1.0, 2), (16, 21, 1000, 0.9, 4), (4, 64, 152064, 1.0, 3)])
+def test_sampling_accept_bit_exact(B, n, V, tau, k):
+    """Trees whose sibling lists are drawn without replacement from a noisy copy of the target
+    distribution (sigma = 1 on the logits): the long-tail workload's drafter."""
+    rng = np.random.default_rng(V + n)
+    cfg, ctx = _ctx(V, B, n)
+    logits = synthetic_logits((B, n, V), seed=7)
+    ql = logits + rng.standard_normal(size=logits.shape).astype(np.float32)
+    q = np.exp(ql - ql.max(axis=-1, keepdims=True))
+    q = (q / q.sum(axis=-1, keepdims=True)).astype(np.float32)
+    token = np.zeros((B, n), dtype=np.int32)
+    parent = np.full((B, n), -1, dtype=np.int32)
+    for b in range(B):                                 # breadth-first k-ary template
+        nxt = 1
+        for p in range(n):
+            if nxt >= n:
+                break
+            kids = oa.draw_without_replacement(q[b, p], k, rng)
+            for t in kids:
+                if nxt < n:
+                    token[b, nxt], parent[b, nxt] = t, p
+                    nxt += 1
+    u_acc, u_fin = uniforms_u32((B, n), 11), uniforms_u32((B,), 12)
+    stride = 6
+    want = oa.accept_sample(token, parent, logits, q, u_acc, u_fin, tau, stride)
+    assert want[0].max() >= 1
+    print(f"sampling accept B={B} n={n} V={V}", flush=True)
+    got = _run_accept(ctx, B, n, stride, 1, _tree_dev(token, parent), logits=_dev(logits), draft_q=_dev(q),
+                      u_accept=_dev(u_acc), u_final=_dev(u_fin), temperature=tau)
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype", [tlt.TLT_F32, tlt.TLT_BF16])
+def test_kv_commit_bit_exact_and_touches_nothing_else(dtype):
+    cfg = dataclasses.replace(TINY, n_layers=3)
+    B, n, stride = 5, 24, 9
+    rng = np.random.default_rng(0)
+    ctxlen = np.array([0, 5, 16, 37, 100], dtype=np.int32)
+    table, n_pages = random_block_table(ctxlen + n, cfg.page_size, seed=4, extra_pages=4)
+    dt = tlt.torch_dtype(dtype)
+    w = make_decoder_weights(cfg, 1, device="cuda", dtype=dt)
+    ctx = tlt.Context(cfg, dtype, w, None, B, n, 8, 4, 4096)
+    shape = (cfg.n_layers, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim)
+    k = torch.randn(shape, generator=torch.Generator().manual_seed(1)).to(dt)
+    v = torch.randn(shape, generator=torch.Generator().manual_seed(2)).to(dt)
+    # paths: strictly increasing node indices starting at the root, including the hazard 0,2,5 -> 0,1,2
+    accept_len = np.array([0, 2, 8, 3, 5], dtype=np.int32)
+    path = np.full((B, stride), -1, dtype=np.int32)
+    path[:, 0] = 0
+    path[1, :3] = [0, 2, 5]
+    path[2, :9] = [0, 1, 2, 3, 4, 5, 6, 7, 8]          # identity: nothing moves
+    path[3, :4] = [0, 3, 4, 23]
+    path[4, :6] = [0, 1, 3, 7, 8, 16]                   # crosses a page boundary
+    kv = tlt.KV(k.cuda(), v.cuda(), _dev(table), _dev(ctxlen), int(ctxlen.max()))
+    print(f"kv_commit dtype={dtype}", flush=True)
+    ctx.kv_commit(B, kv, _dev(accept_len), _dev(path), stride)
+    torch.cuda.synchronize()
+    # bf16 -> float64 is exact, so equality of the float64 images is bit equality
+    k_want, v_want = k.double().numpy().copy(), v.double().numpy().copy()
+    for b in range(B):
+        slots = np.arange(ctxlen[b] + n)
+        pg, off = table[b, slots // cfg.page_size], slots % cfg.page_size
+        for l in range(cfg.n_layers):
+            kd, vd = k_want[l][pg, :, off], v_want[l][pg, :, off]          # dense view [slots, Hkv, d] (copies)
+            new_len = sd.commit_rows(kd, vd, int(ctxlen[b]), [int(p) for p in path[b, : accept_len[b] + 1]])
+            assert new_len == ctxlen[b] + accept_len[b] + 1
+            k_want[l][pg, :, off] = kd
+            v_want[l][pg, :, off] = vd
+    np.testing.assert_array_equal(kv.k_pool.double().cpu().numpy(), k_want)
+    np.testing.assert_array_equal(kv.v_pool.double().cpu().numpy(), v_want)
+    assert not np.array_equal(k_want, k.double().numpy())               # the case moved something
+    np.testing.assert_array_equal(kv.seq_len.cpu().numpy(), ctxlen + accept_len + 1)
+    ctx.close()

@@ -1,0 +1,64 @@
+"""tlt_gemm (the projection / LM-head kernel) against a float64 matrix product."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_16665_amd import binding as tlt
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(M, N, K, dtype, out_mode, seed):
+    g = torch.Generator().manual_seed(seed)
+    A = torch.randn((M, K), generator=g)
+    W = torch.randn((N, K), generator=g) * 0.05
+    C0 = torch.randn((M, N), generator=g)
+    if dtype == tlt.TLT_BF16:
+        A, W = A.bfloat16(), W.bfloat16()
+    want = A.double().numpy() @ W.double().numpy().T
+    if out_mode == 0:
+        out = torch.zeros((M, N), dtype=A.dtype, device="cuda")
+    else:
+        out = C0.clone().cuda() if out_mode == 2 else torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    if out_mode == 2:
+        want = want + C0.double().numpy()
+    print(f"gemm M={M} N={N} K={K} dtype={dtype} out_mode={out_mode}", flush=True)
+    tlt.gemm(dtype, out_mode, A.cuda(), W.cuda(), out)
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    scale = np.abs(want).max()
+    tol = 1e-5 if dtype == tlt.TLT_F32 else (1e-2 if out_mode == 0 else 2e-3)   # bf16 store rounds to 2^-9
+    assert np.abs(got - want).max() <= tol * scale
+
+
+@pytest.mark.parametrize("out_mode", [0, 1, 2])
+@pytest.mark.parametrize("M,N,K", [(1, 7, 5), (70, 130, 33), (257, 64, 256)])
+def test_gemm_fp32_generic(M, N, K, out_mode):
+    _case(M, N, K, tlt.TLT_F32, out_mode, 1)
+
+
+@pytest.mark.parametrize("out_mode", [0, 1, 2])
+@pytest.mark.parametrize("M,N,K", [
+    (300, 512, 256),      # 128x128 tiles, ragged M tail, 4 K steps
+    (8, 384, 64),         # one K step, tiny M
+    (129, 128, 640),      # single N tile
+    (1000, 16384, 128),   # 256x256 tiles (>= 256 of them), ragged M tail
+    (50, 200, 96),        # shape the MFMA path cannot take -> generic kernel on bf16
+])
+def test_gemm_bf16(M, N, K, out_mode):
+    _case(M, N, K, tlt.TLT_BF16, out_mode, 2)
+
+
+def test_gemm_bf16_7b_layer_shape_sampled_rows():
+    """qkv projection shape of the 7B workload (M = 1536): check a sample of output rows."""
+    M, N, K = 1536, 4608, 3584
+    g = torch.Generator().manual_seed(3)
+    A = torch.randn((M, K), generator=g).bfloat16()
+    W = (torch.randn((N, K), generator=g) * 0.02).bfloat16()
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    tlt.gemm(tlt.TLT_BF16, 1, A.cuda(), W.cuda(), out)
+    torch.cuda.synchronize()
+    rows = [0, 1, 127, 128, 255, 256, 777, 1535]
+    want = A[rows].double().numpy() @ W.double().numpy().T
+    got = out[rows].double().cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-3 * np.abs(want).max()
