@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding step on one MI355X.
+
+Workload (the configuration the metric is quoted on): Qwen2.5-7B-shaped target, random-init bf16,
+1-layer drafter of the same width, batch 32, contexts lognormal(median 4096, sigma 0.8, floor 256,
+cap 16384) in a paged KV cache with 16-token pages filled with N(0,1), tree depth 6 / top-k 8 /
+48 verify tokens, greedy acceptance.  One step = tlt_draft_expand + tlt_verify_forward + tlt_accept
++ tlt_kv_commit over the whole batch, inputs resident in HBM.
+
+Prints ONE JSON line: accepted tokens/s (value), plus the roofline of the dominant kernel (the
+bf16 MFMA GEMM of the verification forward, timed per launch with HIP events inside the library),
+verify latency versus tree size, and the CPU oracle timed on a bounded sample of the same
+workload as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def build_workload(args):
+    import torch
+
+    from paper_2511_16665_amd import binding as tlt
+    from paper_2511_16665_amd import engine as eng
+    from synth import (QWEN7B, QWEN32B, MID, fill_kv_pool, lognormal_contexts, make_decoder_weights,
+                       make_drafter_weights, random_block_table)
+
+    cfg = {"7b": QWEN7B, "32b": QWEN32B, "mid": MID}[args.model]
+    B, K, D, N = args.batch, args.topk, args.depth, args.verify
+    ctx = lognormal_contexts(B, args.ctx_median, 0.8, args.ctx_cap, min(256, args.ctx_median), seed=0)
+    grow = (args.steps + args.warmup + 8) * (min(D, N - 1) + 1) * 2 + 64 + N
+    caps = ctx + grow + max(D - 1, 0) * K
+    table, n_pages = random_block_table(caps, cfg.page_size, seed=1, extra_pages=8)
+    dtable, dn_pages = random_block_table(caps, cfg.page_size, seed=2, extra_pages=8)
+    dt = torch.bfloat16
+    t0 = time.time()
+    tw = make_decoder_weights(cfg, 1234, device="cuda", dtype=dt)
+    dw = make_drafter_weights(cfg, 1234, device="cuda", dtype=dt)
+    kfill = fill_kv_pool(cfg.n_layers, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 3, "cuda", dt)
+    dfill = fill_kv_pool(1, dn_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 4, "cuda", dt)
+    kv = eng.alloc_kv(cfg, tlt.TLT_BF16, cfg.n_layers, table, n_pages, ctx, fill=kfill)
+    dkv = eng.alloc_kv(cfg, tlt.TLT_BF16, 1, dtable, dn_pages, ctx, fill=dfill)
+    max_ctx = int(caps.max()) + 64
+    e = eng.Engine(cfg, tlt.TLT_BF16, tw, dw, B, max(N, 64) if args.sweep else N, D, K, max_ctx, kv, dkv)
+    # the drafter starts one entry behind: (root token, hidden state of the last committed position)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    tok = torch.randint(0, cfg.vocab, (B, 1), generator=g, device="cuda", dtype=torch.int32)
+    hid = torch.randn((B, 1, cfg.hidden), generator=g, device="cuda", dtype=torch.float32)
+    src = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+    one = torch.ones((B,), dtype=torch.int32, device="cuda")
+    e.set_pending(tok, src, one, hid, 1)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    return cfg, e, ctx, tw, dw, table, dtable, setup_s
+
+
+def verify_latency_sweep(cfg, e, sizes, iters=3):
+    """Latency of tlt_verify_forward alone versus the number of tree nodes (chain trees)."""
+    import torch
+    out = {}
+    B = e.B
+    for n in sizes:
+        t = e.tree(n)
+        t.token.copy_(torch.randint(0, cfg.vocab, (B, n), device="cuda", dtype=torch.int32))
+        t.parent.copy_(torch.arange(-1, n - 1, dtype=torch.int32, device="cuda").expand(B, n))
+        e.ctx.tree_finalize(B, t)
+        am = e._buf("am", n)
+        e.ctx.verify_forward(B, t, e.kv, None, am, None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            e.ctx.verify_forward(B, t, e.kv, None, am, None)
+        torch.cuda.synchronize()
+        out[str(n)] = round((time.perf_counter() - t0) / iters * 1e3, 3)
+    return out
+
+
+def _gather_rows(pool_layer, table_row, c, page_size):
+    """First c cache rows of one sequence in one layer as float64 [c, Hkv, d]."""
+    import torch
+    slots = np.arange(c)
+    pg = torch.from_numpy(table_row[slots // page_size].astype(np.int64)).cuda()
+    off = torch.from_numpy((slots % page_size).astype(np.int64)).cuda()
+    return pool_layer[pg, :, off].double().cpu().numpy()
+
+
+class _EmbedRows:
+    """Embedding table kept on the device; rows are widened to float64 when the oracle indexes it."""
+
+    def __init__(self, t):
+        self.t = t
+
+    def __getitem__(self, idx):
+        import torch
+        return self.t[torch.as_tensor(np.asarray(idx), device=self.t.device)].double().cpu().numpy()
+
+
+def cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args):
+    """The oracle's SD step (as it stands in oracle/) for ONE sequence of the batch, the one with the
+    shortest context, with 2 of the target's decoder layers, timed on the host cores; the layer part
+    is scaled to the full depth.  Weight widening to float64 happens before the clock starts."""
+    import dataclasses
+
+    from oracle import decoder as dec
+    from oracle import sd
+
+    L_sample = min(2, cfg.n_layers)
+    b = int(np.argmin(ctx))
+    c = int(ctx[b])
+    to64 = dec.weights_to_f64
+    tw64 = {"embed": _EmbedRows(tw["embed"]), "lm_head": to64(tw["lm_head"]), "final_norm": to64(tw["final_norm"]),
+            "layers": [to64(tw["layers"][l]) for l in range(L_sample)]}
+    dw64 = to64(dw)
+    small = dataclasses.replace(cfg, n_layers=L_sample)
+    st = sd.SeqState(small, c + args.verify + args.depth * args.topk + 16, dec.round_to_bf16)
+    for l in range(L_sample):
+        st.target[l].k[:c] = _gather_rows(e.kv.k_pool[l], table[b], c, cfg.page_size)
+        st.target[l].v[:c] = _gather_rows(e.kv.v_pool[l], table[b], c, cfg.page_size)
+    st.draft.k[:c] = _gather_rows(e.dkv.k_pool[0], dtable[b], c, cfg.page_size)
+    st.draft.v[:c] = _gather_rows(e.dkv.v_pool[0], dtable[b], c, cfg.page_size)
+    st.ctx = c
+    st.draft_len = c
+    rng = np.random.default_rng(0)
+    t0 = time.perf_counter()
+    sd.draft_extend(small, tw64, dw64, st, [int(rng.integers(cfg.vocab))], rng.normal(size=(1, cfg.hidden)))
+    tree, _ = sd.draft_expand(small, tw64, dw64, st, 1, args.topk, args.depth, args.verify)
+    t_draft = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    logits, hidden = sd.verify(small, tw64, st, tree)
+    t_verify = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    dec.lm_logits(small, tw64, hidden)
+    t_head = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    a, path, out = sd.accept_greedy(tree, logits)
+    sd.commit(st, path)
+    t_tail = time.perf_counter() - t0
+    t_layers = max(t_verify - t_head, 0.0)
+    t_seq = t_draft + t_layers * cfg.n_layers / L_sample + t_head + t_tail
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": round((a + 1) / t_seq, 4), "unit": "accepted tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one sequence of the batch (context {c}): drafter extend + expand, {L_sample} of {cfg.n_layers} "
+                      f"target layers + LM head, accept, commit; layer time scaled by {cfg.n_layers}/{L_sample}; the "
+                      f"oracle runs sequences one after another, so its tokens/s does not grow with the batch",
+            "seconds_measured": round(t_draft + t_verify + t_head + t_tail, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--model", default="7b", choices=["7b", "32b", "mid"])
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--depth", type=int, default=6)
+    ap.add_argument("--topk", type=int, default=8)
+    ap.add_argument("--verify", type=int, default=48)
+    ap.add_argument("--ctx-median", type=int, default=4096)
+    ap.add_argument("--ctx-cap", type=int, default=16384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", dest="sweep", action="store_false")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent and would "
+                 "shard by sequence); run with --gpus 1")
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
+    K, D, N, B = args.topk, args.depth, args.verify, args.batch
+
+    for _ in range(args.warmup):
+        e.step(K, D, N)
+    torch.cuda.synchronize()
+    emitted = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        al, _ = e.step(K, D, N)
+        emitted += int(al.sum()) + B
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # same steps again with per-launch HIP events inside the library (roofline of each kernel class)
+    e.ctx.profile_begin(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e.step(K, D, N)
+    torch.cuda.synchronize()
+    ms_prof = (time.perf_counter() - t0) / args.steps * 1e3
+    prof = e.ctx.profile_read()
+    e.ctx.profile_begin(False)
+    g = prof["gemm"]
+    gemm_tflops = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
+    at = prof["attention"]
+    attn_gbs = at["bytes"] / (at["ms"] * 1e-3) / 1e9 if at["ms"] > 0 else 0.0
+    per_class = {k: {"ms_per_step": round(v["ms"] / args.steps, 4), "launches_per_step": v["launches"] // args.steps}
+                 for k, v in prof.items()}
+
+    result = {
+        "metric": "accepted tokens/s per GPU in SD rollout step; verify latency vs tree size",
+        "value": round(emitted / dt, 2), "unit": "accepted tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} random-init bf16, 1-layer drafter, batch {B}, contexts lognormal(median "
+                               f"{args.ctx_median}, sigma 0.8, cap {args.ctx_cap}) = {int(ctx.sum())} cached tokens, "
+                               f"16-token pages, tree depth {D} top-k {K} verify {N}, greedy",
+                   "accepted_per_step": round(emitted / args.steps, 2), "drafter": "random-init (accept length ~0)"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_k (verification forward GEMMs)",
+                     "achieved": round(gemm_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "avg_launch_us": round(g["ms"] / max(g["launches"], 1) * 1e3, 2),
+                     "flops_per_launch": round(g["flops"] / max(g["launches"], 1), 0)},
+        "attention_roofline": {"bound": "hbm", "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": round(attn_gbs / PEAK_HBM_GBS, 4)},
+        "per_class": per_class, "ms_per_step_profiled": round(ms_prof, 3), "setup_s": round(setup_s, 1),
+    }
+    if args.sweep:
+        result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

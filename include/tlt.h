@@ -176,10 +176,12 @@ int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const v
  * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
 int tlt_set_attention_impl(tlt_ctx *ctx, int impl);
 
-/* Per-kernel-class timing with HIP events on the launch stream.  Classes: 0 GEMM, 1 attention,
- * 2 KV commit, 3 everything else.  tlt_profile_read synchronises the recorded events and returns,
- * per class, summed milliseconds, launches, algorithmic flops and algorithmic bytes since the last
- * tlt_profile_begin.  Arrays are HOST, 4 entries each. */
+/* Per-kernel-class timing with HIP events on the launch stream.  Classes: 0 GEMMs of the target's
+ * verification forward, 1 its tree attention, 2 KV commit, 3 everything else, 4 the drafter's GEMMs,
+ * 5 the drafter's attention.  tlt_profile_read synchronises the recorded events and returns, per
+ * class, summed milliseconds, launches, algorithmic flops and algorithmic bytes since the last
+ * tlt_profile_begin.  Arrays are HOST, TLT_PROFILE_CLASSES entries each. */
+enum { TLT_PROFILE_CLASSES = 6 };
 int tlt_profile_begin(tlt_ctx *ctx, int enable);
 int tlt_profile_read(tlt_ctx *ctx, double *ms, int64_t *launches, double *flops, double *bytes);
 

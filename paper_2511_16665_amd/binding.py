@@ -242,9 +242,9 @@ class Context:
         self._check(self.lib.tlt_profile_begin(self.handle, int(enable)), "tlt_profile_begin")
 
     def profile_read(self):
-        ms, n, fl, by = (C.c_double * 4)(), (C.c_int64 * 4)(), (C.c_double * 4)(), (C.c_double * 4)()
+        ms, n, fl, by = (C.c_double * 6)(), (C.c_int64 * 6)(), (C.c_double * 6)(), (C.c_double * 6)()
         self._check(self.lib.tlt_profile_read(self.handle, ms, n, fl, by), "tlt_profile_read")
-        names = ("gemm", "attention", "kv_commit", "other")
+        names = ("gemm", "attention", "kv_commit", "other", "gemm_draft", "attention_draft")
         return {k: {"ms": ms[i], "launches": n[i], "flops": fl[i], "bytes": by[i]} for i, k in enumerate(names)}
 
 

@@ -15,7 +15,7 @@ using namespace tlt;
 
 namespace {
 
-enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_COMMIT = 2, CLS_OTHER = 3, CLS_N = 4 };
+enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_COMMIT = 2, CLS_OTHER = 3, CLS_GEMM_DRAFT = 4, CLS_ATTN_DRAFT = 5, CLS_N = 6 };
 
 struct ProfRec {
     int cls;
@@ -101,6 +101,7 @@ struct tlt_ctx {
     Plan plan;
     int hip_error = 0;
     int attn_impl = -1;  // -1: pick by dtype/shape
+    bool in_draft = false;  // launches are accounted to the drafter's classes
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> events;
@@ -152,7 +153,7 @@ size_t esz_of(const tlt_ctx* c) { return c->cfg.dtype == TLT_F32 ? 4 : 2; }
 int run_gemm(tlt_ctx* ctx, hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
     const double e = (double)esz_of(ctx);
     const double out_b = out_mode == OUT_T ? e : (out_mode == OUT_F32 ? 4.0 : 8.0);
-    TLT_RUN(ctx, s, CLS_GEMM, 2.0 * M * N * K, ((double)M * K + (double)N * K) * e + (double)M * N * out_b,
+    TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 2.0 * M * N * K, ((double)M * K + (double)N * K) * e + (double)M * N * out_b,
             gemm(s, ctx->cfg.dtype, out_mode, M, N, K, A, W, C));
     return TLT_OK;
 }
@@ -193,7 +194,7 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
         const double keys = (double)rows.B * ((double)kv.seq_len_bound + rows.n_region);
         const double bytes = keys * 2.0 * c.n_kv_heads * c.head_dim * e + 2.0 * M * q_dim * e;
         const double flops = 4.0 * c.head_dim * c.n_q_heads * (double)rows.n * keys;
-        TLT_RUN(ctx, s, CLS_ATTN, flops, bytes,
+        TLT_RUN(ctx, s, ctx->in_draft ? CLS_ATTN_DRAFT : CLS_ATTN, flops, bytes,
                 attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl));
     }
     if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
@@ -356,6 +357,11 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     int rc = check_kv(ctx, draft_kv, new_stride + prov_rows);
     if (rc) return rc;
 
+    struct DraftFlag {
+        tlt_ctx* c;
+        explicit DraftFlag(tlt_ctx* x) : c(x) { c->in_draft = true; }
+        ~DraftFlag() { c->in_draft = false; }
+    } draft_flag(ctx);
     hipStream_t s = (hipStream_t)stream;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;

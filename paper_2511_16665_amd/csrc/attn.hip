@@ -7,6 +7,7 @@
 // impl 0 ("wave-per-row"): one wavefront per (row, query head); lanes own keys for the score pass
 //   and head dimensions for the value pass; online softmax across 64-key tiles.  Any dtype, any
 //   head_dim that is a multiple of 64 up to 256.  Used for fp32 mode and as a cross-check.
+// impl 1 ("MFMA split-KV"): the bf16 / head_dim 128 production kernel, described further down.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -90,16 +91,366 @@ __global__ __launch_bounds__(64) void attn_wave_per_row_k(Rows rows, KVLayer kv,
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// impl 1 ("MFMA split-KV"), bf16, head_dim 128.
+//
+// One workgroup (8 waves, two per SIMD) owns (sequence b, kv head, chunk of CK keys, group of
+// query-row tiles).
+// All G query heads of the kv head and all tree rows form the row set R = n*G, row r = i*G + g, cut
+// into tiles of 16 rows dealt round-robin to the waves; a wave keeps its tiles' Q fragments and
+// fp32 output accumulators in registers and the whole workgroup streams the chunk's K/V pages once
+// through LDS in tiles of 64 keys (global -> registers -> LDS, next tile's loads issued before the
+// current tile's MFMAs).
+//
+// Both products run on v_mfma_f32_16x16x32_bf16 in the transposed orientation:
+//   S^T[key][row] = sum_d K[key][d] Q[row][d]      A = K rows from LDS, B = Q fragment
+//   O^T[d][row]  += sum_key V^T[d][key] P^T[key][row]   A = V^T from LDS, B = P packed from S^T
+// In that orientation a lane's S^T results (4 consecutive keys of its own row l%16) are already the
+// k-slots the second product's B operand wants, so P never leaves registers; V is transposed once
+// per tile on its way into LDS, with the keys of each 32-key group permuted to the k-slot order
+// (key 16*sub + 4*g + v  ->  slot 8*g + 4*sub + v).  A lane's 32 accumulators all belong to one row,
+// so the online-softmax rescale is a per-lane scalar.
+// Each workgroup writes unnormalised partial outputs with their running max and sum (fp32); a
+// second kernel merges the chunks.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+constexpr int kD = 128;       // head_dim of this kernel
+constexpr int kKT = 64;       // keys per LDS tile
+constexpr int kKStr = 136;    // LDS row stride of the K tile (elements): 272 B, rows shift by 16 B
+constexpr int kVStr = 72;     // LDS row stride of the V^T tile (elements)
+constexpr int kTileElems = kKT * kKStr + kD * kVStr;
+constexpr float kNegBig = -1e30f;
+
+struct AttnPlan {
+    int ck;          // keys per chunk (multiple of 64)
+    int n_chunks;    // grid.x
+    int row_tiles;   // ceil(R / 16)
+    int row_groups;  // grid.y factor: row tiles are cut into groups of at most 8 * tpw = 24
+    int tpw;         // row tiles per wave (template instance)
+    int r_pad;       // row_tiles * 16
+};
+
+static AttnPlan plan_attention(int B, int n, int G, int n_kv, int bound_total) {
+    AttnPlan p;
+    const int pairs = B * n_kv;
+    int target = 768 / (pairs > 0 ? pairs : 1);
+    if (target < 1) target = 1;
+    int ck = (bound_total + target - 1) / target;
+    ck = ((ck + 63) / 64) * 64;
+    if (ck < 256) ck = 256;
+    p.ck = ck;
+    p.n_chunks = (bound_total + ck - 1) / ck;
+    if (p.n_chunks < 1) p.n_chunks = 1;
+    p.row_tiles = (n * G + 15) / 16;
+    p.r_pad = p.row_tiles * 16;
+    p.row_groups = (p.row_tiles + 23) / 24;
+    const int per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
+    const int per_wave = (per_group + 7) / 8;
+    p.tpw = per_wave <= 1 ? 1 : (per_wave <= 2 ? 2 : 3);
+    return p;
+}
+
+template <int TPW>
+__global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
+                                                   float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                   int n_q_heads, int ck, int n_chunks, int row_tiles,
+                                                   int tiles_per_group, int r_pad, float scale_log2) {
+    extern __shared__ __align__(16) uint16_t lds[];
+    const int chunk = blockIdx.x;
+    const int kh = blockIdx.y % kv.n_kv, rg = blockIdx.y / kv.n_kv;
+    const int b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g4 = lane >> 4;
+    const int G = n_q_heads / kv.n_kv;
+    const int n = rows.n;
+    const int R = n * G;
+    const int ctx = kv.seq_len[b];
+    const int total = ctx + rows.n_region;
+    const int k_begin = chunk * ck;
+    if (k_begin >= total) return;  // uniform
+    const int k_end = min(total, k_begin + ck);
+    const int qkv_dim = (n_q_heads + 2 * kv.n_kv) * kD;
+    const int nv = rows.n_valid ? min(rows.n_valid[b], n) : n;
+
+    // ---- this wave's row tiles: Q fragments, masks, accumulators
+    u32x4_t qf[TPW][4];
+    uint64_t mk0[TPW], mk1[TPW];
+    int row_i[TPW];
+    bool tile_on[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int tile = rg * tiles_per_group + wave + 8 * t;
+        tile_on[t] = (wave + 8 * t) < tiles_per_group && tile < row_tiles;
+        const int r = tile * 16 + l16;
+        const int i = r / G, gq = r - i * G;
+        const bool valid = tile_on[t] && r < R && i < nv;
+        row_i[t] = valid ? i : -1;
+        const uint16_t* qp = qkv + (int64_t)(b * n + (valid ? i : 0)) * qkv_dim + (kh * G + gq) * kD + g4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            u32x4_t z = {0u, 0u, 0u, 0u};
+            qf[t][ks] = valid ? *(const u32x4_t*)(qp + ks * 32) : z;
+        }
+        uint64_t m0 = 0, m1 = 0;
+        if (valid) {
+            if (rows.mask) {
+                const uint64_t* mp = rows.mask + (int64_t)(b * n + i) * rows.mask_words;
+                m0 = mp[0];
+                m1 = rows.mask_words > 1 ? mp[1] : 0ull;
+            } else {  // causal within the new rows
+                m0 = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
+                m1 = i < 64 ? 0ull : (i >= 127 ? ~0ull : ((2ull << (i - 64)) - 1ull));
+            }
+        }
+        mk0[t] = m0;
+        mk1[t] = m1;
+    }
+    f32x4_t acc[TPW][8];
+    float m_run[TPW], l_run[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        m_run[t] = kNegBig;
+        l_run[t] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) acc[t][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- staging: thread handles 16-byte chunks q = tid + 512*e, e < 2, of the K tile and of the V
+    // tile: key q / 16, d-chunk q % 16
+    const uint16_t* kpool = (const uint16_t*)kv.k;
+    const uint16_t* vpool = (const uint16_t*)kv.v;
+    u32x4_t rk[2], rv[2];
+    auto issue_loads = [&](int t0) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int q = tid + 512 * e;
+            const int key = t0 + (q >> 4), dc = (q & 15) * 8;
+            u32x4_t z = {0u, 0u, 0u, 0u};
+            rk[e] = z;
+            rv[e] = z;
+            PageRef pr;
+            if (key < k_end && locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, key, pr)) {
+                const int64_t off = ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * kD + dc;
+                rk[e] = *(const u32x4_t*)(kpool + off);
+                rv[e] = *(const u32x4_t*)(vpool + off);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        uint16_t* kt = lds + buf * kTileElems;
+        uint16_t* vt = kt + kKT * kKStr;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int q = tid + 512 * e;
+            const int key = q >> 4, dc = (q & 15) * 8;
+            *(u32x4_t*)(kt + key * kKStr + dc) = rk[e];
+            // V^T with the k-slot permutation inside each 32-key group
+            const int grp = key >> 5, kk = key & 31;
+            const int pos = grp * 32 + ((kk & 15) >> 2) * 8 + (kk >> 4) * 4 + (kk & 3);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                vt[(dc + 2 * j) * kVStr + pos] = (uint16_t)(rv[e][j] & 0xffffu);
+                vt[(dc + 2 * j + 1) * kVStr + pos] = (uint16_t)(rv[e][j] >> 16);
+            }
+        }
+    };
+
+    const int n_tiles = (k_end - k_begin + kKT - 1) / kKT;
+    issue_loads(k_begin);
+    store_tile(0);
+    __syncthreads();
+    for (int it = 0; it < n_tiles; ++it) {
+        const int buf = it & 1;
+        const int t0 = k_begin + it * kKT;
+        if (it + 1 < n_tiles) issue_loads(t0 + kKT);
+        const uint16_t* kt = lds + buf * kTileElems;
+        const uint16_t* vt = kt + kKT * kKStr;
+        const bool need_mask = t0 + kKT > ctx;  // uniform: tile touches the masked region or the tail
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            if (!tile_on[t]) continue;  // wave-uniform
+            // S^T for 4 sub-tiles of 16 keys
+            f32x4_t sc[4];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                sc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                const uint16_t* kp = kt + (st * 16 + l16) * kKStr + g4 * 8;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + ks * 32));
+                    bf16x8_t bq = __builtin_bit_cast(bf16x8_t, qf[t][ks]);
+                    sc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq, sc[st], 0, 0, 0);
+                }
+            }
+            // scale, mask, running max
+            float tmax = kNegBig;
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float x = sc[st][v] * scale_log2;
+                    if (need_mask) {
+                        const int key = t0 + st * 16 + g4 * 4 + v;
+                        bool vis = row_i[t] >= 0 && key < k_end;
+                        if (vis && key >= ctx) {
+                            const int j = key - ctx;
+                            vis = j < 64 ? ((mk0[t] >> j) & 1ull) : (j < 128 ? ((mk1[t] >> (j - 64)) & 1ull) : false);
+                        }
+                        x = vis ? x : kNegBig;
+                    }
+                    sc[st][v] = x;
+                    tmax = fmaxf(tmax, x);
+                }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run[t], tmax);
+            const float alpha = exp2f(m_run[t] - m_new);
+            m_run[t] = m_new;
+            float psum = 0.f;
+            uint32_t pk[4][2];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                float p[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = sc[st][v];
+                    p[v] = x <= kNegBig ? 0.f : exp2f(x - m_new);
+                    psum += p[v];
+                }
+                pk[st][0] = pack_bf16x2(p[0], p[1]);
+                pk[st][1] = pack_bf16x2(p[2], p[3]);
+            }
+            l_run[t] = l_run[t] * alpha + psum;
+            if (alpha != 1.0f) {
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
+            }
+            // O^T += V^T P^T, two k-steps of 32 keys
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                u32x4_t pb = {pk[2 * half][0], pk[2 * half][1], pk[2 * half + 1][0], pk[2 * half + 1][1]};
+                bf16x8_t bp = __builtin_bit_cast(bf16x8_t, pb);
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) {
+                    bf16x8_t a = __builtin_bit_cast(
+                        bf16x8_t, *(const u32x4_t*)(vt + (dt * 16 + l16) * kVStr + half * 32 + g4 * 8));
+                    acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bp, acc[t][dt], 0, 0, 0);
+                }
+            }
+        }
+        if (it + 1 < n_tiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- partial results: part_o [B][n_kv][n_chunks][r_pad][128], part_ml [..][r_pad][2]
+    const int64_t pbase = (((int64_t)b * kv.n_kv + kh) * n_chunks + chunk) * r_pad;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        if (!tile_on[t]) continue;
+        const int tile = rg * tiles_per_group + wave + 8 * t;
+        const int r = tile * 16 + l16;
+        float l = l_run[t];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        float* po = part_o + (pbase + r) * kD;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(po + dt * 16 + g4 * 4) = acc[t][dt];
+        if (g4 == 0) {
+            part_ml[(pbase + r) * 2] = m_run[t];
+            part_ml[(pbase + r) * 2 + 1] = l;
+        }
+    }
+}
+
+// One wave per (b, kv head, row): merges the chunks' partial outputs (base-2 running max).
+__global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
+                                                     const float* __restrict__ part_ml, uint16_t* __restrict__ out,
+                                                     int n_q_heads, int ck, int n_chunks, int r_pad) {
+    const int r = blockIdx.x, kh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    const int G = n_q_heads / kv.n_kv;
+    const int i = r / G, gq = r - i * G;
+    const int n = rows.n;
+    const int nv = rows.n_valid ? min(rows.n_valid[b], n) : n;
+    uint32_t* o = (uint32_t*)(out + ((int64_t)(b * n + i) * n_q_heads + kh * G + gq) * kD);
+    if (i >= nv) {
+        o[lane] = 0u;
+        return;
+    }
+    const int total = kv.seq_len[b] + rows.n_region;
+    int used = (total + ck - 1) / ck;
+    if (used > n_chunks) used = n_chunks;
+    const int64_t pbase = ((int64_t)b * kv.n_kv + kh) * n_chunks * r_pad + r;
+    float M = kNegBig;
+    for (int c = 0; c < used; ++c) M = fmaxf(M, part_ml[(pbase + (int64_t)c * r_pad) * 2]);
+    float a0 = 0.f, a1 = 0.f, L = 0.f;
+    for (int c = 0; c < used; ++c) {
+        const int64_t pr = pbase + (int64_t)c * r_pad;
+        const float w = exp2f(part_ml[pr * 2] - M);
+        L += part_ml[pr * 2 + 1] * w;
+        const float2 v = *(const float2*)(part_o + pr * kD + lane * 2);
+        a0 += v.x * w;
+        a1 += v.y * w;
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    o[lane] = pack_bf16x2(a0 * inv, a1 * inv);
+}
+
 size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx) {
-    (void)B; (void)n; (void)n_q_heads; (void)n_kv_heads; (void)d; (void)max_ctx;
-    return 256;
+    (void)max_ctx;
+    if (d != kD) return 256;
+    const int G = n_q_heads / n_kv_heads;
+    const size_t r_pad = (size_t)((n * G + 15) / 16) * 16;
+    const size_t pairs = (size_t)B * n_kv_heads;
+    const size_t wg = (pairs > 768 ? pairs : 768) + pairs;  // pairs * n_chunks never exceeds this
+    return wg * r_pad * (kD + 2) * sizeof(float) + 256;
+}
+
+template <int TPW>
+static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
+                                   int n_q_heads, const AttnPlan& p, float* part_o, float* part_ml) {
+    const size_t lds = (size_t)2 * kTileElems * sizeof(uint16_t);
+    auto kern = attn_mfma_k<TPW>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)kD);
+    dim3 grid(p.n_chunks, kv.n_kv * p.row_groups, rows.B), block(512);
+    hipLaunchKernelGGL(kern, grid, block, lds, s, rows, kv, (const uint16_t*)qkv, part_o, part_ml, n_q_heads, p.ck,
+                       p.n_chunks, p.row_tiles, tiles_per_group, p.r_pad, scale_log2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int R = rows.n * (n_q_heads / kv.n_kv);
+    hipLaunchKernelGGL(attn_combine_k, dim3(R, kv.n_kv, rows.B), dim3(64), 0, s, rows, kv, part_o, part_ml,
+                       (uint16_t*)out, n_q_heads, p.ck, p.n_chunks, p.r_pad);
+    return hipGetLastError();
 }
 
 hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
                      int n_q_heads, void* ws, size_t ws_bytes, int impl) {
-    (void)ws; (void)ws_bytes; (void)impl;
     if (rows.B * rows.n <= 0) return hipSuccess;
     if (kv.d % 64 != 0 || kv.d > 256) return hipErrorInvalidValue;
+    const int G = n_q_heads / kv.n_kv;
+    const bool mfma_ok = dtype == BF16 && kv.d == kD && rows.n_region <= 128 && kv.page_size == 16;
+    if (mfma_ok && impl != 0) {
+        const AttnPlan p = plan_attention(rows.B, rows.n, G, kv.n_kv, kv.seq_len_bound + rows.n_region);
+        const size_t need = (size_t)rows.B * kv.n_kv * p.n_chunks * p.r_pad * (kD + 2) * sizeof(float);
+        if (need <= ws_bytes) {
+            float* part_o = (float*)ws;
+            float* part_ml = part_o + (size_t)rows.B * kv.n_kv * p.n_chunks * p.r_pad * kD;
+            switch (p.tpw) {
+                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
+                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
+                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
+            }
+        }
+        if (impl == 1) return hipErrorInvalidValue;  // explicitly requested but the workspace cannot hold it
+    }
     float scale = 1.0f / sqrtf((float)kv.d);
     dim3 grid(rows.n, n_q_heads, rows.B), block(64);
     if (dtype == F32)

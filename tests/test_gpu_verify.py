@@ -6,7 +6,11 @@ import torch
 from oracle import decoder as dec
 from oracle import sd
 from paper_2511_16665_amd import binding as tlt
+import dataclasses
+
 from synth import MID, TINY, fill_kv_pool
+
+MID7 = dataclasses.replace(MID, name="mid-g7", n_q_heads=14, n_layers=2)   # 7 query heads per kv head, as in the 7B shape
 
 from gpu_util import dense_cache, make_engine, make_models, rel_err
 
@@ -21,14 +25,18 @@ def _random_tree(rng, n, vocab):
     return sd.Tree(rng.integers(0, vocab, size=n), parent, depth, np.zeros(n))
 
 
-@pytest.mark.parametrize("cfg,dtype,tol,n,ctxs,std", [
-    (TINY, "fp32", 1e-4, 13, [0, 37, 150], 0.02),
-    (TINY, "fp32", 1e-4, 64, [1, 200], 0.1),
-    (TINY, "fp32", 1e-4, 1, [5, 64], 0.02),           # N = 1: plain decode
-    (MID, "bf16", 2e-2, 13, [0, 37, 150], 0.02),
-    (MID, "bf16", 2e-2, 48, [300, 1100, 17], 0.02),   # several attention tiles / GEMM tiles, ragged
+@pytest.mark.parametrize("cfg,dtype,tol,n,ctxs,std,impl", [
+    (TINY, "fp32", 1e-4, 13, [0, 37, 150], 0.02, -1),
+    (TINY, "fp32", 1e-4, 64, [1, 200], 0.1, -1),
+    (TINY, "fp32", 1e-4, 1, [5, 64], 0.02, -1),           # N = 1: plain decode
+    (MID, "bf16", 2e-2, 13, [0, 37, 150], 0.02, 0),       # wave-per-row attention in bf16
+    (MID, "bf16", 2e-2, 13, [0, 37, 150], 0.02, 1),       # MFMA attention, 1 row tile per wave
+    (MID, "bf16", 2e-2, 48, [300, 1100, 17], 0.02, 1),    # several key chunks / GEMM tiles, ragged
+    (MID, "bf16", 2e-2, 1, [63, 64, 65, 1000], 0.02, 1),  # N = 1 on page and tile boundaries
+    (MID7, "bf16", 2e-2, 48, [700, 90], 0.02, 1),         # 336 query rows per kv head: 3 row tiles per wave
+    (MID7, "bf16", 2e-2, 64, [2100, 5], 0.05, 1),         # 448 rows: two row groups
 ])
-def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std):
+def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std, impl):
     rng = np.random.default_rng(n)
     B = len(ctxs)
     ctxs = np.array(ctxs, dtype=np.int32)
@@ -45,6 +53,7 @@ def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std):
     t.parent.copy_(torch.tensor(np.stack([tr.parent for tr in trees]), dtype=torch.int32))
     print(f"verify {cfg.name} {dtype} n={n} ctx={list(ctxs)}", flush=True)
     e.ctx.tree_finalize(B, t)
+    e.ctx.set_attention_impl(impl)
     logits = torch.zeros((B, n, cfg.vocab), dtype=torch.float32, device="cuda")
     hidden = torch.zeros((B, n, cfg.hidden), dtype=torch.float32, device="cuda")
     argmax = torch.zeros((B, n), dtype=torch.int32, device="cuda")
