@@ -24,7 +24,7 @@ struct ProfRec {
 
 struct Plan {  // byte offsets into the workspace
     size_t x, xn, qkv, att, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
-        pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, total;
+        pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, total;
     size_t attn_ws_bytes;
     int max_rows, pool_cap, feat_rows;
 };
@@ -72,6 +72,7 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.attn_ws_bytes = attention_workspace_bytes(B, std::max(n, K), c.n_q_heads, c.n_kv_heads, c.head_dim, max_ctx);
     p.attn_ws = take(p.attn_ws_bytes);
     p.accept_ws = take(accept_sample_workspace_bytes(B, c.vocab));
+    p.topk_ws = take(row_topk_workspace_bytes(B * K, c.vocab, K));
     p.total = o;
     return true;
 }
@@ -414,7 +415,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * (4 + e),
             rmsnorm(s, dt, B, h, feat, ctx->target.final_norm, c.rms_eps, ws + p.xn, row_map));
     if ((rc = run_gemm(ctx, s, OUT_F32, B, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * V * 4, row_topk_logp(s, B, V, topk, logits, top_tok, top_logp));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * V * 4, row_topk_logp(s, B, V, topk, logits, top_tok, top_logp, ws + p.topk_ws));
     TLT_RUN(ctx, s, CLS_OTHER, 0, 0, draft_level0(s, B, topk, top_tok, top_logp, st, FR));
 
     for (int level = 1; level < depth; ++level) {
@@ -437,7 +438,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
                 rmsnorm(s, dt, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
         if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_topk_logp(s, M, V, topk, logits, top_tok, top_logp));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_topk_logp(s, M, V, topk, logits, top_tok, top_logp, ws + p.topk_ws));
         TLT_RUN(ctx, s, CLS_OTHER, 0, 0, draft_level_select(s, B, topk, level, top_tok, top_logp, st, FR));
     }
     TLT_RUN(ctx, s, CLS_OTHER, 0, 0,

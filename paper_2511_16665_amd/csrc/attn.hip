@@ -122,6 +122,7 @@ constexpr int kKStr = 136;    // LDS row stride of the K tile (elements): 272 B,
 constexpr int kVStr = 72;     // LDS row stride of the V^T tile (elements)
 constexpr int kTileElems = kKT * kKStr + kD * kVStr;
 constexpr float kNegBig = -1e30f;
+constexpr int kMaxChunk = 4096;  // keys per chunk: bounds the page-id table kept in LDS
 
 struct AttnPlan {
     int ck;          // keys per chunk (multiple of 64)
@@ -135,11 +136,12 @@ struct AttnPlan {
 static AttnPlan plan_attention(int B, int n, int G, int n_kv, int bound_total) {
     AttnPlan p;
     const int pairs = B * n_kv;
-    int target = 768 / (pairs > 0 ? pairs : 1);
+    int target = 1536 / (pairs > 0 ? pairs : 1);
     if (target < 1) target = 1;
     int ck = (bound_total + target - 1) / target;
     ck = ((ck + 63) / 64) * 64;
     if (ck < 256) ck = 256;
+    if (ck > kMaxChunk) ck = kMaxChunk;
     p.ck = ck;
     p.n_chunks = (bound_total + ck - 1) / ck;
     if (p.n_chunks < 1) p.n_chunks = 1;
@@ -221,6 +223,19 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     // tile: key q / 16, d-chunk q % 16
     const uint16_t* kpool = (const uint16_t*)kv.k;
     const uint16_t* vpool = (const uint16_t*)kv.v;
+    // page ids of this chunk, range-checked once (-1 = not backed: those keys read as zeros and are
+    // never visible because they lie beyond `total` only when the block table is too short)
+    int32_t* page_ids = (int32_t*)(lds + 2 * kTileElems);
+    {
+        const int first_page = k_begin / kv.page_size;
+        const int n_pg = (k_end - 1) / kv.page_size - first_page + 1;
+        for (int pi = tid; pi < n_pg; pi += 512) {
+            const int lp = first_page + pi;
+            int pg = lp < kv.max_pages ? kv.block_table[(int64_t)b * kv.max_pages + lp] : -1;
+            page_ids[pi] = (pg >= 0 && pg < kv.n_pages) ? pg : -1;
+        }
+    }
+    __syncthreads();
     u32x4_t rk[2], rv[2];
     auto issue_loads = [&](int t0) {
 #pragma unroll
@@ -230,11 +245,13 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             u32x4_t z = {0u, 0u, 0u, 0u};
             rk[e] = z;
             rv[e] = z;
-            PageRef pr;
-            if (key < k_end && locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, key, pr)) {
-                const int64_t off = ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * kD + dc;
-                rk[e] = *(const u32x4_t*)(kpool + off);
-                rv[e] = *(const u32x4_t*)(vpool + off);
+            if (key < k_end) {
+                const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
+                if (pg >= 0) {
+                    const int64_t off = (((int64_t)pg * kv.n_kv + kh) * 16 + (key & 15)) * kD + dc;
+                    rk[e] = *(const u32x4_t*)(kpool + off);
+                    rv[e] = *(const u32x4_t*)(vpool + off);
+                }
             }
         }
     };
@@ -247,8 +264,11 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             const int key = q >> 4, dc = (q & 15) * 8;
             *(u32x4_t*)(kt + key * kKStr + dc) = rk[e];
             // V^T with the k-slot permutation inside each 32-key group
+            // plus an XOR of the 8-slot group index with (d / 8) % 8, which spreads the 2-byte
+            // writes of a wave (16 different d-chunks) over the banks
             const int grp = key >> 5, kk = key & 31;
-            const int pos = grp * 32 + ((kk & 15) >> 2) * 8 + (kk >> 4) * 4 + (kk & 3);
+            const int g8 = (grp * 4 + ((kk & 15) >> 2)) ^ ((dc >> 3) & 7);
+            const int pos = g8 * 8 + (kk >> 4) * 4 + (kk & 3);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 vt[(dc + 2 * j) * kVStr + pos] = (uint16_t)(rv[e][j] & 0xffffu);
@@ -284,13 +304,14 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                     sc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq, sc[st], 0, 0, 0);
                 }
             }
-            // scale, mask, running max
+            // mask (region / tail tiles only), running max on the raw scores; the softmax scale is
+            // folded into the exponent: p = exp2(s * c - m * c)
             float tmax = kNegBig;
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    float x = sc[st][v] * scale_log2;
+                    float x = sc[st][v];
                     if (need_mask) {
                         const int key = t0 + st * 16 + g4 * 4 + v;
                         bool vis = row_i[t] >= 0 && key < k_end;
@@ -299,14 +320,15 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                             vis = j < 64 ? ((mk0[t] >> j) & 1ull) : (j < 128 ? ((mk1[t] >> (j - 64)) & 1ull) : false);
                         }
                         x = vis ? x : kNegBig;
+                        sc[st][v] = x;
                     }
-                    sc[st][v] = x;
                     tmax = fmaxf(tmax, x);
                 }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
             const float m_new = fmaxf(m_run[t], tmax);
-            const float alpha = exp2f(m_run[t] - m_new);
+            const float alpha = exp2f((m_run[t] - m_new) * scale_log2);
+            const float mc = m_new * scale_log2;
             m_run[t] = m_new;
             float psum = 0.f;
             uint32_t pk[4][2];
@@ -316,8 +338,10 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const float x = sc[st][v];
-                    p[v] = x <= kNegBig ? 0.f : exp2f(x - m_new);
-                    psum += p[v];
+                    float e = exp2f(fmaf(x, scale_log2, -mc));
+                    if (need_mask) e = x <= kNegBig ? 0.f : e;
+                    p[v] = e;
+                    psum += e;
                 }
                 pk[st][0] = pack_bf16x2(p[0], p[1]);
                 pk[st][1] = pack_bf16x2(p[2], p[3]);
@@ -334,8 +358,8 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                 bf16x8_t bp = __builtin_bit_cast(bf16x8_t, pb);
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
-                    bf16x8_t a = __builtin_bit_cast(
-                        bf16x8_t, *(const u32x4_t*)(vt + (dt * 16 + l16) * kVStr + half * 32 + g4 * 8));
+                    const int g8 = (half * 4 + g4) ^ ((2 * dt + (l16 >> 3)) & 7);
+                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(vt + (dt * 16 + l16) * kVStr + g8 * 8));
                     acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bp, acc[t][dt], 0, 0, 0);
                 }
             }
@@ -364,10 +388,10 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     }
 }
 
-// One wave per (b, kv head, row): merges the chunks' partial outputs (base-2 running max).
+// One wave per (b, kv head, row): merges the chunks' partial outputs (running max in raw score units).
 __global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
                                                      const float* __restrict__ part_ml, uint16_t* __restrict__ out,
-                                                     int n_q_heads, int ck, int n_chunks, int r_pad) {
+                                                     int n_q_heads, int ck, int n_chunks, int r_pad, float scale_log2) {
     const int r = blockIdx.x, kh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
     const int G = n_q_heads / kv.n_kv;
     const int i = r / G, gq = r - i * G;
@@ -387,7 +411,7 @@ __global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, cons
     float a0 = 0.f, a1 = 0.f, L = 0.f;
     for (int c = 0; c < used; ++c) {
         const int64_t pr = pbase + (int64_t)c * r_pad;
-        const float w = exp2f(part_ml[pr * 2] - M);
+        const float w = exp2f((part_ml[pr * 2] - M) * scale_log2);
         L += part_ml[pr * 2 + 1] * w;
         const float2 v = *(const float2*)(part_o + pr * kD + lane * 2);
         a0 += v.x * w;
@@ -398,19 +422,20 @@ __global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, cons
 }
 
 size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx) {
-    (void)max_ctx;
     if (d != kD) return 256;
     const int G = n_q_heads / n_kv_heads;
     const size_t r_pad = (size_t)((n * G + 15) / 16) * 16;
     const size_t pairs = (size_t)B * n_kv_heads;
-    const size_t wg = (pairs > 768 ? pairs : 768) + pairs;  // pairs * n_chunks never exceeds this
+    const size_t by_target = (pairs > 1536 ? pairs : 1536) + pairs;          // chunk length from the target count
+    const size_t by_cap = pairs * (size_t)((max_ctx + kMaxChunk - 1) / kMaxChunk + 1);  // chunk length capped
+    const size_t wg = by_target > by_cap ? by_target : by_cap;               // pairs * n_chunks never exceeds this
     return wg * r_pad * (kD + 2) * sizeof(float) + 256;
 }
 
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
                                    int n_q_heads, const AttnPlan& p, float* part_o, float* part_ml) {
-    const size_t lds = (size_t)2 * kTileElems * sizeof(uint16_t);
+    const size_t lds = (size_t)2 * kTileElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t);
     auto kern = attn_mfma_k<TPW>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -427,7 +452,7 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     if (e != hipSuccess) return e;
     const int R = rows.n * (n_q_heads / kv.n_kv);
     hipLaunchKernelGGL(attn_combine_k, dim3(R, kv.n_kv, rows.B), dim3(64), 0, s, rows, kv, part_o, part_ml,
-                       (uint16_t*)out, n_q_heads, p.ck, p.n_chunks, p.r_pad);
+                       (uint16_t*)out, n_q_heads, p.ck, p.n_chunks, p.r_pad, scale_log2);
     return hipGetLastError();
 }
 

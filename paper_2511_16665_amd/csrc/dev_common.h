@@ -29,8 +29,12 @@ __device__ __forceinline__ bf16 from_float<bf16>(float x) {  // round to nearest
     return bf16{(uint16_t)(u >> 16)};
 }
 
+// Two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950).
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)from_float<bf16>(lo).bits | ((uint32_t)from_float<bf16>(hi).bits << 16);
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 __device__ __forceinline__ float wave_max(float v) {

@@ -67,7 +67,8 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
 // ---- sample.hip
 hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
 // per row: log-softmax statistics and the K best (token, log-prob) pairs, best first.
-hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp);
+size_t row_topk_workspace_bytes(int M, int V, int K);
+hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp, void* ws);
 
 struct DraftState {  // device arrays owned by the workspace; P = pool capacity per sequence
     int P = 0;

@@ -79,36 +79,51 @@ __global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restri
     if (threadIdx.x == 0) out[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
 }
 
-// One workgroup per row: max, log-sum-exp, then K rounds of "best element after the previous
-// winner" in the (value desc, index asc) order.  The row (<= 600 KB) is re-read from L2.
-__global__ __launch_bounds__(256) void row_topk_logp_k(int V, int K, const float* __restrict__ logits,
-                                                       int32_t* __restrict__ tok, float* __restrict__ logp) {
+// Log-softmax statistics and the K best tokens of every logits row, in two kernels.
+// (1) One workgroup per (row, segment of kTopkSeg logits): the segment is staged in LDS once, then
+//     its max, its sum of exponentials and its K best entries ("best element after the previous
+//     winner" in the (value desc, index asc) order, K rounds over LDS) are written out.
+// (2) One wave per row merges the segments: the K best of the union of the per-segment lists are
+//     the K best of the row because the order is total.
+constexpr int kTopkSeg = 8192;
+
+__global__ __launch_bounds__(256) void row_topk_seg_k(int V, int K, int n_seg, const float* __restrict__ logits,
+                                                      float* __restrict__ seg_stat, float* __restrict__ seg_val,
+                                                      int32_t* __restrict__ seg_idx) {
+    __shared__ float buf[kTopkSeg];
     __shared__ float sv[4];
     __shared__ int si[4];
-    const float* row = logits + (int64_t)blockIdx.x * V;
+    const int row = blockIdx.y, seg = blockIdx.x;
+    const int j0 = seg * kTopkSeg, len = min(kTopkSeg, V - j0);
+    const float* src = logits + (int64_t)row * V + j0;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int j = threadIdx.x; j < V; j += 256) {
-        float v = row[j];
+    for (int j = threadIdx.x; j < len; j += 256) {
+        float v = src[j];
+        buf[j] = v;
         if (better(v, j, bv, bi)) {
             bv = v;
             bi = j;
         }
     }
-    block_best(bv, bi, sv, si);
+    block_best(bv, bi, sv, si);  // includes the barriers that publish buf
     const float mx = bv;
     float se = 0.f;
-    for (int j = threadIdx.x; j < V; j += 256) se += expf(row[j] - mx);
+    for (int j = threadIdx.x; j < len; j += 256) se += expf(buf[j] - mx);
     se = block_sum_f(se, sv);
-    const float lse = mx + logf(se);
+    const int64_t o = (int64_t)row * n_seg + seg;
+    if (threadIdx.x == 0) {
+        seg_stat[2 * o] = mx;
+        seg_stat[2 * o + 1] = se;
+    }
     float pv = bv;
     int pi = bi;
     for (int k = 0; k < K; ++k) {
         if (k > 0) {
             float cv = -INFINITY;
             int ci = 0x7fffffff;
-            for (int j = threadIdx.x; j < V; j += 256) {
-                float v = row[j];
+            for (int j = threadIdx.x; j < len; j += 256) {
+                float v = buf[j];
                 bool after = v < pv || (v == pv && j > pi);
                 if (after && better(v, j, cv, ci)) {
                     cv = v;
@@ -121,8 +136,55 @@ __global__ __launch_bounds__(256) void row_topk_logp_k(int V, int K, const float
         }
         if (threadIdx.x == 0) {
             bool have = pi != 0x7fffffff;
-            tok[(int64_t)blockIdx.x * K + k] = have ? pi : -1;
-            logp[(int64_t)blockIdx.x * K + k] = have ? pv - lse : -INFINITY;
+            seg_val[o * K + k] = have ? pv : -INFINITY;
+            seg_idx[o * K + k] = have ? j0 + pi : 0x7fffffff;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void row_topk_merge_k(int K, int n_seg, const float* __restrict__ seg_stat,
+                                                       const float* __restrict__ seg_val,
+                                                       const int32_t* __restrict__ seg_idx, int32_t* __restrict__ tok,
+                                                       float* __restrict__ logp) {
+    const int row = blockIdx.x, lane = threadIdx.x;
+    const int64_t o = (int64_t)row * n_seg;
+    float mx = -INFINITY;
+    for (int sgm = lane; sgm < n_seg; sgm += 64) mx = fmaxf(mx, seg_stat[2 * (o + sgm)]);
+    mx = wave_max(mx);
+    float se = 0.f;
+    for (int sgm = lane; sgm < n_seg; sgm += 64) se += seg_stat[2 * (o + sgm) + 1] * expf(seg_stat[2 * (o + sgm)] - mx);
+    se = wave_sum(se);
+    const float lse = mx + logf(se);
+    const int n_cand = n_seg * K;
+    float pv = INFINITY;
+    int pi = -1;
+    for (int k = 0; k < K; ++k) {
+        float cv = -INFINITY;
+        int ci = 0x7fffffff;
+        for (int c = lane; c < n_cand; c += 64) {
+            float v = seg_val[o * K + c];
+            int j = seg_idx[o * K + c];
+            bool after = v < pv || (v == pv && j > pi);
+            if (j != 0x7fffffff && after && better(v, j, cv, ci)) {
+                cv = v;
+                ci = j;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            float ov = __shfl_xor(cv, off, 64);
+            int oi = __shfl_xor(ci, off, 64);
+            if (better(ov, oi, cv, ci)) {
+                cv = ov;
+                ci = oi;
+            }
+        }
+        pv = cv;
+        pi = ci;
+        if (lane == 0) {
+            bool have = ci != 0x7fffffff;
+            tok[(int64_t)row * K + k] = have ? ci : -1;
+            logp[(int64_t)row * K + k] = have ? cv - lse : -INFINITY;
         }
     }
 }
@@ -528,9 +590,21 @@ hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t*
     return hipGetLastError();
 }
 
-hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp) {
+size_t row_topk_workspace_bytes(int M, int V, int K) {
+    const size_t n_seg = (size_t)(V + kTopkSeg - 1) / kTopkSeg;
+    return (size_t)M * n_seg * (2 + 2 * (size_t)K) * 4 + 256;
+}
+
+hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp, void* ws) {
     if (M <= 0) return hipSuccess;
-    hipLaunchKernelGGL(row_topk_logp_k, dim3(M), dim3(256), 0, s, V, K, logits, tok, logp);
+    const int n_seg = (V + kTopkSeg - 1) / kTopkSeg;
+    float* seg_stat = (float*)ws;
+    float* seg_val = seg_stat + (size_t)M * n_seg * 2;
+    int32_t* seg_idx = (int32_t*)(seg_val + (size_t)M * n_seg * K);
+    hipLaunchKernelGGL(row_topk_seg_k, dim3(n_seg, M), dim3(256), 0, s, V, K, n_seg, logits, seg_stat, seg_val, seg_idx);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(row_topk_merge_k, dim3(M), dim3(64), 0, s, K, n_seg, seg_stat, seg_val, seg_idx, tok, logp);
     return hipGetLastError();
 }
 
