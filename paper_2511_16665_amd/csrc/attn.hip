@@ -95,21 +95,21 @@ __global__ __launch_bounds__(64) void attn_wave_per_row_k(Rows rows, KVLayer kv,
 // impl 1 ("MFMA split-KV"), bf16, head_dim 128.
 //
 // One workgroup (8 waves, two per SIMD) owns (sequence b, kv head, chunk of CK keys, group of
-// query-row tiles).
-// All G query heads of the kv head and all tree rows form the row set R = n*G, row r = i*G + g, cut
-// into tiles of 16 rows dealt round-robin to the waves; a wave keeps its tiles' Q fragments and
-// fp32 output accumulators in registers and the whole workgroup streams the chunk's K/V pages once
-// through LDS in tiles of 64 keys (global -> registers -> LDS, next tile's loads issued before the
-// current tile's MFMAs).
+// query-row tiles).  All G query heads of the kv head and all tree rows form the row set R = n*G,
+// row r = i*G + g, cut into tiles of 16 rows dealt round-robin to the waves; a wave keeps its tiles'
+// Q fragments and fp32 output accumulators in registers and the whole workgroup streams the chunk's
+// K/V pages once through a 4-stage LDS ring in tiles of 64 keys, filled by direct global->LDS loads
+// issued three tiles ahead.
 //
 // Both products run on v_mfma_f32_16x16x32_bf16 in the transposed orientation:
 //   S^T[key][row] = sum_d K[key][d] Q[row][d]      A = K rows from LDS, B = Q fragment
-//   O^T[d][row]  += sum_key V^T[d][key] P^T[key][row]   A = V^T from LDS, B = P packed from S^T
+//   O^T[d][row]  += sum_key V^T[d][key] P^T[key][row]   A = V^T read with the LDS transpose load,
+//                                                       B = P packed from S^T
 // In that orientation a lane's S^T results (4 consecutive keys of its own row l%16) are already the
-// k-slots the second product's B operand wants, so P never leaves registers; V is transposed once
-// per tile on its way into LDS, with the keys of each 32-key group permuted to the k-slot order
-// (key 16*sub + 4*g + v  ->  slot 8*g + 4*sub + v).  A lane's 32 accumulators all belong to one row,
-// so the online-softmax rescale is a per-lane scalar.
+// k-slots the second product's B operand wants, so P never leaves registers, and the k-slot order
+// (slot 4*sub + v of lane group g = key 16*sub + 4*g + v) is matched on the V side by which keys each
+// transpose load addresses.  A lane's 32 accumulators all belong to one row, so the online-softmax
+// rescale is a per-lane scalar.
 // Each workgroup writes unnormalised partial outputs with their running max and sum (fp32); a
 // second kernel merges the chunks.
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -118,9 +118,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 constexpr int kD = 128;       // head_dim of this kernel
 constexpr int kKT = 64;       // keys per LDS tile
-constexpr int kKStr = 136;    // LDS row stride of the K tile (elements): 272 B, rows shift by 16 B
-constexpr int kVStr = 72;     // LDS row stride of the V^T tile (elements)
-constexpr int kTileElems = kKT * kKStr + kD * kVStr;
+constexpr int kStages = 4;                  // LDS ring depth: three tiles of K/V in flight
+constexpr int kStageElems = 2 * kKT * kD;   // one stage: K tile then V tile, 16 KB each
 constexpr float kNegBig = -1e30f;
 constexpr int kMaxChunk = 4096;  // keys per chunk: bounds the page-id table kept in LDS
 
@@ -178,7 +177,6 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 
     // ---- this wave's row tiles: Q fragments, masks, accumulators
     u32x4_t qf[TPW][4];
-    uint64_t mk0[TPW], mk1[TPW];
     int row_i[TPW];
     bool tile_on[TPW];
 #pragma unroll
@@ -195,19 +193,6 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             u32x4_t z = {0u, 0u, 0u, 0u};
             qf[t][ks] = valid ? *(const u32x4_t*)(qp + ks * 32) : z;
         }
-        uint64_t m0 = 0, m1 = 0;
-        if (valid) {
-            if (rows.mask) {
-                const uint64_t* mp = rows.mask + (int64_t)(b * n + i) * rows.mask_words;
-                m0 = mp[0];
-                m1 = rows.mask_words > 1 ? mp[1] : 0ull;
-            } else {  // causal within the new rows
-                m0 = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
-                m1 = i < 64 ? 0ull : (i >= 127 ? ~0ull : ((2ull << (i - 64)) - 1ull));
-            }
-        }
-        mk0[t] = m0;
-        mk1[t] = m1;
     }
     f32x4_t acc[TPW][8];
     float m_run[TPW], l_run[TPW];
@@ -219,14 +204,19 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         for (int dt = 0; dt < 8; ++dt) acc[t][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- staging: thread handles 16-byte chunks q = tid + 512*e, e < 2, of the K tile and of the V
-    // tile: key q / 16, d-chunk q % 16
+    // ---- K/V tiles: a ring of kStages LDS stages, each [64 keys][128] for K then the same for V,
+    // filled by direct global->LDS loads.  One DMA instruction moves 4 keys (1 KB): lane -> key
+    // lane/16 of the block, 16-byte slot lane%16, and it fetches logical chunk slot ^ (key & 15), so a
+    // row's chunks are XOR-swizzled by its key index and both the 16-byte K fragment reads of 16
+    // consecutive keys and the transposing V reads spread over the banks.
     const uint16_t* kpool = (const uint16_t*)kv.k;
     const uint16_t* vpool = (const uint16_t*)kv.v;
-    // page ids of this chunk, range-checked once (-1 = not backed: those keys read as zeros and are
-    // never visible because they lie beyond `total` only when the block table is too short)
-    int32_t* page_ids = (int32_t*)(lds + 2 * kTileElems);
+    int32_t* page_ids = (int32_t*)(lds + kStages * kStageElems);
     {
+        // zero the ring once: slots whose DMA is skipped (unbacked pages) must hold finite values
+        u32x4_t z = {0u, 0u, 0u, 0u};
+        for (int e = tid; e < kStages * kStageElems / 8; e += 512) *(u32x4_t*)(lds + e * 8) = z;
+        // page ids of this chunk, range-checked once (-1 = not backed by the block table)
         const int first_page = k_begin / kv.page_size;
         const int n_pg = (k_end - 1) / kv.page_size - first_page + 1;
         for (int pi = tid; pi < n_pg; pi += 512) {
@@ -236,94 +226,92 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         }
     }
     __syncthreads();
-    u32x4_t rk[2], rv[2];
-    auto issue_loads = [&](int t0) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int q = tid + 512 * e;
-            const int key = t0 + (q >> 4), dc = (q & 15) * 8;
-            u32x4_t z = {0u, 0u, 0u, 0u};
-            rk[e] = z;
-            rv[e] = z;
-            if (key < k_end) {
-                const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
-                if (pg >= 0) {
-                    const int64_t off = (((int64_t)pg * kv.n_kv + kh) * 16 + (key & 15)) * kD + dc;
-                    rk[e] = *(const u32x4_t*)(kpool + off);
-                    rv[e] = *(const u32x4_t*)(vpool + off);
-                }
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        uint16_t* kt = lds + buf * kTileElems;
-        uint16_t* vt = kt + kKT * kKStr;
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int q = tid + 512 * e;
-            const int key = q >> 4, dc = (q & 15) * 8;
-            *(u32x4_t*)(kt + key * kKStr + dc) = rk[e];
-            // V^T with the k-slot permutation inside each 32-key group
-            // plus an XOR of the 8-slot group index with (d / 8) % 8, which spreads the 2-byte
-            // writes of a wave (16 different d-chunks) over the banks
-            const int grp = key >> 5, kk = key & 31;
-            const int g8 = (grp * 4 + ((kk & 15) >> 2)) ^ ((dc >> 3) & 7);
-            const int pos = g8 * 8 + (kk >> 4) * 4 + (kk & 3);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                vt[(dc + 2 * j) * kVStr + pos] = (uint16_t)(rv[e][j] & 0xffffu);
-                vt[(dc + 2 * j + 1) * kVStr + pos] = (uint16_t)(rv[e][j] >> 16);
-            }
-        }
-    };
-
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int n_tiles = (k_end - k_begin + kKT - 1) / kKT;
-    issue_loads(k_begin);
-    store_tile(0);
-    __syncthreads();
+    auto issue_dma = [&](int tile, int stage) {
+        uint16_t* sb = lds + stage * kStageElems;
+        const int t0 = k_begin + tile * kKT;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int blk = wave_u + 8 * e;                 // 4-key block of the tile
+            const int key_t = blk * 4 + (lane >> 4);        // key slot inside the tile
+            const int lc = (lane & 15) ^ (key_t & 15);      // logical 16-byte chunk this lane fetches
+            int key = t0 + key_t;
+            key = key < k_end ? key : k_end - 1;            // tail slots re-read the last key (masked later)
+            const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
+            const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (key & 15)) * kD + lc * 8;
+            if (pg >= 0) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kpool + off),
+                                                 (__attribute__((address_space(3))) void*)(sb + blk * 512), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vpool + off),
+                                                 (__attribute__((address_space(3))) void*)(sb + kKT * kD + blk * 512),
+                                                 16, 0, 0);
+            }
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < kStages - 1; ++st) issue_dma(st < n_tiles ? st : n_tiles - 1, st);
+
     for (int it = 0; it < n_tiles; ++it) {
-        const int buf = it & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70u | (4 * (kStages - 2)));  // vmcnt: this tile's 4 DMAs per wave have landed
+        __builtin_amdgcn_s_barrier();
+        {
+            const int nxt = it + kStages - 1;
+            issue_dma(nxt < n_tiles ? nxt : n_tiles - 1, nxt % kStages);
+        }
         const int t0 = k_begin + it * kKT;
-        if (it + 1 < n_tiles) issue_loads(t0 + kKT);
-        const uint16_t* kt = lds + buf * kTileElems;
-        const uint16_t* vt = kt + kKT * kKStr;
+        const uint16_t* kt = lds + (it % kStages) * kStageElems;
+        const uint16_t* vt = kt + kKT * kD;
         const bool need_mask = t0 + kKT > ctx;  // uniform: tile touches the masked region or the tail
+
+        // ---- per row tile: S^T = K Q^T (four 16-key sub-tiles), online softmax, P packed straight
+        // into the second product's B operand
+        u32x4_t pb[TPW][2];
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-            if (!tile_on[t]) continue;  // wave-uniform
-            // S^T for 4 sub-tiles of 16 keys
             f32x4_t sc[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                sc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                const uint16_t* kp = kt + (st * 16 + l16) * kKStr + g4 * 8;
+                const uint16_t* kp = kt + (st * 16 + l16) * kD;
+                f32x4_t a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + ks * 32));
-                    bf16x8_t bq = __builtin_bit_cast(bf16x8_t, qf[t][ks]);
-                    sc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq, sc[st], 0, 0, 0);
+                    bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, __builtin_bit_cast(bf16x8_t, qf[t][ks]), a, 0, 0, 0);
                 }
+                sc[st] = a;
             }
-            // mask (region / tail tiles only), running max on the raw scores; the softmax scale is
-            // folded into the exponent: p = exp2(s * c - m * c)
             float tmax = kNegBig;
+            if (need_mask) {  // region / tail tile: fetch this row's visibility bits (rare path)
+                uint64_t m0 = 0, m1 = 0;
+                const int i = row_i[t];
+                if (i >= 0) {
+                    if (rows.mask) {
+                        const uint64_t* mp = rows.mask + (int64_t)(b * n + i) * rows.mask_words;
+                        m0 = mp[0];
+                        m1 = rows.mask_words > 1 ? mp[1] : 0ull;
+                    } else {  // causal within the new rows
+                        m0 = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
+                        m1 = i < 64 ? 0ull : (i >= 127 ? ~0ull : ((2ull << (i - 64)) - 1ull));
+                    }
+                }
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int key = t0 + st * 16 + g4 * 4 + v;
+                        bool vis = i >= 0 && key < k_end;
+                        if (vis && key >= ctx) {
+                            const int jj = key - ctx;
+                            vis = jj < 64 ? ((m0 >> jj) & 1ull) : (jj < 128 ? ((m1 >> (jj - 64)) & 1ull) : false);
+                        }
+                        sc[st][v] = vis ? sc[st][v] : kNegBig;
+                    }
+            }
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float x = sc[st][v];
-                    if (need_mask) {
-                        const int key = t0 + st * 16 + g4 * 4 + v;
-                        bool vis = row_i[t] >= 0 && key < k_end;
-                        if (vis && key >= ctx) {
-                            const int j = key - ctx;
-                            vis = j < 64 ? ((mk0[t] >> j) & 1ull) : (j < 128 ? ((mk1[t] >> (j - 64)) & 1ull) : false);
-                        }
-                        x = vis ? x : kNegBig;
-                        sc[st][v] = x;
-                    }
-                    tmax = fmaxf(tmax, x);
-                }
+                for (int v = 0; v < 4; ++v) tmax = fmaxf(tmax, sc[st][v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
             const float m_new = fmaxf(m_run[t], tmax);
@@ -334,39 +322,54 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             uint32_t pk[4][2];
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                float p[4];
+                float pv[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const float x = sc[st][v];
                     float e = exp2f(fmaf(x, scale_log2, -mc));
                     if (need_mask) e = x <= kNegBig ? 0.f : e;
-                    p[v] = e;
+                    pv[v] = e;
                     psum += e;
                 }
-                pk[st][0] = pack_bf16x2(p[0], p[1]);
-                pk[st][1] = pack_bf16x2(p[2], p[3]);
+                pk[st][0] = pack_bf16x2(pv[0], pv[1]);
+                pk[st][1] = pack_bf16x2(pv[2], pv[3]);
             }
             l_run[t] = l_run[t] * alpha + psum;
             if (alpha != 1.0f) {
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
             }
-            // O^T += V^T P^T, two k-steps of 32 keys
+            pb[t][0] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
+            pb[t][1] = u32x4_t{pk[2][0], pk[2][1], pk[3][0], pk[3][1]};
+        }
+        // ---- O^T += V^T P^T.  V stays row-major in LDS; ds_read_b64_tr_b16 hands lane (l16, g4) the
+        // four keys 4*g4 .. 4*g4+3 of a 16-key sub-tile for head dimension 16*dt + l16: the 16 lanes of
+        // a group address a 4-key x 16-dim block (lane s -> key s/4, dims 4*(s%4) ..) and the
+        // instruction transposes it.  Two such reads (sub-tiles 2*half, 2*half+1) form the 8 k-slots.
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                u32x4_t pb = {pk[2 * half][0], pk[2 * half][1], pk[2 * half + 1][0], pk[2 * half + 1][1]};
-                bf16x8_t bp = __builtin_bit_cast(bf16x8_t, pb);
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) {
-                    const int g8 = (half * 4 + g4) ^ ((2 * dt + (l16 >> 3)) & 7);
-                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(vt + (dt * 16 + l16) * kVStr + g8 * 8));
-                    acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bp, acc[t][dt], 0, 0, 0);
+            for (int dt = 0; dt < 8; ++dt) {
+                typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+                s16x4_t vv[2];
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
+                    const int lcv = 2 * dt + ((l16 & 3) >> 1);
+                    const uint16_t* vp = vt + key_t * kD + ((lcv ^ (key_t & 15)) * 8) + (l16 & 1) * 4;
+                    vv[sub] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
                 }
+                typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+                s16x8_t v8 = {vv[0][0], vv[0][1], vv[0][2], vv[0][3], vv[1][0], vv[1][1], vv[1][2], vv[1][3]};
+                bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+                    acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8_t, pb[t][half]),
+                                                                         acc[t][dt], 0, 0, 0);
             }
         }
-        if (it + 1 < n_tiles) store_tile(buf ^ 1);
-        __syncthreads();
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70u);  // drain the redundant tail DMAs before the LDS is released
 
     // ---- partial results: part_o [B][n_kv][n_chunks][r_pad][128], part_ml [..][r_pad][2]
     const int64_t pbase = (((int64_t)b * kv.n_kv + kh) * n_chunks + chunk) * r_pad;
@@ -435,7 +438,7 @@ size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, in
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
                                    int n_q_heads, const AttnPlan& p, float* part_o, float* part_ml) {
-    const size_t lds = (size_t)2 * kTileElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t);
+    const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t);
     auto kern = attn_mfma_k<TPW>;
     static bool attr_set = false;
     if (!attr_set) {
