@@ -121,6 +121,7 @@ constexpr int kKT = 64;       // keys per LDS tile
 constexpr int kStages = 4;                  // LDS ring depth: three tiles of K/V in flight
 constexpr int kStageElems = 2 * kKT * kD;   // one stage: K tile then V tile, 16 KB each
 constexpr float kNegBig = -1e30f;
+constexpr int kMaxRows = 128;    // rows per sequence whose visibility bits are kept in LDS
 constexpr int kMaxChunk = 4096;  // keys per chunk: bounds the page-id table kept in LDS
 
 struct AttnPlan {
@@ -212,7 +213,23 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     const uint16_t* kpool = (const uint16_t*)kv.k;
     const uint16_t* vpool = (const uint16_t*)kv.v;
     int32_t* page_ids = (int32_t*)(lds + kStages * kStageElems);
+    uint64_t* mask_lds = (uint64_t*)(page_ids + kMaxChunk / 16 + 2);  // [n][2] visibility bits of this sequence's rows
     {
+        for (int i = tid; i < n; i += 512) {
+            uint64_t m0 = 0, m1 = 0;
+            if (i < nv) {
+                if (rows.mask) {
+                    const uint64_t* mp = rows.mask + (int64_t)(b * n + i) * rows.mask_words;
+                    m0 = mp[0];
+                    m1 = rows.mask_words > 1 ? mp[1] : 0ull;
+                } else {  // causal within the new rows
+                    m0 = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
+                    m1 = i < 64 ? 0ull : (i >= 127 ? ~0ull : ((2ull << (i - 64)) - 1ull));
+                }
+            }
+            mask_lds[2 * i] = m0;
+            mask_lds[2 * i + 1] = m1;
+        }
         // zero the ring once: slots whose DMA is skipped (unbacked pages) must hold finite values
         u32x4_t z = {0u, 0u, 0u, 0u};
         for (int e = tid; e < kStages * kStageElems / 8; e += 512) *(u32x4_t*)(lds + e * 8) = z;
@@ -228,8 +245,8 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     __syncthreads();
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int n_tiles = (k_end - k_begin + kKT - 1) / kKT;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
     auto issue_dma = [&](int tile, int stage) {
-        uint16_t* sb = lds + stage * kStageElems;
         const int t0 = k_begin + tile * kKT;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -241,17 +258,19 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
             const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (key & 15)) * kD + lc * 8;
             if (pg >= 0) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kpool + off),
-                                                 (__attribute__((address_space(3))) void*)(sb + blk * 512), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vpool + off),
-                                                 (__attribute__((address_space(3))) void*)(sb + kKT * kD + blk * 512),
-                                                 16, 0, 0);
+                const uint32_t dst = lds_base + (uint32_t)(stage * kStageElems + blk * 512) * 2u;
+                dma_global_to_lds_16(kpool + off, dst);
+                dma_global_to_lds_16(vpool + off, dst + kKT * kD * 2u);
             }
         }
     };
 #pragma unroll
     for (int st = 0; st < kStages - 1; ++st) issue_dma(st < n_tiles ? st : n_tiles - 1, st);
 
+    // Drain every load issued so far (Q fragments, table reads, the first DMAs) once, here, so that the
+    // compiler's own wait bookkeeping enters the loop clean and adds no vmcnt(0) of its own inside it,
+    // which would also drain the DMA queue on every tile.
+    __builtin_amdgcn_s_waitcnt(0x0F70u);
     for (int it = 0; it < n_tiles; ++it) {
         __builtin_amdgcn_s_waitcnt(0x0F70u | (4 * (kStages - 2)));  // vmcnt: this tile's 4 DMAs per wave have landed
         __builtin_amdgcn_s_barrier();
@@ -262,49 +281,57 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         const int t0 = k_begin + it * kKT;
         const uint16_t* kt = lds + (it % kStages) * kStageElems;
         const uint16_t* vt = kt + kKT * kD;
-        const bool need_mask = t0 + kKT > ctx;  // uniform: tile touches the masked region or the tail
+        // 1 for the tile(s) touching the tree region or the chunk's tail, else 0.  Used as the trip count
+        // of the masking loop below: a loop with a uniform run-time bound stays a real branch, whereas an
+        // `if` around this much select-able code gets flattened and would run on every tile.
+        const int mask_reps = t0 + kKT > ctx ? 1 : 0;
 
-        // ---- per row tile: S^T = K Q^T (four 16-key sub-tiles), online softmax, P packed straight
-        // into the second product's B operand
+        // ---- S^T = K Q^T: each K fragment is read once and feeds the TPW independent row tiles.  The
+        // LDS reads are issued in batches of 4 fragments ahead of the 4*TPW MFMAs that consume them, so
+        // one LDS latency is exposed per batch instead of one per fragment.
+        f32x4_t scs[TPW][4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            bf16x8_t kf[4];
+            const uint16_t* kp = kt + (st * 16 + l16) * kD;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                kf[ks] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+                    scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
+                                                                         scs[t][st], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
+        }
+        // ---- per row tile: online softmax, P packed straight into the second product's B operand
         u32x4_t pb[TPW][2];
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
             f32x4_t sc[4];
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const uint16_t* kp = kt + (st * 16 + l16) * kD;
-                f32x4_t a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, __builtin_bit_cast(bf16x8_t, qf[t][ks]), a, 0, 0, 0);
-                }
-                sc[st] = a;
-            }
+            for (int st = 0; st < 4; ++st) sc[st] = scs[t][st];
             float tmax = kNegBig;
-            if (need_mask) {  // region / tail tile: fetch this row's visibility bits (rare path)
+            for (int rep = 0; rep < mask_reps; ++rep) {  // region / tail tile only (see mask_reps)
                 uint64_t m0 = 0, m1 = 0;
                 const int i = row_i[t];
-                if (i >= 0) {
-                    if (rows.mask) {
-                        const uint64_t* mp = rows.mask + (int64_t)(b * n + i) * rows.mask_words;
-                        m0 = mp[0];
-                        m1 = rows.mask_words > 1 ? mp[1] : 0ull;
-                    } else {  // causal within the new rows
-                        m0 = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
-                        m1 = i < 64 ? 0ull : (i >= 127 ? ~0ull : ((2ull << (i - 64)) - 1ull));
-                    }
+                if (i >= 0) {  // from the LDS copy: no global load (and so no vmcnt wait) inside the loop
+                    m0 = mask_lds[2 * i];
+                    m1 = mask_lds[2 * i + 1];
                 }
 #pragma unroll
                 for (int st = 0; st < 4; ++st)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int key = t0 + st * 16 + g4 * 4 + v;
-                        bool vis = i >= 0 && key < k_end;
-                        if (vis && key >= ctx) {
-                            const int jj = key - ctx;
-                            vis = jj < 64 ? ((m0 >> jj) & 1ull) : (jj < 128 ? ((m1 >> (jj - 64)) & 1ull) : false);
-                        }
+                        const int jj = key - ctx;  // index into the masked region when >= 0
+                        const uint64_t w = jj < 64 ? m0 : m1;
+                        const bool bit = (w >> (jj & 63)) & 1ull;
+                        const bool vis = (i >= 0) & (key < k_end) & ((jj < 0) | (bit & (jj < 128)));
                         sc[st][v] = vis ? sc[st][v] : kNegBig;
                     }
             }
@@ -315,8 +342,9 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
             const float m_new = fmaxf(m_run[t], tmax);
-            const float alpha = exp2f((m_run[t] - m_new) * scale_log2);
-            const float mc = m_new * scale_log2;
+            const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2);
+            // the clamp keeps exp2(x*c - mc) = 0 for masked scores (-1e30) while no key has been visible yet
+            const float mc = fmaxf(m_new, -1e29f) * scale_log2;
             m_run[t] = m_new;
             float psum = 0.f;
             uint32_t pk[4][2];
@@ -326,8 +354,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const float x = sc[st][v];
-                    float e = exp2f(fmaf(x, scale_log2, -mc));
-                    if (need_mask) e = x <= kNegBig ? 0.f : e;
+                    float e = __builtin_amdgcn_exp2f(fmaf(x, scale_log2, -mc));
                     pv[v] = e;
                     psum += e;
                 }
@@ -348,27 +375,38 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         // instruction transposes it.  Two such reads (sub-tiles 2*half, 2*half+1) form the 8 k-slots.
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
+            typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+            typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-                s16x4_t vv[2];
+            for (int dq = 0; dq < 2; ++dq) {
+                s16x4_t vv[4][2];
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) {
-                    const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
-                    const int lcv = 2 * dt + ((l16 & 3) >> 1);
-                    const uint16_t* vp = vt + key_t * kD + ((lcv ^ (key_t & 15)) * 8) + (l16 & 1) * 4;
-                    vv[sub] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
+                for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub) {
+                        const int dt = dq * 4 + d4;
+                        const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
+                        const int lcv = 2 * dt + ((l16 & 3) >> 1);
+                        const uint16_t* vp = vt + key_t * kD + ((lcv ^ (key_t & 15)) * 8) + (l16 & 1) * 4;
+                        vv[d4][sub] =
+                            __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
+                    }
+#pragma unroll
+                for (int d4 = 0; d4 < 4; ++d4) {
+                    const int dt = dq * 4 + d4;
+                    s16x8_t v8 = {vv[d4][0][0], vv[d4][0][1], vv[d4][0][2], vv[d4][0][3],
+                                  vv[d4][1][0], vv[d4][1][1], vv[d4][1][2], vv[d4][1][3]};
+                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t)
+                        acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            a, __builtin_bit_cast(bf16x8_t, pb[t][half]), acc[t][dt], 0, 0, 0);
                 }
-                typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-                s16x8_t v8 = {vv[0][0], vv[0][1], vv[0][2], vv[0][3], vv[1][0], vv[1][1], vv[1][2], vv[1][3]};
-                bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
-#pragma unroll
-                for (int t = 0; t < TPW; ++t)
-                    acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8_t, pb[t][half]),
-                                                                         acc[t][dt], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // 8 transposing reads
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
             }
         }
-    }
+        }
     __builtin_amdgcn_s_waitcnt(0x0F70u);  // drain the redundant tail DMAs before the LDS is released
 
     // ---- partial results: part_o [B][n_kv][n_chunks][r_pad][128], part_ml [..][r_pad][2]
@@ -438,7 +476,9 @@ size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, in
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
                                    int n_q_heads, const AttnPlan& p, float* part_o, float* part_ml) {
-    const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t);
+    const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t) +
+                       (size_t)kMaxRows * 2 * sizeof(uint64_t);
+    if (rows.n > kMaxRows) return hipErrorInvalidValue;
     auto kern = attn_mfma_k<TPW>;
     static bool attr_set = false;
     if (!attr_set) {

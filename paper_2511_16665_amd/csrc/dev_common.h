@@ -48,6 +48,18 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// 16 bytes per lane from global memory straight into LDS at lds_byte_offset + lane * 16 (the offset
+// must be wave-uniform).  Issued through inline assembly on purpose: the compiler then does not
+// treat it as an LDS write it has to order against every later LDS read (which it does with a full
+// vmcnt(0) wait, i.e. by draining the whole prefetch queue); the kernels that use this wait
+// explicitly with s_waitcnt vmcnt(n) for exactly the stage they are about to read.
+__device__ __forceinline__ void dma_global_to_lds_16(const void* gptr, uint32_t lds_byte_offset) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_byte_offset)
+                 : "memory", "m0");
+}
+
 // (value, index) ordering used everywhere a "largest" element is picked:
 // larger value first, lower index on equal values.
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
