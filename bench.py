@@ -108,16 +108,17 @@ class _EmbedRows:
 
 
 def cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args):
-    """The oracle's SD step (as it stands in oracle/) for ONE sequence of the batch, the one with the
-    shortest context, with 2 of the target's decoder layers, timed on the host cores; the layer part
-    is scaled to the full depth.  Weight widening to float64 happens before the clock starts."""
+    """The oracle's SD step (as it stands in oracle/) for ONE sequence of the batch, the one whose
+    context is the batch median, with 4 of the target's decoder layers, timed on the host cores; the
+    layer part is scaled to the full depth.  Weight widening to float64 happens before the clock
+    starts.  Sized to about 10-30 s of CPU work."""
     import dataclasses
 
     from oracle import decoder as dec
     from oracle import sd
 
-    L_sample = min(2, cfg.n_layers)
-    b = int(np.argmin(ctx))
+    L_sample = min(4, cfg.n_layers)
+    b = int(np.argsort(ctx)[len(ctx) // 2])
     c = int(ctx[b])
     to64 = dec.weights_to_f64
     tw64 = {"embed": _EmbedRows(tw["embed"]), "lm_head": to64(tw["lm_head"]), "final_norm": to64(tw["final_norm"]),
