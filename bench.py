@@ -108,58 +108,76 @@ class _EmbedRows:
 
 
 def cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args):
-    """The oracle's SD step (as it stands in oracle/) for ONE sequence of the batch, the one whose
-    context is the batch median, with 4 of the target's decoder layers, timed on the host cores; the
-    layer part is scaled to the full depth.  Weight widening to float64 happens before the clock
-    starts.  Sized to about 10-30 s of CPU work."""
+    """The oracle's SD step (as it stands in oracle/) for EIGHT sequences of the batch (every fourth
+    one in order of context length, so the sample keeps the batch's length mix), one after another,
+    with 6 of the target's decoder layers, timed on the host cores; the layer part is scaled to the
+    full depth.  Weight widening to float64 happens before the clock starts.  Sized to about 10-30 s
+    of CPU work."""
     import dataclasses
 
     from oracle import decoder as dec
     from oracle import sd
 
-    L_sample = min(4, cfg.n_layers)
-    b = int(np.argsort(ctx)[len(ctx) // 2])
-    c = int(ctx[b])
+    L_sample = min(6, cfg.n_layers)
+    order = np.argsort(ctx)
+    picks = [int(order[i]) for i in range(len(order) // 16, len(order), max(len(order) // 8, 1))][:8]
     to64 = dec.weights_to_f64
     tw64 = {"embed": _EmbedRows(tw["embed"]), "lm_head": to64(tw["lm_head"]), "final_norm": to64(tw["final_norm"]),
             "layers": [to64(tw["layers"][l]) for l in range(L_sample)]}
     dw64 = to64(dw)
     small = dataclasses.replace(cfg, n_layers=L_sample)
-    st = sd.SeqState(small, c + args.verify + args.depth * args.topk + 16, dec.round_to_bf16)
-    for l in range(L_sample):
-        st.target[l].k[:c] = _gather_rows(e.kv.k_pool[l], table[b], c, cfg.page_size)
-        st.target[l].v[:c] = _gather_rows(e.kv.v_pool[l], table[b], c, cfg.page_size)
-    st.draft.k[:c] = _gather_rows(e.dkv.k_pool[0], dtable[b], c, cfg.page_size)
-    st.draft.v[:c] = _gather_rows(e.dkv.v_pool[0], dtable[b], c, cfg.page_size)
-    st.ctx = c
-    st.draft_len = c
     rng = np.random.default_rng(0)
-    t0 = time.perf_counter()
-    sd.draft_extend(small, tw64, dw64, st, [int(rng.integers(cfg.vocab))], rng.normal(size=(1, cfg.hidden)))
-    tree, _ = sd.draft_expand(small, tw64, dw64, st, 1, args.topk, args.depth, args.verify)
-    t_draft = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    logits, hidden = sd.verify(small, tw64, st, tree)
-    t_verify = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    dec.lm_logits(small, tw64, hidden)
-    t_head = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    a, path, out = sd.accept_greedy(tree, logits)
-    sd.commit(st, path)
-    t_tail = time.perf_counter() - t0
-    t_layers = max(t_verify - t_head, 0.0)
-    t_seq = t_draft + t_layers * cfg.n_layers / L_sample + t_head + t_tail
+    tokens, t_scaled, t_measured = 0, 0.0, 0.0
+    for b in picks:
+        c = int(ctx[b])
+        st = sd.SeqState(small, c + args.verify + args.depth * args.topk + 16, dec.round_to_bf16)
+        for l in range(L_sample):
+            st.target[l].k[:c] = _gather_rows(e.kv.k_pool[l], table[b], c, cfg.page_size)
+            st.target[l].v[:c] = _gather_rows(e.kv.v_pool[l], table[b], c, cfg.page_size)
+        st.draft.k[:c] = _gather_rows(e.dkv.k_pool[0], dtable[b], c, cfg.page_size)
+        st.draft.v[:c] = _gather_rows(e.dkv.v_pool[0], dtable[b], c, cfg.page_size)
+        st.ctx = c
+        st.draft_len = c
+        t0 = time.perf_counter()
+        sd.draft_extend(small, tw64, dw64, st, [int(rng.integers(cfg.vocab))], rng.normal(size=(1, cfg.hidden)))
+        tree, _ = sd.draft_expand(small, tw64, dw64, st, 1, args.topk, args.depth, args.verify)
+        t_draft = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        logits, hidden = sd.verify(small, tw64, st, tree)
+        t_verify = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        dec.lm_logits(small, tw64, hidden)
+        t_head = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        a, path, out = sd.accept_greedy(tree, logits)
+        sd.commit(st, path)
+        t_tail = time.perf_counter() - t0
+        t_layers = max(t_verify - t_head, 0.0)
+        t_scaled += t_draft + t_layers * cfg.n_layers / L_sample + t_head + t_tail
+        t_measured += t_draft + t_verify + t_head + t_tail
+        tokens += a + 1
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
-    return {"value": round((a + 1) / t_seq, 4), "unit": "accepted tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"one sequence of the batch (context {c}): drafter extend + expand, {L_sample} of {cfg.n_layers} "
-                      f"target layers + LM head, accept, commit; layer time scaled by {cfg.n_layers}/{L_sample}; the "
-                      f"oracle runs sequences one after another, so its tokens/s does not grow with the batch",
-            "seconds_measured": round(t_draft + t_verify + t_head + t_tail, 2)}
+    return {"value": round(tokens / t_scaled, 4), "unit": "accepted tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(picks)} of the batch's {len(ctx)} sequences (contexts {sorted(int(ctx[b]) for b in picks)}), one "
+                      f"after another: drafter extend + expand, {L_sample} of {cfg.n_layers} target layers + LM head, "
+                      f"accept, commit; layer time scaled by {cfg.n_layers}/{L_sample}",
+            "seconds_measured": round(t_measured, 2)}
+
+
+def recorded_traffic(key):
+    """HBM-side bytes per launch from the committed counter summary (two rocprofv3 --pmc runs of this
+    same command, scaled by a plain copy of known size); None when there is no such record."""
+    import re
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_sd_step_7b_b32_n48.md")
+    try:
+        m = re.search(r"traffic_bytes_per_launch %s = (\d+)" % re.escape(key), open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def main():
@@ -176,6 +194,9 @@ def main():
     ap.add_argument("--ctx-cap", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", dest="sweep", action="store_false")
+    ap.add_argument("--pmc-copy-mib", type=int, default=0,
+                    help="end with one plain device copy of this many MiB: the known-size kernel that hardware "
+                         "counter readings (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent and would "
@@ -216,6 +237,7 @@ def main():
     per_class = {k: {"ms_per_step": round(v["ms"] / args.steps, 4), "launches_per_step": v["launches"] // args.steps}
                  for k, v in prof.items()}
 
+    default_workload = (args.model, B, D, K, N, args.ctx_median, args.ctx_cap) == ("7b", 32, 6, 8, 48, 4096, 16384)
     result = {
         "metric": "accepted tokens/s per GPU in SD rollout step; verify latency vs tree size",
         "value": round(emitted / dt, 2), "unit": "accepted tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -225,11 +247,16 @@ def main():
                                f"{args.ctx_median}, sigma 0.8, cap {args.ctx_cap}) = {int(ctx.sum())} cached tokens, "
                                f"16-token pages, tree depth {D} top-k {K} verify {N}, greedy",
                    "accepted_per_step": round(emitted / args.steps, 2), "drafter": "random-init (accept length ~0)"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_k (verification forward GEMMs)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dtl_k (verification forward GEMMs)",
                      "achieved": round(gemm_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": recorded_traffic("gemm_bf16_dtl_k_verify") if default_workload else None,
                      "avg_launch_us": round(g["ms"] / max(g["launches"], 1) * 1e3, 2),
-                     "flops_per_launch": round(g["flops"] / max(g["launches"], 1), 0)},
+                     "flops_per_launch": round(g["flops"] / max(g["launches"], 1), 0),
+                     # every launch of the kernel in the step (drafter included): the figure a
+                     # kernel trace of the same command averages to over all its instantiations
+                     "avg_launch_us_all": round((g["ms"] + prof["gemm_draft"]["ms"])
+                                                / max(g["launches"] + prof["gemm_draft"]["launches"], 1) * 1e3, 2)},
         "attention_roofline": {"bound": "hbm", "kernel": "attn_mfma_k + attn_combine_k (verification forward)",
                                "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
@@ -241,6 +268,11 @@ def main():
         result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args)
+    if args.pmc_copy_mib > 0:
+        src = torch.ones(args.pmc_copy_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(result))
 
 
