@@ -4,14 +4,15 @@
 //
 // bf16 path (gfx950): v_mfma_f32_32x32x16_bf16, fp32 accumulation.  A workgroup of 4 waves (2x2)
 // owns a (64*WTM) x (64*WTN) tile; each wave owns WTM x WTN MFMA tiles of 32x32.  K is walked in
-// steps of 64 through two LDS stages filled by direct global->LDS loads (no staging registers, no
-// ds_write).  Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8
-// XCDs) walks a contiguous range of tiles, M fastest: neighbours on one XCD share the same weight
-// tile in that XCD's L2 and every weight byte is fetched from HBM once.
-// Measured ceilings on MI355X that shape this kernel: a register-only MFMA loop reaches 2.0-2.4
-// PFLOP/s; adding the 64 KB per K-step of global->LDS traffic of a 256x256 tile caps a CU at
-// ~1.35 PFLOP/s-equivalent even when every load hits L2 (the per-CU vector-memory path sustains
-// about 24 B/clk), and at ~1.0 when half the loads come over the fabric.
+// steps of 64 through rings of LDS slots (SA for the activation rows, SB for the weight rows) filled
+// by direct global->LDS loads (no staging registers, no ds_write).  Workgroup ids are remapped so
+// that each XCD (ids are dealt round-robin over the 8 XCDs) walks a contiguous range of tiles, M
+// fastest: neighbours on one XCD share the same weight tile in that XCD's L2.
+// Measured on MI355X, and what shapes the kernel: a register-only MFMA loop with one wave per SIMD
+// reaches ~2.0 PFLOP/s; the chip clocks down to ~1.6-1.8 GHz under sustained MFMA load; a CU's
+// vector-memory front end moves ~50 B/clk of global->LDS traffic when rows are fetched as whole
+// 128-byte lines (~110 GB/s per CU, half that for 64-byte pieces), so the 64 KB a 256x256 tile
+// needs per K step occupy it for ~1300 of the step's 2048 MFMA clocks.
 //
 // Generic path (fp32 mode, odd shapes): 64x64 LDS-tiled FMA kernel with full bounds checks.
 #include "dev_common.h"
@@ -35,26 +36,58 @@ __device__ __forceinline__ void store_out(void* C, int64_t idx, float v) {
         ((float*)C)[idx] += v;
 }
 
-// ------------------------------------------------------------------------------------------------
-// The tiles go from global memory straight into LDS (global_load_lds_dwordx4,
-// 1 KB = 8 tile rows per wave instruction), so no registers are spent on staging, nothing is
-// re-written with ds_write, and the only wait is the vmcnt wait for the stage loaded S-1 steps ago.
-// Tile rows are stored unpadded (128 B = 8 chunks of 16 B) with chunk c of row r at position
-// c ^ (r & 7): the DMA lays lanes out contiguously, so the swizzle is applied by choosing which
-// global chunk each lane fetches, and the fragment reads of 8 consecutive rows hit 8 distinct
-// 16-byte columns.
 constexpr uint32_t vmcnt_imm(int n) { return 0x0F70u | (uint32_t)(n & 15) | ((uint32_t)(n >> 4) << 14); }
 
-template <int WGM, int WGN, int WTM, int WTN, int STAGES, int OUT>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dtl_k(int M, int N, int K, const uint16_t* __restrict__ A,
-                                                       const uint16_t* __restrict__ W, void* __restrict__ C, int nbm,
-                                                       int total_tiles, int per_xcd) {
-    constexpr int NW = WGM * WGN;                    // waves per workgroup, WGM x WGN grid of wave tiles
+// ------------------------------------------------------------------------------------------------
+// The main loop is software-pipelined by hand.  What the schedule has to respect on this chip:
+//  * one wave per SIMD issues in order, so anything that blocks the wave blocks its matrix pipe;
+//  * the vector-memory front end accepts one 1 KB global->LDS wave instruction every ~20 clocks and
+//    a wave that issues one while it is busy waits for its turn, so the loads are never issued as a
+//    burst: every MFMA row (WTN MFMAs) is followed by exactly one load, all step long;
+//  * a slot can only be refilled after the barrier that frees it and must have landed before the
+//    barrier that publishes it.  The activation rows get one slot more than the weight rows (3 + 2
+//    slots of 32 KB = the whole 160 KB LDS for a 256x256 tile): weight loads are issued in the first
+//    half of that window and have the second half to land, activation loads are issued in the
+//    second half and have a whole further step.
+// Per K step t (four 16-wide slices, fragment register sets F0/F1):
+//    slice 0 on F0 | LDS reads of slice 1 -> F1 | W tile t-1+SB, second half
+//    slice 1 on F1 | LDS reads of slice 2 -> F0 | A tile t-1+SA, first half
+//    slice 2 on F0 | LDS reads of slice 3 -> F1 | A tile t-1+SA, second half
+//    wait for the reads and for tile t+1, barrier                 (tile t's slots are free from here)
+//    slice 3 on F1 | LDS reads of (t+1, slice 0) -> F0 | W tile t+SB, first half
+// so the last slice's MFMAs cover the barrier skew and the first reads of the next tile.  The loads
+// are issued from inline assembly (scalar base + 32-bit per-lane byte offset) and waited for
+// explicitly: the compiler does not see them and so cannot order them against the LDS reads with a
+// full vmcnt(0).
+// LDS layout: tile rows unpadded (128 B = 8 chunks of 16 B), chunk c of row r at c ^ ((r >> 1) & 7).
+// The LDS has 64 banks (256 B per clock): a 16-byte fragment read is served 16 lanes at a time, and
+// with this swizzle 16 consecutive rows hit 16 distinct 16-byte columns (SQ_LDS_BANK_CONFLICT = 0;
+// swizzling with r & 7 instead costs a two-way conflict on every read).
+__device__ __forceinline__ void dma_saddr_16(const void* sbase, uint32_t voff_bytes, uint32_t lds_bytes) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff_bytes), "s"(sbase), "s"(lds_bytes)
+                 : "memory", "m0");
+}
+
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
+                                                        const uint16_t* __restrict__ W, void* __restrict__ C, int nbm,
+                                                        int total_tiles, int per_xcd) {
+    constexpr int NW = WGM * WGN;
+    constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
-    constexpr int STAGE = (BM + BN) * kBK;          // elements per stage
-    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // DMA instructions per wave per stage for A and W
+    constexpr int ASZ = BM * BKS, BSZ = BN * BKS;      // elements per A slot / W slot
+    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 1 KB DMA instructions per wave per tile: A part, W part
+    constexpr int NR = WTM + WTN;                     // fragment reads per slice
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split evenly over the waves");
-    extern __shared__ __align__(16) uint16_t lds[];
+    static_assert(LA == 2 * WTM && LB == 2 * WTM && NR % WTM == 0, "schedule: one load per MFMA row, two slices per operand");
+    static_assert(SA >= 2 && SB >= 2, "at least double buffering");
+    constexpr int RPR = NR / WTM;
+    // loads that may still be in flight when tile t+1 must be complete (issue order per step: W, then A)
+    constexpr int kInFlightA = (SA - 2) * (LA + LB), kInFlightB = (SB - 1) * LA + (SB - 2) * LB;
+    constexpr int kInFlight = kInFlightA < kInFlightB ? kInFlightA : kInFlightB;
+    extern __shared__ __align__(16) uint16_t lds[];   // SA A slots, then SB W slots
 
     const int pid = blockIdx.x;
     const int logical = (pid & 7) * per_xcd + (pid >> 3);
@@ -62,34 +95,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dtl_k(int M, int N, 
     const int tile_m = logical % nbm, tile_n = logical / nbm;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS DMA bases live in SGPRs
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    // DMA addressing: instruction i of this wave covers tile rows (wave + NW i) * 8 .. + 8
-    const int r8 = lane >> 3, lc = (lane & 7) ^ r8;  // row in the block, logical chunk this lane fetches
-    uint32_t offA[LA];
+    // DMA addressing: wave w fills 1 KB blocks w*LA .. of an A slot (8 tile rows each) and w*LB .. of
+    // a W slot; lane -> (row r of the block, stored chunk c) fetches the logical chunk that the
+    // swizzle places there
+    const int r = lane >> 3, c = lane & 7;
+    uint32_t offA[LA], offB[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        int row = m0 + (wave + NW * i) * 8 + r8;
+        const int trow = (wave * LA + i) * 8 + r;
+        int row = m0 + trow;
         row = row < M ? row : M - 1;
-        offA[i] = (uint32_t)(row - m0) * (uint32_t)K + lc * 8;
+        offA[i] = ((uint32_t)(row - m0) * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
     }
-    const uint32_t offB0 = (uint32_t)(wave * 8 + r8) * (uint32_t)K + lc * 8;
-    const uint32_t strideB = (uint32_t)(8 * NW) * (uint32_t)K;
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int trow = (wave * LB + i) * 8 + r;
+        offB[i] = ((uint32_t)trow * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
+    }
     const uint16_t* gA = A + (int64_t)m0 * K;
     const uint16_t* gB = W + (int64_t)n0 * K;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
+    const uint32_t lds_waveA = lds_base + (uint32_t)(wave * LA) * 1024u;
+    const uint32_t lds_waveB = lds_base + (uint32_t)(SA * ASZ * 2) + (uint32_t)(wave * LB) * 1024u;
 
-#define TLT_DMA(stage, k0)                                                                                       \
-    {                                                                                                            \
-        uint16_t* sb = lds + (stage) * STAGE;                                                                    \
-        _Pragma("unroll") for (int i = 0; i < LA; ++i) __builtin_amdgcn_global_load_lds(                          \
-            (const __attribute__((address_space(1))) void*)(gA + (k0) + offA[i]),                                \
-            (__attribute__((address_space(3))) void*)(sb + (wave + NW * i) * 512), 16, 0, 0);                     \
-        _Pragma("unroll") for (int i = 0; i < LB; ++i) __builtin_amdgcn_global_load_lds(                          \
-            (const __attribute__((address_space(1))) void*)(gB + (k0) + offB0 + i * strideB),                    \
-            (__attribute__((address_space(3))) void*)(sb + BM * kBK + (wave + NW * i) * 512), 16, 0, 0);          \
-    }
+#define TLT_DMA_A(slot, k0, d) dma_saddr_16(gA + (k0), offA[d], lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
+#define TLT_DMA_B(slot, k0, d) dma_saddr_16(gB + (k0), offB[d], lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
 
     f32x16_t acc[WTM][WTN];
 #pragma unroll
@@ -99,45 +133,81 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dtl_k(int M, int N, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = K / kBK;
+    const int nt = K / BKS;
+    auto ktile = [&](int t) { return (t < nt ? t : nt - 1) * BKS; };   // past the end: harmless re-fetch of the last tile
+    // prologue: tile 0 first, then A tiles 1 .. SA-2, W tiles 1 .. SB-2 and the first half of W tile SB-1
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) {
-        const int kt = st < nk ? st : nk - 1;
-        TLT_DMA(st, kt * kBK)
-    }
-    // fragment addressing: row l32 of each 32-row MFMA tile, chunk (2 kk + lhi) ^ (row & 7)
-    const int fragA = (wm * (WTM * 32) + l32) * kBK;
-    const int fragB = BM * kBK + (wn * (WTN * 32) + l32) * kBK;
-    const int sw = l32 & 7;
-    for (int kt = 0; kt < nk; ++kt) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((LA + LB) * (STAGES - 2)));  // this stage's DMA has landed
-        __builtin_amdgcn_s_barrier();  // ... for every wave, and the stage about to be refilled is no longer read
-        {
-            const int nxt = kt + STAGES - 1;
-            const int ktl = nxt < nk ? nxt : nk - 1;  // past the end: harmless re-fetch of the last tile
-            TLT_DMA(nxt % STAGES, ktl * kBK)
-        }
-        const uint16_t* sb = lds + (kt % STAGES) * STAGE;
+    for (int d = 0; d < LA; ++d) TLT_DMA_A(0, 0, d)
 #pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            const int ch = ((2 * kk + lhi) ^ sw) * 8;
-            bf16x8_t fa[WTM], fb[WTN];
+    for (int d = 0; d < LB; ++d) TLT_DMA_B(0, 0, d)
 #pragma unroll
-            for (int i = 0; i < WTM; ++i)
-                fa[i] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(sb + fragA + i * 32 * kBK + ch));
+    for (int st = 1; st < SA - 1; ++st)
 #pragma unroll
-            for (int j = 0; j < WTN; ++j)
-                fb[j] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(sb + fragB + j * 32 * kBK + ch));
+        for (int d = 0; d < LA; ++d) TLT_DMA_A(st, ktile(st), d)
 #pragma unroll
-            for (int i = 0; i < WTM; ++i)
+    for (int st = 1; st < SB - 1; ++st)
 #pragma unroll
-                for (int j = 0; j < WTN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-    }
-#undef TLT_DMA
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the redundant tail fetches before the LDS is released
+        for (int d = 0; d < LB; ++d) TLT_DMA_B(st, ktile(st), d)
+#pragma unroll
+    for (int d = 0; d < LB / 2; ++d) TLT_DMA_B(SB - 1, ktile(SB - 1), d)
 
+    const int fragA = (wm * (WTM * 32) + l32) * BKS;
+    const int fragB = (wn * (WTN * 32) + l32) * BKS;
+    const int sw = (l32 >> 1) & 7;
+
+    bf16x8_t fa[2][WTM], fb[2][WTN];
+    // read q of a slice's NR fragment reads: the W fragments first (every MFMA row needs them all)
+#define TLT_READ1(buf, pa, pb, kk, q)                                                                             \
+    {                                                                                                             \
+        const int ch = ((2 * (kk) + lhi) ^ sw) * 8;                                                               \
+        if ((q) < WTN) fb[buf][q] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)((pb) + fragB + (q) * 32 * BKS + ch)); \
+        else fa[buf][(q) - WTN] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)((pa) + fragA + ((q) - WTN) * 32 * BKS + ch)); \
+    }
+#define TLT_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    // one slice: the MFMA rows on fragment set `buf`; the reads of the next slice into the other set
+    // in its first rows; one load (LOADX) after each row
+#define TLT_SLICE(buf, pa, pb, rkk, LOADX)                                                                        \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                              \
+        if (i < WTM / 2) {                                                                                        \
+            _Pragma("unroll") for (int q = 0; q < 2 * RPR; ++q) TLT_READ1((buf) ^ 1, pa, pb, rkk, i * 2 * RPR + q) \
+        }                                                                                                         \
+        _Pragma("unroll") for (int j = 0; j < WTN; ++j) TLT_MFMA(buf, i, j)                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        LOADX                                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+    }
+
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((SA - 2) * LA + (SB - 2) * LB + LB / 2));   // tile 0 has landed
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int q = 0; q < NR; ++q) TLT_READ1(0, lds, lds + SA * ASZ, 0, q)
+
+    // slot of tile t in each ring; pa_/pb_ = slot of tile t-1 (the one being refilled during step t)
+    int sa = 0, sb = 0, pa_ = SA - 1, pb_ = SB - 1;
+    for (int t = 0; t < nt; ++t) {
+        const uint16_t* pa = lds + sa * ASZ;
+        const uint16_t* pb = lds + SA * ASZ + sb * BSZ;
+        const int na = sa + 1 == SA ? 0 : sa + 1, nb = sb + 1 == SB ? 0 : sb + 1;
+        const int kBprev = ktile(t - 1 + SB), kAprev = ktile(t - 1 + SA), kBnext = ktile(t + SB);
+        // the first slice's fragments were requested a whole slice ago; waiting here, before the next
+        // reads are issued, keeps the compiler from waiting for those as well
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        TLT_SLICE(0, pa, pb, 1, TLT_DMA_B(pb_, kBprev, LB / 2 + i))       // W tile t-1+SB, second half
+        TLT_SLICE(1, pa, pb, 2, TLT_DMA_A(pa_, kAprev, i))                // A tile t-1+SA, first half
+        TLT_SLICE(0, pa, pb, 3, TLT_DMA_A(pa_, kAprev, LA / 2 + i))       //               second half
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInFlight));        // tile t+1 has landed
+        __builtin_amdgcn_s_barrier();                            // ... for every wave; tile t's slots are free
+        __builtin_amdgcn_sched_barrier(0);
+        TLT_SLICE(1, lds + na * ASZ, lds + SA * ASZ + nb * BSZ, 0, TLT_DMA_B(sb, kBnext, i))   // W tile t+SB, first half
+        pa_ = sa; pb_ = sb; sa = na; sb = nb;
+    }
+#undef TLT_READ1
+#undef TLT_MFMA
+#undef TLT_SLICE
+#undef TLT_DMA_A
+#undef TLT_DMA_B
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the redundant tail fetches before the LDS is released
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
 #pragma unroll
@@ -207,17 +277,17 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
     }
 }
 
-template <int WGM, int WGN, int WTM, int WTN, int STAGES>
-static hipError_t launch_dtl(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB>
+static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     const int nbm = (M + BM - 1) / BM, nbn = N / BN;
     const int total = nbm * nbn;
     const int per_xcd = (total + 7) / 8;
-    const size_t lds = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
+    const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
     dim3 grid(per_xcd * 8), block(64 * WGM * WGN);
 #define LAUNCH(OUT)                                                                                                   \
     {                                                                                                                 \
-        auto kern = gemm_bf16_dtl_k<WGM, WGN, WTM, WTN, STAGES, OUT>;                                                 \
+        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT>;                                               \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -253,8 +323,13 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
     // per-lane DMA offsets are 32-bit element offsets inside a 256-row panel
     if (aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)256 * K < ((int64_t)1 << 31)) {
         const int tiles256 = ((M + 255) / 256) * (N / 256);
-        if (N % 256 == 0 && tiles256 >= 256) return launch_dtl<2, 2, 4, 4, 2>(s, out_mode, M, N, K, A, W, C);
-        return launch_dtl<2, 2, 2, 2, 2>(s, out_mode, M, N, K, A, W, C);
+        const int tiles128 = ((M + 127) / 128) * (N / 128);
+        // 256x256 tiles (three A slots + two W slots = all 160 KB of LDS) when they fill the chip;
+        // otherwise 128x128 tiles: 80 KB of slots lets two workgroups share a CU when there are
+        // more tiles than CUs, 96 KB buys a deeper prefetch when there are not
+        if (N % 256 == 0 && tiles256 >= 256) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C);
+        if (tiles128 > 256) return launch_pipe<2, 2, 2, 2, 3, 2>(s, out_mode, M, N, K, A, W, C);
+        return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N, K, A, W, C);
     }
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
 }
