@@ -56,17 +56,18 @@ constexpr uint32_t vmcnt_imm(int n) { return 0x0F70u | (uint32_t)(n & 15) | ((ui
 //    wait for the reads and for tile t+1, barrier                 (tile t's slots are free from here)
 //    slice 3 on F1 | LDS reads of (t+1, slice 0) -> F0 | W tile t+SB, first half
 // so the last slice's MFMAs cover the barrier skew and the first reads of the next tile.  The loads
-// are issued from inline assembly (scalar base + 32-bit per-lane byte offset) and waited for
+// are issued from inline assembly (buffer descriptor + 32-bit per-lane byte offset + scalar K offset) and waited for
 // explicitly: the compiler does not see them and so cannot order them against the LDS reads with a
 // full vmcnt(0).
 // LDS layout: tile rows unpadded (128 B = 8 chunks of 16 B), chunk c of row r at c ^ ((r >> 1) & 7).
 // The LDS has 64 banks (256 B per clock): a 16-byte fragment read is served 16 lanes at a time, and
 // with this swizzle 16 consecutive rows hit 16 distinct 16-byte columns (SQ_LDS_BANK_CONFLICT = 0;
 // swizzling with r & 7 instead costs a two-way conflict on every read).
-__device__ __forceinline__ void dma_saddr_16(const void* sbase, uint32_t voff_bytes, uint32_t lds_bytes) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+__device__ __forceinline__ void dma_buf_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff_bytes, uint32_t soff_bytes,
+                                           uint32_t lds_bytes) {
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
                  :
-                 : "v"(voff_bytes), "s"(sbase), "s"(lds_bytes)
+                 : "v"(voff_bytes), "s"(rsrc), "s"(soff_bytes), "s"(lds_bytes)
                  : "memory", "m0");
 }
 
@@ -116,14 +117,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         const int trow = (wave * LB + i) * 8 + r;
         offB[i] = ((uint32_t)trow * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
     }
-    const uint16_t* gA = A + (int64_t)m0 * K;
-    const uint16_t* gB = W + (int64_t)n0 * K;
+    // raw buffer descriptors over the two row panels (range checking effectively off: every offset
+    // is below 2^31 by the launcher's shape check)
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)m0 * K), 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)(W + (int64_t)n0 * K), 0, 0x7fffffff, 0x00020000);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
     const uint32_t lds_waveA = lds_base + (uint32_t)(wave * LA) * 1024u;
     const uint32_t lds_waveB = lds_base + (uint32_t)(SA * ASZ * 2) + (uint32_t)(wave * LB) * 1024u;
 
-#define TLT_DMA_A(slot, k0, d) dma_saddr_16(gA + (k0), offA[d], lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
-#define TLT_DMA_B(slot, k0, d) dma_saddr_16(gB + (k0), offB[d], lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
+#define TLT_DMA_A(slot, k0, d) dma_buf_16(rsA, offA[d], (uint32_t)(k0) * 2u, lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
+#define TLT_DMA_B(slot, k0, d) dma_buf_16(rsB, offB[d], (uint32_t)(k0) * 2u, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
 
     f32x16_t acc[WTM][WTN];
 #pragma unroll
@@ -321,7 +324,7 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
     if (dtype == F32) return launch_generic<float>(s, out_mode, M, N, K, A, W, C);
     const bool aligned = (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
     // per-lane DMA offsets are 32-bit element offsets inside a 256-row panel
-    if (aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)256 * K < ((int64_t)1 << 31)) {
+    if (aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)258 * K * 2 < ((int64_t)1 << 31)) {
         const int tiles256 = ((M + 255) / 256) * (N / 256);
         const int tiles128 = ((M + 127) / 128) * (N / 128);
         // 256x256 tiles (three A slots + two W slots = all 160 KB of LDS) when they fill the chip;
