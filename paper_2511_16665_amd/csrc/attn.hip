@@ -116,9 +116,22 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
+// max over the four 16-lane groups of a wave (lanes l, l^16, l^32, l^48) without going through the LDS
+// crossbar: v_permlane32_swap / v_permlane16_swap exchange half-waves / odd and even 16-lane rows of
+// two registers, so swapping a value with a copy of itself puts the partner's value beside it.
+__device__ __forceinline__ float group_max4(float x) {
+    const uint32_t u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const uint32_t v = __float_as_uint(m);
+    const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 constexpr int kD = 128;       // head_dim of this kernel
 constexpr int kKT = 64;       // keys per LDS tile
-constexpr int kStages = 4;                  // LDS ring depth: three tiles of K/V in flight
+constexpr int kStages = 4;                  // LDS ring depth
+constexpr int kAhead = 2;                   // tiles of K/V in flight; one more stage stays readable for the late waves (below)
 constexpr int kStageElems = 2 * kKT * kD;   // one stage: K tile then V tile, 16 KB each
 constexpr float kNegBig = -1e30f;
 constexpr int kMaxRows = 128;    // rows per sequence whose visibility bits are kept in LDS
@@ -196,11 +209,12 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         }
     }
     f32x4_t acc[TPW][8];
-    float m_run[TPW], l_run[TPW];
+    float m_run[TPW];
+    f32x4_t acc_l[TPW];   // running softmax denominator, accumulated by the matrix pipe (PV product against a row of ones)
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         m_run[t] = kNegBig;
-        l_run[t] = 0.f;
+        acc_l[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) acc[t][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
@@ -230,16 +244,22 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             mask_lds[2 * i] = m0;
             mask_lds[2 * i + 1] = m1;
         }
-        // zero the ring once: slots whose DMA is skipped (unbacked pages) must hold finite values
-        u32x4_t z = {0u, 0u, 0u, 0u};
-        for (int e = tid; e < kStages * kStageElems / 8; e += 512) *(u32x4_t*)(lds + e * 8) = z;
         // page ids of this chunk, range-checked once (-1 = not backed by the block table)
         const int first_page = k_begin / kv.page_size;
         const int n_pg = (k_end - 1) / kv.page_size - first_page + 1;
+        int unbacked = 0;
         for (int pi = tid; pi < n_pg; pi += 512) {
             const int lp = first_page + pi;
             int pg = lp < kv.max_pages ? kv.block_table[(int64_t)b * kv.max_pages + lp] : -1;
-            page_ids[pi] = (pg >= 0 && pg < kv.n_pages) ? pg : -1;
+            pg = (pg >= 0 && pg < kv.n_pages) ? pg : -1;
+            page_ids[pi] = pg;
+            unbacked |= pg < 0;
+        }
+        // slots whose DMA is skipped (unbacked pages: a caller error) must still hold finite values:
+        // only then is the ring zeroed first
+        if (__syncthreads_or(unbacked)) {
+            u32x4_t z = {0u, 0u, 0u, 0u};
+            for (int e = tid; e < kStages * kStageElems / 8; e += 512) *(u32x4_t*)(lds + e * 8) = z;
         }
     }
     __syncthreads();
@@ -265,110 +285,17 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         }
     };
 #pragma unroll
-    for (int st = 0; st < kStages - 1; ++st) issue_dma(st < n_tiles ? st : n_tiles - 1, st);
+    for (int st = 0; st < kAhead; ++st) issue_dma(st < n_tiles ? st : n_tiles - 1, st);
 
     // Drain every load issued so far (Q fragments, table reads, the first DMAs) once, here, so that the
     // compiler's own wait bookkeeping enters the loop clean and adds no vmcnt(0) of its own inside it,
     // which would also drain the DMA queue on every tile.
     __builtin_amdgcn_s_waitcnt(0x0F70u);
-    for (int it = 0; it < n_tiles; ++it) {
-        __builtin_amdgcn_s_waitcnt(0x0F70u | (4 * (kStages - 2)));  // vmcnt: this tile's 4 DMAs per wave have landed
-        __builtin_amdgcn_s_barrier();
-        {
-            const int nxt = it + kStages - 1;
-            issue_dma(nxt < n_tiles ? nxt : n_tiles - 1, nxt % kStages);
-        }
-        const int t0 = k_begin + it * kKT;
-        const uint16_t* kt = lds + (it % kStages) * kStageElems;
-        const uint16_t* vt = kt + kKT * kD;
-        // 1 for the tile(s) touching the tree region or the chunk's tail, else 0.  Used as the trip count
-        // of the masking loop below: a loop with a uniform run-time bound stays a real branch, whereas an
-        // `if` around this much select-able code gets flattened and would run on every tile.
-        const int mask_reps = t0 + kKT > ctx ? 1 : 0;
-
-        // ---- S^T = K Q^T: each K fragment is read once and feeds the TPW independent row tiles.  The
-        // LDS reads are issued in batches of 4 fragments ahead of the 4*TPW MFMAs that consume them, so
-        // one LDS latency is exposed per batch instead of one per fragment.
-        f32x4_t scs[TPW][4];
+    // P of the tile whose PV product is still owed (packed bf16, the second product's B operand)
+    u32x4_t pb[TPW][2];
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            bf16x8_t kf[4];
-            const uint16_t* kp = kt + (st * 16 + l16) * kD;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                kf[ks] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int t = 0; t < TPW; ++t)
-                    scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
-                                                                         scs[t][st], 0, 0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
-        }
-        // ---- per row tile: online softmax, P packed straight into the second product's B operand
-        u32x4_t pb[TPW][2];
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            f32x4_t sc[4];
-#pragma unroll
-            for (int st = 0; st < 4; ++st) sc[st] = scs[t][st];
-            float tmax = kNegBig;
-            for (int rep = 0; rep < mask_reps; ++rep) {  // region / tail tile only (see mask_reps)
-                uint64_t m0 = 0, m1 = 0;
-                const int i = row_i[t];
-                if (i >= 0) {  // from the LDS copy: no global load (and so no vmcnt wait) inside the loop
-                    m0 = mask_lds[2 * i];
-                    m1 = mask_lds[2 * i + 1];
-                }
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int key = t0 + st * 16 + g4 * 4 + v;
-                        const int jj = key - ctx;  // index into the masked region when >= 0
-                        const uint64_t w = jj < 64 ? m0 : m1;
-                        const bool bit = (w >> (jj & 63)) & 1ull;
-                        const bool vis = (i >= 0) & (key < k_end) & ((jj < 0) | (bit & (jj < 128)));
-                        sc[st][v] = vis ? sc[st][v] : kNegBig;
-                    }
-            }
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) tmax = fmaxf(tmax, sc[st][v]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run[t], tmax);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2);
-            // the clamp keeps exp2(x*c - mc) = 0 for masked scores (-1e30) while no key has been visible yet
-            const float mc = fmaxf(m_new, -1e29f) * scale_log2;
-            m_run[t] = m_new;
-            float psum = 0.f;
-            uint32_t pk[4][2];
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                float pv[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float x = sc[st][v];
-                    float e = __builtin_amdgcn_exp2f(fmaf(x, scale_log2, -mc));
-                    pv[v] = e;
-                    psum += e;
-                }
-                pk[st][0] = pack_bf16x2(pv[0], pv[1]);
-                pk[st][1] = pack_bf16x2(pv[2], pv[3]);
-            }
-            l_run[t] = l_run[t] * alpha + psum;
-            if (alpha != 1.0f) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
-            }
-            pb[t][0] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
-            pb[t][1] = u32x4_t{pk[2][0], pk[2][1], pk[3][0], pk[3][1]};
-        }
+    for (int t = 0; t < TPW; ++t) pb[t][0] = pb[t][1] = u32x4_t{0u, 0u, 0u, 0u};
+    auto pv_step = [&](const uint16_t* vt) {
         // ---- O^T += V^T P^T.  V stays row-major in LDS; ds_read_b64_tr_b16 hands lane (l16, g4) the
         // four keys 4*g4 .. 4*g4+3 of a 16-key sub-tile for head dimension 16*dt + l16: the 16 lanes of
         // a group address a 4-key x 16-dim block (lane s -> key s/4, dims 4*(s%4) ..) and the
@@ -377,6 +304,14 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         for (int half = 0; half < 2; ++half) {
             typedef __attribute__((ext_vector_type(4))) short s16x4_t;
             typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+            {   // denominator: the same product against a V^T row of ones (bf16 1.0 = 0x3f80)
+                const s16x8_t one8 = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+                    acc_l[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, one8),
+                                                                      __builtin_bit_cast(bf16x8_t, pb[t][half]),
+                                                                      acc_l[t], 0, 0, 0);
+            }
 #pragma unroll
             for (int dq = 0; dq < 2; ++dq) {
                 s16x4_t vv[4][2];
@@ -406,7 +341,111 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                 __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
             }
         }
+    };
+    // The two waves that share a SIMD (w and w + 4) run the loop one phase apart, so that one's softmax
+    // (VALU) overlaps the other's MFMA phases instead of both doing the same thing at the same time:
+    // the early waves 0..3 pass the tile barrier before S = QK^T, the late waves 4..7 pass it one
+    // phase earlier, before the PV product of the previous tile.  PV of tile it-1 therefore runs at the
+    // top of iteration it for everyone, and the stage of tile it-1 stays untouched until iteration it+1.
+    const bool late = wave_u >= 4;
+    auto tile_sync = [&](int it) {
+        __builtin_amdgcn_s_waitcnt(0x0F70u | (4 * (kAhead - 1)));  // vmcnt: this tile's 4 DMAs per wave have landed
+        __builtin_amdgcn_s_barrier();
+        const int nxt = it + kAhead;
+        issue_dma(nxt < n_tiles ? nxt : n_tiles - 1, nxt % kStages);
+    };
+    for (int it = 0; it < n_tiles; ++it) {
+        if (late) tile_sync(it);
+        if (it > 0) pv_step(lds + ((it - 1) % kStages) * kStageElems + kKT * kD);
+        if (!late) tile_sync(it);
+        const int t0 = k_begin + it * kKT;
+        const uint16_t* kt = lds + (it % kStages) * kStageElems;
+        // 1 for the tile(s) touching the tree region or the chunk's tail, else 0.  Used as the trip count
+        // of the masking loop below: a loop with a uniform run-time bound stays a real branch, whereas an
+        // `if` around this much select-able code gets flattened and would run on every tile.
+        const int mask_reps = t0 + kKT > ctx ? 1 : 0;
+
+        // ---- S^T = K Q^T: each K fragment is read once and feeds the TPW independent row tiles.  The
+        // LDS reads are issued in batches of 4 fragments ahead of the 4*TPW MFMAs that consume them, so
+        // one LDS latency is exposed per batch instead of one per fragment.
+        f32x4_t scs[TPW][4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            bf16x8_t kf[4];
+            const uint16_t* kp = kt + (st * 16 + l16) * kD;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                kf[ks] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+                    scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
+                                                                         scs[t][st], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
         }
+        // ---- per row tile: online softmax, P packed straight into the second product's B operand
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            f32x4_t sc[4];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) sc[st] = scs[t][st];
+            float tmax = kNegBig;
+            for (int rep = 0; rep < mask_reps; ++rep) {  // region / tail tile only (see mask_reps)
+                uint64_t m0 = 0, m1 = 0;
+                const int i = row_i[t];
+                if (i >= 0) {  // from the LDS copy: no global load (and so no vmcnt wait) inside the loop
+                    m0 = mask_lds[2 * i];
+                    m1 = mask_lds[2 * i + 1];
+                }
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int key = t0 + st * 16 + g4 * 4 + v;
+                        const int jj = key - ctx;  // index into the masked region when >= 0
+                        const uint64_t w = jj < 64 ? m0 : m1;
+                        const bool bit = (w >> (jj & 63)) & 1ull;
+                        const bool vis = (i >= 0) & (key < k_end) & ((jj < 0) | (bit & (jj < 128)));
+                        sc[st][v] = vis ? sc[st][v] : kNegBig;
+                    }
+            }
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) tmax = fmaxf(tmax, sc[st][v]);
+            tmax = group_max4(tmax);
+            const float m_new = fmaxf(m_run[t], tmax);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2);
+            // the clamp keeps exp2(x*c - mc) = 0 for masked scores (-1e30) while no key has been visible yet
+            const float mc = fmaxf(m_new, -1e29f) * scale_log2;
+            m_run[t] = m_new;
+            uint32_t pk[4][2];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                float pv[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = sc[st][v];
+                    float e = __builtin_amdgcn_exp2f(fmaf(x, scale_log2, -mc));
+                    pv[v] = e;
+                }
+                pk[st][0] = pack_bf16x2(pv[0], pv[1]);
+                pk[st][1] = pack_bf16x2(pv[2], pv[3]);
+            }
+            if (alpha != 1.0f) {
+                acc_l[t] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
+            }
+            pb[t][0] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
+            pb[t][1] = u32x4_t{pk[2][0], pk[2][1], pk[3][0], pk[3][1]};
+        }
+    }
+    pv_step(lds + ((n_tiles - 1) % kStages) * kStageElems + kKT * kD);
     __builtin_amdgcn_s_waitcnt(0x0F70u);  // drain the redundant tail DMAs before the LDS is released
 
     // ---- partial results: part_o [B][n_kv][n_chunks][r_pad][128], part_ml [..][r_pad][2]
@@ -416,9 +455,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         if (!tile_on[t]) continue;
         const int tile = rg * tiles_per_group + wave + 8 * t;
         const int r = tile * 16 + l16;
-        float l = l_run[t];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
+        const float l = acc_l[t][0];   // every lane of the row holds the full sum
         float* po = part_o + (pbase + r) * kD;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(po + dt * 16 + g4 * 4) = acc[t][dt];
