@@ -137,55 +137,127 @@ constexpr float kNegBig = -1e30f;
 constexpr int kMaxRows = 128;    // rows per sequence whose visibility bits are kept in LDS
 constexpr int kMaxChunk = 4096;  // keys per chunk: bounds the page-id table kept in LDS
 
+// Work decomposition.  A work item is (sequence, key range); each item is run by n_kv * row_groups
+// workgroups.  The key ranges are cut ON THE DEVICE from the actual sequence lengths (the host only
+// knows an upper bound): a one-workgroup planning kernel picks the item length so that the chip
+// gets about two items per CU (8 .. 64 tiles of 64 keys), gives every sequence equally long chunks,
+// and lists the items longest first.  Workgroups are dispatched in list order, so the long items
+// start first and the short ones fill the tail (longest-processing-time-first list scheduling).
+struct AttnItem {
+    int b, k_begin, k_end, slot;   // slot: index of this item's partial result (slots of a sequence are contiguous)
+};
+struct AttnWork {        // lives in the workspace, written by attn_plan_k
+    int n_items;
+    int pad[3];
+    // int slot0[B]; int n_chunks[B]; AttnItem items[max_items];
+};
+
 struct AttnPlan {
-    int ck;          // keys per chunk (multiple of 64)
-    int n_chunks;    // grid.x
     int row_tiles;   // ceil(R / 16)
-    int row_groups;  // grid.y factor: row tiles are cut into groups of at most 8 * tpw = 24
+    int row_groups;  // row tiles are cut into groups of at most 8 * tpw = 24
     int tpw;         // row tiles per wave (template instance)
     int r_pad;       // row_tiles * 16
+    int heads;       // workgroups per item: n_kv * row_groups
+    int max_items;   // upper bound of the item count, from the host-side length bound
 };
 
 static AttnPlan plan_attention(int B, int n, int G, int n_kv, int bound_total) {
     AttnPlan p;
-    const int pairs = B * n_kv;
-    int target = 1536 / (pairs > 0 ? pairs : 1);
-    if (target < 1) target = 1;
-    int ck = (bound_total + target - 1) / target;
-    ck = ((ck + 63) / 64) * 64;
-    if (ck < 256) ck = 256;
-    if (ck > kMaxChunk) ck = kMaxChunk;
-    p.ck = ck;
-    p.n_chunks = (bound_total + ck - 1) / ck;
-    if (p.n_chunks < 1) p.n_chunks = 1;
     p.row_tiles = (n * G + 15) / 16;
     p.r_pad = p.row_tiles * 16;
     p.row_groups = (p.row_tiles + 23) / 24;
     const int per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
     const int per_wave = (per_group + 7) / 8;
     p.tpw = per_wave <= 1 ? 1 : (per_wave <= 2 ? 2 : 3);
+    p.heads = n_kv * p.row_groups;
+    // items <= sum_b ceil(tiles_b / T) <= total_tiles / T + B with T = clamp(ceil(total_tiles * heads / 512), 8, 64):
+    // the first term is at most 512 / heads unless T is capped at 64
+    const int64_t tiles_bound = (int64_t)B * ((bound_total + kKT - 1) / kKT);
+    const int64_t a = (512 + p.heads - 1) / p.heads, c = (tiles_bound + 63) / 64;
+    p.max_items = B + (int)(a > c ? a : c);
     return p;
+}
+
+static size_t attn_work_bytes(int B, int max_items) {
+    return (sizeof(AttnWork) + (size_t)2 * B * sizeof(int) + (size_t)max_items * sizeof(AttnItem) + 255) / 256 * 256;
+}
+
+__global__ __launch_bounds__(256) void attn_plan_k(const int32_t* __restrict__ seq_len, int B, int n_region, int heads,
+                                                   int max_items, AttnWork* __restrict__ work) {
+    __shared__ int s_T, s_total, s_hist[66], s_pos[66];
+    int* slot0 = (int*)(work + 1);
+    int* nch = slot0 + B;
+    AttnItem* items = (AttnItem*)(nch + B);
+    const int tid = threadIdx.x;
+    if (tid < 66) s_hist[tid] = 0;
+    if (tid == 0) {
+        int64_t total = 0;
+        for (int b = 0; b < B; ++b) total += (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
+        int64_t c = (total * heads + 511) / 512;
+        s_T = (int)(c < 8 ? 8 : (c > 64 ? 64 : c));
+        int acc = 0;
+        for (int b = 0; b < B; ++b) {
+            const int tiles = (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
+            const int k = (tiles + s_T - 1) / s_T;
+            slot0[b] = acc;
+            nch[b] = k;
+            acc += k;
+        }
+        s_total = acc < max_items ? acc : max_items;   // cannot exceed the bound when seq_len respects the host's
+        work->n_items = s_total;
+    }
+    __syncthreads();
+    // counting sort by tile count, longest first
+    for (int b = tid; b < B; b += 256) {
+        const int total_b = max(seq_len[b], 0) + n_region;
+        const int tiles = (total_b + kKT - 1) / kKT, k = nch[b];
+        const int per = k > 0 ? (tiles + k - 1) / k : 0;
+        for (int j = 0; j < k; ++j) {
+            const int kb = j * per * kKT, ke = min(total_b, kb + per * kKT);
+            if (slot0[b] + j < max_items) atomicAdd(&s_hist[ke > kb ? (ke - kb + kKT - 1) / kKT : 0], 1);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int acc = 0;
+        for (int t = 65; t >= 0; --t) {
+            s_pos[t] = acc;
+            acc += s_hist[t];
+        }
+    }
+    __syncthreads();
+    for (int b = tid; b < B; b += 256) {
+        const int total_b = max(seq_len[b], 0) + n_region;
+        const int tiles = (total_b + kKT - 1) / kKT, k = nch[b];
+        const int per = k > 0 ? (tiles + k - 1) / k : 0;
+        for (int j = 0; j < k; ++j) {
+            const int kb = j * per * kKT, ke = min(total_b, kb + per * kKT);
+            if (slot0[b] + j >= max_items) continue;
+            const int pos = atomicAdd(&s_pos[ke > kb ? (ke - kb + kKT - 1) / kKT : 0], 1);
+            items[pos] = AttnItem{b, kb, ke, slot0[b] + j};
+        }
+    }
 }
 
 template <int TPW>
 __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
                                                    float* __restrict__ part_o, float* __restrict__ part_ml,
-                                                   int n_q_heads, int ck, int n_chunks, int row_tiles,
-                                                   int tiles_per_group, int r_pad, float scale_log2) {
+                                                   const AttnWork* __restrict__ work, int heads, int n_q_heads,
+                                                   int row_tiles, int tiles_per_group, int r_pad, float scale_log2) {
     extern __shared__ __align__(16) uint16_t lds[];
-    const int chunk = blockIdx.x;
-    const int kh = blockIdx.y % kv.n_kv, rg = blockIdx.y / kv.n_kv;
-    const int b = blockIdx.z;
+    const int rank = blockIdx.x / heads, hy = blockIdx.x - rank * heads;
+    if (rank >= work->n_items) return;  // uniform
+    const AttnItem item = ((const AttnItem*)((const int*)(work + 1) + 2 * rows.B))[rank];
+    const int kh = hy % kv.n_kv, rg = hy / kv.n_kv;
+    const int b = item.b;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g4 = lane >> 4;
     const int G = n_q_heads / kv.n_kv;
     const int n = rows.n;
     const int R = n * G;
+    const int k_begin = item.k_begin, k_end = item.k_end;
+    if (k_begin >= k_end) return;  // uniform (an empty sequence)
     const int ctx = kv.seq_len[b];
-    const int total = ctx + rows.n_region;
-    const int k_begin = chunk * ck;
-    if (k_begin >= total) return;  // uniform
-    const int k_end = min(total, k_begin + ck);
     const int qkv_dim = (n_q_heads + 2 * kv.n_kv) * kD;
     const int nv = rows.n_valid ? min(rows.n_valid[b], n) : n;
 
@@ -448,8 +520,8 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     pv_step(lds + ((n_tiles - 1) % kStages) * kStageElems + kKT * kD);
     __builtin_amdgcn_s_waitcnt(0x0F70u);  // drain the redundant tail DMAs before the LDS is released
 
-    // ---- partial results: part_o [B][n_kv][n_chunks][r_pad][128], part_ml [..][r_pad][2]
-    const int64_t pbase = (((int64_t)b * kv.n_kv + kh) * n_chunks + chunk) * r_pad;
+    // ---- partial results: part_o [slot][n_kv][r_pad][128], part_ml [..][r_pad][2]
+    const int64_t pbase = ((int64_t)item.slot * kv.n_kv + kh) * r_pad;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         if (!tile_on[t]) continue;
@@ -469,26 +541,29 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 // One wave per (b, kv head, row): merges the chunks' partial outputs (running max in raw score units).
 __global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
                                                      const float* __restrict__ part_ml, uint16_t* __restrict__ out,
-                                                     int n_q_heads, int ck, int n_chunks, int r_pad, float scale_log2) {
+                                                     const AttnWork* __restrict__ work, int n_q_heads, int max_items,
+                                                     int r_pad, float scale_log2) {
     const int r = blockIdx.x, kh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
     const int G = n_q_heads / kv.n_kv;
     const int i = r / G, gq = r - i * G;
     const int n = rows.n;
     const int nv = rows.n_valid ? min(rows.n_valid[b], n) : n;
     uint32_t* o = (uint32_t*)(out + ((int64_t)(b * n + i) * n_q_heads + kh * G + gq) * kD);
-    if (i >= nv) {
+    const int* slot0 = (const int*)(work + 1);
+    const int first = slot0[b];
+    int used = slot0[rows.B + b];
+    if (first + used > max_items) used = max(max_items - first, 0);
+    if (i >= nv || used <= 0) {
         o[lane] = 0u;
         return;
     }
-    const int total = kv.seq_len[b] + rows.n_region;
-    int used = (total + ck - 1) / ck;
-    if (used > n_chunks) used = n_chunks;
-    const int64_t pbase = ((int64_t)b * kv.n_kv + kh) * n_chunks * r_pad + r;
+    const int64_t pbase = ((int64_t)first * kv.n_kv + kh) * r_pad + r;
+    const int64_t pstride = (int64_t)kv.n_kv * r_pad;
     float M = kNegBig;
-    for (int c = 0; c < used; ++c) M = fmaxf(M, part_ml[(pbase + (int64_t)c * r_pad) * 2]);
+    for (int c = 0; c < used; ++c) M = fmaxf(M, part_ml[(pbase + c * pstride) * 2]);
     float a0 = 0.f, a1 = 0.f, L = 0.f;
     for (int c = 0; c < used; ++c) {
-        const int64_t pr = pbase + (int64_t)c * r_pad;
+        const int64_t pr = pbase + c * pstride;
         const float w = exp2f((part_ml[pr * 2] - M) * scale_log2);
         L += part_ml[pr * 2 + 1] * w;
         const float2 v = *(const float2*)(part_o + pr * kD + lane * 2);
@@ -499,20 +574,25 @@ __global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, cons
     o[lane] = pack_bf16x2(a0 * inv, a1 * inv);
 }
 
+static size_t attn_need_bytes(int B, const AttnPlan& p, int n_kv) {
+    return attn_work_bytes(B, p.max_items) + (size_t)p.max_items * n_kv * p.r_pad * (kD + 2) * sizeof(float);
+}
+
 size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx) {
     if (d != kD) return 256;
     const int G = n_q_heads / n_kv_heads;
-    const size_t r_pad = (size_t)((n * G + 15) / 16) * 16;
-    const size_t pairs = (size_t)B * n_kv_heads;
-    const size_t by_target = (pairs > 1536 ? pairs : 1536) + pairs;          // chunk length from the target count
-    const size_t by_cap = pairs * (size_t)((max_ctx + kMaxChunk - 1) / kMaxChunk + 1);  // chunk length capped
-    const size_t wg = by_target > by_cap ? by_target : by_cap;               // pairs * n_chunks never exceeds this
-    return wg * r_pad * (kD + 2) * sizeof(float) + 256;
+    size_t need = 0;   // any row count up to n may be asked for later
+    for (int m = 1; m <= n; ++m) {
+        const AttnPlan p = plan_attention(B, m, G, n_kv_heads, max_ctx + 128);
+        const size_t x = attn_need_bytes(B, p, n_kv_heads);
+        need = x > need ? x : need;
+    }
+    return need + 256;
 }
 
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                                   int n_q_heads, const AttnPlan& p, float* part_o, float* part_ml) {
+                                   int n_q_heads, const AttnPlan& p, AttnWork* work, float* part_o, float* part_ml) {
     const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t) +
                        (size_t)kMaxRows * 2 * sizeof(uint64_t);
     if (rows.n > kMaxRows) return hipErrorInvalidValue;
@@ -525,14 +605,14 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     }
     const int tiles_per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)kD);
-    dim3 grid(p.n_chunks, kv.n_kv * p.row_groups, rows.B), block(512);
-    hipLaunchKernelGGL(kern, grid, block, lds, s, rows, kv, (const uint16_t*)qkv, part_o, part_ml, n_q_heads, p.ck,
-                       p.n_chunks, p.row_tiles, tiles_per_group, p.r_pad, scale_log2);
+    hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work);
+    hipLaunchKernelGGL(kern, dim3(p.max_items * p.heads), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
+                       part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int R = rows.n * (n_q_heads / kv.n_kv);
     hipLaunchKernelGGL(attn_combine_k, dim3(R, kv.n_kv, rows.B), dim3(64), 0, s, rows, kv, part_o, part_ml,
-                       (uint16_t*)out, n_q_heads, p.ck, p.n_chunks, p.r_pad, scale_log2);
+                       (uint16_t*)out, work, n_q_heads, p.max_items, p.r_pad, scale_log2);
     return hipGetLastError();
 }
 
@@ -544,14 +624,14 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
     const bool mfma_ok = dtype == BF16 && kv.d == kD && rows.n_region <= 128 && kv.page_size == 16;
     if (mfma_ok && impl != 0) {
         const AttnPlan p = plan_attention(rows.B, rows.n, G, kv.n_kv, kv.seq_len_bound + rows.n_region);
-        const size_t need = (size_t)rows.B * kv.n_kv * p.n_chunks * p.r_pad * (kD + 2) * sizeof(float);
-        if (need <= ws_bytes) {
-            float* part_o = (float*)ws;
-            float* part_ml = part_o + (size_t)rows.B * kv.n_kv * p.n_chunks * p.r_pad * kD;
+        if (attn_need_bytes(rows.B, p, kv.n_kv) <= ws_bytes) {
+            AttnWork* work = (AttnWork*)ws;
+            float* part_o = (float*)((char*)ws + attn_work_bytes(rows.B, p.max_items));
+            float* part_ml = part_o + (size_t)p.max_items * kv.n_kv * p.r_pad * kD;
             switch (p.tpw) {
-                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
-                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
-                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, part_o, part_ml);
+                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
+                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
+                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
             }
         }
         if (impl == 1) return hipErrorInvalidValue;  // explicitly requested but the workspace cannot hold it
