@@ -200,9 +200,14 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     }
     if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
-    if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wg, ws + p.g))) return rc;
-    if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wu, ws + p.u))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * F * e * 3, swiglu(s, dt, (int64_t)M * F, ws + p.g, ws + p.u, ws + p.act));
+    if (gemm_glu_supported(dt, M, F, h, ws + p.xn, w.wg, w.wu)) {
+        TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 4.0 * M * F * h,
+                ((double)M * h + 2.0 * F * h + (double)M * F) * e, gemm_glu(s, M, F, h, ws + p.xn, w.wg, w.wu, ws + p.act));
+    } else {
+        if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wg, ws + p.g))) return rc;
+        if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wu, ws + p.u))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * F * e * 3, swiglu(s, dt, (int64_t)M * F, ws + p.g, ws + p.u, ws + p.act));
+    }
     if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, F, ws + p.act, w.wd, x))) return rc;
     return TLT_OK;
 }

@@ -71,10 +71,14 @@ __device__ __forceinline__ void dma_buf_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t
                  : "memory", "m0");
 }
 
-template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT>
+// GLU = true: the fused gate/up projection.  A workgroup's BN weight rows are BN/2 rows of W (gate)
+// followed by the same BN/2 rows of W2 (up); each wave multiplies both halves for its columns and
+// the epilogue stores silu(gate) * up, so C is [M][N] with N counting gate columns and the two
+// intermediate matrices never exist.
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
-                                                        const uint16_t* __restrict__ W, void* __restrict__ C, int nbm,
-                                                        int total_tiles, int per_xcd) {
+                                                        const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
+                                                        void* __restrict__ C, int nbm, int total_tiles, int per_xcd) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -94,7 +98,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     const int logical = (pid & 7) * per_xcd + (pid >> 3);
     if (logical >= total_tiles) return;
     const int tile_m = logical % nbm, tile_n = logical / nbm;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    constexpr int BNO = GLU ? BN / 2 : BN;            // output columns per workgroup
+    static_assert(!GLU || (NW % 2 == 0 && WTN % 2 == 0), "gate and up halves split over waves and over a wave's column tiles");
+    const int m0 = tile_m * BM, n0 = tile_n * BNO;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
@@ -120,7 +126,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     // raw buffer descriptors over the two row panels (range checking effectively off: every offset
     // is below 2^31 by the launcher's shape check)
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)m0 * K), 0, 0x7fffffff, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)(W + (int64_t)n0 * K), 0, 0x7fffffff, 0x00020000);
+    // (GLU: the first half of the waves fetch the gate rows, the second half the up rows; a wave's
+    // LB blocks are BN / NW consecutive tile rows, so they never straddle the two halves)
+    const bool up_wave = GLU && wave >= NW / 2;
+    const uint16_t* wsrc = up_wave ? W2 + ((int64_t)n0 - BN / 2) * K : W + (int64_t)n0 * K;
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)wsrc, 0, 0x7fffffff, 0x00020000);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
     const uint32_t lds_waveA = lds_base + (uint32_t)(wave * LA) * 1024u;
     const uint32_t lds_waveB = lds_base + (uint32_t)(SA * ASZ * 2) + (uint32_t)(wave * LB) * 1024u;
@@ -155,7 +165,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     for (int d = 0; d < LB / 2; ++d) TLT_DMA_B(SB - 1, ktile(SB - 1), d)
 
     const int fragA = (wm * (WTM * 32) + l32) * BKS;
-    const int fragB = (wn * (WTN * 32) + l32) * BKS;
+    // tile row of column tile j of this wave (GLU: j < WTN/2 are gate rows, the rest the matching up rows)
+    auto colrow = [&](int j) {
+        return GLU ? (j / (WTN / 2)) * (BN / 2) + (j % (WTN / 2)) * 32 : j * 32;
+    };
+    const int fragB = ((GLU ? wn * (WTN / 2 * 32) : wn * (WTN * 32)) + l32) * BKS;
     const int sw = (l32 >> 1) & 7;
 
     bf16x8_t fa[2][WTM], fb[2][WTN];
@@ -163,7 +177,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #define TLT_READ1(buf, pa, pb, kk, q)                                                                             \
     {                                                                                                             \
         const int ch = ((2 * (kk) + lhi) ^ sw) * 8;                                                               \
-        if ((q) < WTN) fb[buf][q] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)((pb) + fragB + (q) * 32 * BKS + ch)); \
+        if ((q) < WTN) fb[buf][q] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)((pb) + fragB + colrow(q) * BKS + ch)); \
         else fa[buf][(q) - WTN] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)((pa) + fragA + ((q) - WTN) * 32 * BKS + ch)); \
     }
 #define TLT_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
@@ -217,10 +231,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         for (int v = 0; v < 16; ++v) {
             int row = m0 + wm * (WTM * 32) + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
             if (row < M) {
+                if (GLU) {
 #pragma unroll
-                for (int j = 0; j < WTN; ++j) {
-                    int col = n0 + wn * (WTN * 32) + j * 32 + l32;
-                    store_out<OUT>(C, (int64_t)row * N + col, acc[i][j][v]);
+                    for (int j = 0; j < WTN / 2; ++j) {
+                        int col = n0 + wn * (WTN / 2 * 32) + j * 32 + l32;
+                        const float g = acc[i][j][v], u = acc[i][j + WTN / 2][v];
+                        store_out<OUT>(C, (int64_t)row * N + col, g / (1.0f + __expf(-g)) * u);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < WTN; ++j) {
+                        int col = n0 + wn * (WTN * 32) + j * 32 + l32;
+                        store_out<OUT>(C, (int64_t)row * N + col, acc[i][j][v]);
+                    }
                 }
             }
         }
@@ -280,27 +303,28 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
     }
 }
 
-template <int WGM, int WGN, int WTM, int WTN, int SA, int SB>
-static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false>
+static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C,
+                              const void* W2 = nullptr) {
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
-    const int nbm = (M + BM - 1) / BM, nbn = N / BN;
+    const int nbm = (M + BM - 1) / BM, nbn = N / (GLU ? BN / 2 : BN);
     const int total = nbm * nbn;
     const int per_xcd = (total + 7) / 8;
     const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
     dim3 grid(per_xcd * 8), block(64 * WGM * WGN);
 #define LAUNCH(OUT)                                                                                                   \
     {                                                                                                                 \
-        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT>;                                               \
+        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU>;                                          \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
             if (e != hipSuccess) return e;                                                                            \
             attr_set = true;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL(kern, grid, block, lds, s, M, N, K, (const uint16_t*)A, (const uint16_t*)W, C, nbm, total,  \
-                           per_xcd);                                                                                  \
+        hipLaunchKernelGGL(kern, grid, block, lds, s, M, N, K, (const uint16_t*)A, (const uint16_t*)W,                \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd);                                              \
     }
-    if (out_mode == OUT_T) LAUNCH(OUT_T)
+    if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
     else LAUNCH(OUT_ADD_F32)
 #undef LAUNCH
@@ -335,6 +359,20 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
         return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N, K, A, W, C);
     }
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
+}
+
+bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu) {
+    const bool aligned = (((uintptr_t)A | (uintptr_t)Wg | (uintptr_t)Wu) & 15) == 0;
+    return dtype == BF16 && M > 0 && aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)258 * K * 2 < ((int64_t)1 << 31);
+}
+
+// act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 in and out; call only when gemm_glu_supported().
+hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
+    const int tiles256 = ((M + 255) / 256) * (N / 128);   // a 256-row weight tile yields 128 output columns
+    const int tiles128 = ((M + 127) / 128) * (N / 64);
+    if (tiles256 >= 256) return launch_pipe<2, 2, 4, 4, 3, 2, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
+    if (tiles128 > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
+    return launch_pipe<2, 2, 2, 2, 3, 3, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
 }
 
 }  // namespace tlt

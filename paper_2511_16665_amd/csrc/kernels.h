@@ -37,6 +37,9 @@ struct KVLayer {
 
 // ---- gemm.hip
 hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C);
+// fused gate/up projection of the SwiGLU MLP (bf16 MFMA path only): act = silu(A Wg^T) * (A Wu^T)
+bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu);
+hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act);
 
 // ---- elementwise.hip
 hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x);
