@@ -32,8 +32,10 @@ __device__ __forceinline__ void store_out(void* C, int64_t idx, float v) {
         ((bf16*)C)[idx] = from_float<bf16>(v);
     else if (OUT == OUT_F32)
         ((float*)C)[idx] = v;
-    else
+    else if (OUT == OUT_ADD_F32)
         ((float*)C)[idx] += v;
+    else
+        unsafeAtomicAdd((float*)C + idx, v);   // split-K partial sums: hardware fp32 add at the L2
 }
 
 constexpr uint32_t vmcnt_imm(int n) { return 0x0F70u | (uint32_t)(n & 15) | ((uint32_t)(n >> 4) << 14); }
@@ -78,7 +80,8 @@ __device__ __forceinline__ void dma_buf_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
-                                                        void* __restrict__ C, int nbm, int total_tiles, int per_xcd) {
+                                                        void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
+                                                        int ksplit) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -97,7 +100,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     const int pid = blockIdx.x;
     const int logical = (pid & 7) * per_xcd + (pid >> 3);
     if (logical >= total_tiles) return;
-    const int tile_m = logical % nbm, tile_n = logical / nbm;
+    // M fastest, then the K split, then N: the workgroups that share a weight tile stay neighbours
+    const int tile_m = logical % nbm, split = (logical / nbm) % ksplit, tile_n = logical / (nbm * ksplit);
     constexpr int BNO = GLU ? BN / 2 : BN;            // output columns per workgroup
     static_assert(!GLU || (NW % 2 == 0 && WTN % 2 == 0), "gate and up halves split over waves and over a wave's column tiles");
     const int m0 = tile_m * BM, n0 = tile_n * BNO;
@@ -146,13 +150,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nt = K / BKS;
-    auto ktile = [&](int t) { return (t < nt ? t : nt - 1) * BKS; };   // past the end: harmless re-fetch of the last tile
+    // this workgroup's share of the K tiles (all of them unless the launch splits K)
+    const int nk_all = K / BKS;
+    const int kt0 = (int)((int64_t)nk_all * split / ksplit), nt = (int)((int64_t)nk_all * (split + 1) / ksplit) - kt0;
+    auto ktile = [&](int t) { return (kt0 + (t < nt ? t : nt - 1)) * BKS; };   // past the end: harmless re-fetch of the last tile
     // prologue: tile 0 first, then A tiles 1 .. SA-2, W tiles 1 .. SB-2 and the first half of W tile SB-1
 #pragma unroll
-    for (int d = 0; d < LA; ++d) TLT_DMA_A(0, 0, d)
+    for (int d = 0; d < LA; ++d) TLT_DMA_A(0, ktile(0), d)
 #pragma unroll
-    for (int d = 0; d < LB; ++d) TLT_DMA_B(0, 0, d)
+    for (int d = 0; d < LB; ++d) TLT_DMA_B(0, ktile(0), d)
 #pragma unroll
     for (int st = 1; st < SA - 1; ++st)
 #pragma unroll
@@ -305,10 +311,10 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
 
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false>
 static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C,
-                              const void* W2 = nullptr) {
+                              const void* W2 = nullptr, int ksplit = 1) {
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     const int nbm = (M + BM - 1) / BM, nbn = N / (GLU ? BN / 2 : BN);
-    const int total = nbm * nbn;
+    const int total = nbm * nbn * ksplit;
     const int per_xcd = (total + 7) / 8;
     const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
     dim3 grid(per_xcd * 8), block(64 * WGM * WGN);
@@ -322,11 +328,12 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             attr_set = true;                                                                                          \
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, N, K, (const uint16_t*)A, (const uint16_t*)W,                \
-                           (const uint16_t*)W2, C, nbm, total, per_xcd);                                              \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit);                                           \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
-    else LAUNCH(OUT_ADD_F32)
+    else if (ksplit == 1) LAUNCH(OUT_ADD_F32)
+    else LAUNCH(OUT_ATOMIC_ADD_F32)
 #undef LAUNCH
     return hipGetLastError();
 }
@@ -355,6 +362,18 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
         // otherwise 128x128 tiles: 80 KB of slots lets two workgroups share a CU when there are
         // more tiles than CUs, 96 KB buys a deeper prefetch when there are not
         if (N % 256 == 0 && tiles256 >= 256) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C);
+        // too few 256x256 tiles for the chip but a long K and an accumulating fp32 output: split K
+        // over several workgroups per tile, which add their partial sums with fp32 atomics (the
+        // order of those additions, and so the last bit of the result, is not fixed)
+        if (out_mode == OUT_ADD_F32 && N % 256 == 0) {
+            const int nk = K / kBK;
+            int ks = 256 / tiles256;
+            if (ks > nk / 16) ks = nk / 16;
+            // every split ends with a 256x256 tile of atomics: worth it for a long K only, or when M is
+            // small and the alternative leaves most of the chip idle while the weights stream in
+            const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
+            if (pays && tiles256 * ks >= 128) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
+        }
         if (tiles128 > 256) return launch_pipe<2, 2, 2, 2, 3, 2>(s, out_mode, M, N, K, A, W, C);
         return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N, K, A, W, C);
     }

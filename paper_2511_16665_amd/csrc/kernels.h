@@ -7,7 +7,7 @@
 namespace tlt {
 
 enum { F32 = 0, BF16 = 1 };
-enum { OUT_T = 0, OUT_F32 = 1, OUT_ADD_F32 = 2 };
+enum { OUT_T = 0, OUT_F32 = 1, OUT_ADD_F32 = 2, OUT_ATOMIC_ADD_F32 = 3 /* internal: split-K partial sums */ };
 
 // Rows of a layer forward, laid out [B][n].  Row (b, i) is active when i < n_valid[b] (all rows
 // when n_valid is null).  Its rotary position is seq_len[b] + pos_base + (pos_off ? pos_off[b*n+i]
