@@ -68,7 +68,18 @@ __global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restri
     const float* row = logits + (int64_t)blockIdx.x * V;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int j = threadIdx.x; j < V; j += 256) {
+    int j = threadIdx.x;
+    if (V % 4 == 0 && ((uintptr_t)logits & 15) == 0) {   // 16 bytes per lane; a lane's indices still increase
+        for (int q = threadIdx.x * 4; q < V; q += 1024) {
+            const float4 x = *(const float4*)(row + q);
+            if (x.x > bv || bi == 0x7fffffff) bv = x.x, bi = q;
+            if (x.y > bv) bv = x.y, bi = q + 1;
+            if (x.z > bv) bv = x.z, bi = q + 2;
+            if (x.w > bv) bv = x.w, bi = q + 3;
+        }
+        j = V;
+    }
+    for (; j < V; j += 256) {
         float v = row[j];
         if (better(v, j, bv, bi)) {
             bv = v;
@@ -80,64 +91,120 @@ __global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restri
 }
 
 // Log-softmax statistics and the K best tokens of every logits row, in two kernels.
-// (1) One workgroup per (row, segment of kTopkSeg logits): the segment is staged in LDS once, then
-//     its max, its sum of exponentials and its K best entries ("best element after the previous
-//     winner" in the (value desc, index asc) order, K rounds over LDS) are written out.
+// (1) One wave per (row, segment of kTopkSeg logits): the segment is read once into registers, then
+//     its max, its sum of exponentials and its K best entries in the (value desc, index asc) order
+//     are written out.
 // (2) One wave per row merges the segments: the K best of the union of the per-segment lists are
 //     the K best of the row because the order is total.
-constexpr int kTopkSeg = 8192;
+constexpr int kTopkSeg = 2048;     // logits per wave: 32 per lane, held in registers
+constexpr int kTopkPerLane = kTopkSeg / 64;
 
+// One WAVE per segment, no LDS and no barriers.  A lane owns 32 logits (eight 16-byte pieces, so
+// the wave's loads are fully coalesced) and keeps its two best in the (value desc, index asc) order.
+// Each of the K rounds takes the best lane candidate of the wave (xor-shuffle reduction) and the
+// winning lane moves on to its second candidate; only a lane that wins a third time has to rescan
+// its registers, which on real logits almost never happens, and the wave skips that code unless
+// some lane needs it.
+template <bool VEC4>
 __global__ __launch_bounds__(256) void row_topk_seg_k(int V, int K, int n_seg, const float* __restrict__ logits,
                                                       float* __restrict__ seg_stat, float* __restrict__ seg_val,
                                                       int32_t* __restrict__ seg_idx) {
-    __shared__ float buf[kTopkSeg];
-    __shared__ float sv[4];
-    __shared__ int si[4];
-    const int row = blockIdx.y, seg = blockIdx.x;
-    const int j0 = seg * kTopkSeg, len = min(kTopkSeg, V - j0);
-    const float* src = logits + (int64_t)row * V + j0;
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int j = threadIdx.x; j < len; j += 256) {
-        float v = src[j];
-        buf[j] = v;
-        if (better(v, j, bv, bi)) {
-            bv = v;
-            bi = j;
+    const int lane = threadIdx.x & 63;
+    const int seg = blockIdx.x * 4 + (threadIdx.x >> 6), row = blockIdx.y;
+    if (seg >= n_seg) return;  // wave-uniform
+    const int j0 = seg * kTopkSeg;
+    const float* src = logits + (int64_t)row * V;
+    float v[kTopkPerLane];
+    // element e of this lane has index j0 + (e / 4) * 256 + lane * 4 + (e % 4): increasing in e
+#pragma unroll
+    for (int c = 0; c < kTopkPerLane / 4; ++c) {
+        const int j = j0 + c * 256 + lane * 4;
+        if (VEC4) {
+            float4 x = j + 3 < V ? *(const float4*)(src + j) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (j + 3 >= V && j < V) {   // ragged end of the row
+                x.x = src[j];
+                x.y = j + 1 < V ? src[j + 1] : -INFINITY;
+                x.z = j + 2 < V ? src[j + 2] : -INFINITY;
+            }
+            v[4 * c] = x.x, v[4 * c + 1] = x.y, v[4 * c + 2] = x.z, v[4 * c + 3] = x.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[4 * c + e] = j + e < V ? src[j + e] : -INFINITY;
         }
     }
-    block_best(bv, bi, sv, si);  // includes the barriers that publish buf
-    const float mx = bv;
+    auto index_of = [&](int e) { return j0 + (e >> 2) * 256 + lane * 4 + (e & 3); };
+    // local best two; indices of a lane increase with e, so strict '>' keeps the lower index on ties
+    float b1 = -INFINITY, b2 = -INFINITY;
+    int e1 = -1, e2 = -1;
+#pragma unroll
+    for (int e = 0; e < kTopkPerLane; ++e) {
+        const float x = index_of(e) < V ? v[e] : -INFINITY;
+        const bool valid = index_of(e) < V;
+        if (valid && (e1 < 0 || x > b1)) {
+            b2 = b1, e2 = e1;
+            b1 = x, e1 = e;
+        } else if (valid && (e2 < 0 || x > b2)) {
+            b2 = x, e2 = e;
+        }
+    }
+    // softmax statistics of the segment
+    const float mx = wave_max(b1);
     float se = 0.f;
-    for (int j = threadIdx.x; j < len; j += 256) se += expf(buf[j] - mx);
-    se = block_sum_f(se, sv);
+#pragma unroll
+    for (int e = 0; e < kTopkPerLane; ++e) se += index_of(e) < V ? expf(v[e] - mx) : 0.f;
+    se = wave_sum(se);
     const int64_t o = (int64_t)row * n_seg + seg;
-    if (threadIdx.x == 0) {
+    if (lane == 0) {
         seg_stat[2 * o] = mx;
         seg_stat[2 * o + 1] = se;
     }
-    float pv = bv;
-    int pi = bi;
+    // K rounds
+    float cv = b1;                                  // this lane's current candidate
+    int ci = e1 >= 0 ? index_of(e1) : 0x7fffffff;
+    int wins = 0;
+    uint32_t taken = 0;                             // elements of this lane already emitted
     for (int k = 0; k < K; ++k) {
-        if (k > 0) {
-            float cv = -INFINITY;
-            int ci = 0x7fffffff;
-            for (int j = threadIdx.x; j < len; j += 256) {
-                float v = buf[j];
-                bool after = v < pv || (v == pv && j > pi);
-                if (after && better(v, j, cv, ci)) {
-                    cv = v;
-                    ci = j;
-                }
+        float wv = cv;
+        int wi = ci;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(wv, off, 64);
+            const int oi = __shfl_xor(wi, off, 64);
+            if (better(ov, oi, wv, wi)) {
+                wv = ov;
+                wi = oi;
             }
-            block_best(cv, ci, sv, si);
-            pv = cv;
-            pi = ci;
         }
-        if (threadIdx.x == 0) {
-            bool have = pi != 0x7fffffff;
-            seg_val[o * K + k] = have ? pv : -INFINITY;
-            seg_idx[o * K + k] = have ? j0 + pi : 0x7fffffff;
+        if (lane == 0) {
+            const bool have = wi != 0x7fffffff;
+            seg_val[o * K + k] = have ? wv : -INFINITY;
+            seg_idx[o * K + k] = have ? wi : 0x7fffffff;
+        }
+        const bool won = wi != 0x7fffffff && wi == ci;
+        if (won) {
+            ++wins;
+            const int e = ((ci - j0) >> 8) * 4 + ((ci - j0) & 3);
+            taken |= 1u << e;
+            if (wins == 1) {
+                cv = b2;
+                ci = e2 >= 0 ? index_of(e2) : 0x7fffffff;
+            }
+        }
+        if (__any(won && wins >= 2)) {   // rare: rescan the registers for the best element not yet emitted
+            if (won && wins >= 2) {
+                float nv = -INFINITY;
+                int ne = -1;
+#pragma unroll
+                for (int e = 0; e < kTopkPerLane; ++e) {
+                    const bool ok = index_of(e) < V && !((taken >> e) & 1u);
+                    if (ok && (ne < 0 || v[e] > nv)) {
+                        nv = v[e];
+                        ne = e;
+                    }
+                }
+                cv = nv;
+                ci = ne >= 0 ? index_of(ne) : 0x7fffffff;
+            }
         }
     }
 }
@@ -601,7 +668,11 @@ hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits
     float* seg_stat = (float*)ws;
     float* seg_val = seg_stat + (size_t)M * n_seg * 2;
     int32_t* seg_idx = (int32_t*)(seg_val + (size_t)M * n_seg * K);
-    hipLaunchKernelGGL(row_topk_seg_k, dim3(n_seg, M), dim3(256), 0, s, V, K, n_seg, logits, seg_stat, seg_val, seg_idx);
+    const dim3 grid((n_seg + 3) / 4, M);
+    if (V % 4 == 0 && ((uintptr_t)logits & 15) == 0)
+        hipLaunchKernelGGL(row_topk_seg_k<true>, grid, dim3(256), 0, s, V, K, n_seg, logits, seg_stat, seg_val, seg_idx);
+    else
+        hipLaunchKernelGGL(row_topk_seg_k<false>, grid, dim3(256), 0, s, V, K, n_seg, logits, seg_stat, seg_val, seg_idx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(row_topk_merge_k, dim3(M), dim3(64), 0, s, K, n_seg, seg_stat, seg_val, seg_idx, tok, logp);
