@@ -177,7 +177,10 @@ KVLayer kv_layer(const tlt_ctx* ctx, const tlt_kv* kv, int layer) {
 }
 
 // One decoder block over M = rows.B * rows.n rows whose residual stream sits in the workspace's x.
-int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const Rows& rows, const KVLayer& kv) {
+// reuse_attn_plan: the attention work list in the workspace was built by an earlier layer of the same
+// forward (same rows, same sequence lengths) and is still valid.
+int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const Rows& rows, const KVLayer& kv,
+                  bool reuse_attn_plan = false) {
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -196,7 +199,8 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
         const double bytes = keys * 2.0 * c.n_kv_heads * c.head_dim * e + 2.0 * M * q_dim * e;
         const double flops = 4.0 * c.head_dim * c.n_q_heads * (double)rows.n * keys;
         TLT_RUN(ctx, s, ctx->in_draft ? CLS_ATTN_DRAFT : CLS_ATTN, flops, bytes,
-                attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl));
+                attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl,
+                          reuse_attn_plan));
     }
     if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
@@ -331,7 +335,7 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
     rows.mask_words = 1;
     rows.n_region = n;
     for (int l = 0; l < c.n_layers; ++l) {
-        rc = layer_forward(ctx, s, ctx->target.layers[l], rows, kv_layer(ctx, kv, l));
+        rc = layer_forward(ctx, s, ctx->target.layers[l], rows, kv_layer(ctx, kv, l), l > 0);
         if (rc) return rc;
     }
     if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));

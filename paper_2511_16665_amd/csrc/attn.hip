@@ -592,7 +592,8 @@ size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, in
 
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                                   int n_q_heads, const AttnPlan& p, AttnWork* work, float* part_o, float* part_ml) {
+                                   int n_q_heads, const AttnPlan& p, AttnWork* work, float* part_o, float* part_ml,
+                                   bool reuse_plan) {
     const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t) +
                        (size_t)kMaxRows * 2 * sizeof(uint64_t);
     if (rows.n > kMaxRows) return hipErrorInvalidValue;
@@ -605,7 +606,8 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     }
     const int tiles_per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)kD);
-    hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work);
+    if (!reuse_plan)
+        hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work);
     hipLaunchKernelGGL(kern, dim3(p.max_items * p.heads), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
                        part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2);
     hipError_t e = hipGetLastError();
@@ -617,7 +619,7 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
 }
 
 hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                     int n_q_heads, void* ws, size_t ws_bytes, int impl) {
+                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan) {
     if (rows.B * rows.n <= 0) return hipSuccess;
     if (kv.d % 64 != 0 || kv.d > 256) return hipErrorInvalidValue;
     const int G = n_q_heads / kv.n_kv;
@@ -629,9 +631,9 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
             float* part_o = (float*)((char*)ws + attn_work_bytes(rows.B, p.max_items));
             float* part_ml = part_o + (size_t)p.max_items * kv.n_kv * p.r_pad * kD;
             switch (p.tpw) {
-                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
-                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
-                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml);
+                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
+                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
+                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
             }
         }
         if (impl == 1) return hipErrorInvalidValue;  // explicitly requested but the workspace cannot hold it

@@ -361,7 +361,9 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
         // 256x256 tiles (three A slots + two W slots = all 160 KB of LDS) when they fill the chip;
         // otherwise 128x128 tiles: 80 KB of slots lets two workgroups share a CU when there are
         // more tiles than CUs, 96 KB buys a deeper prefetch when there are not
-        if (N % 256 == 0 && tiles256 >= 256) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C);
+        // (with M <= 64 three quarters of a 256-row tile would be padding: the 128x128 tiles stream the
+        // weights faster)
+        if (N % 256 == 0 && tiles256 >= 256 && M > 64) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C);
         // too few 256x256 tiles for the chip but a long K and an accumulating fp32 output: split K
         // over several workgroups per tile, which add their partial sums with fp32 atomics (the
         // order of those additions, and so the last bit of the result, is not fixed)

@@ -65,7 +65,7 @@ hipError_t iota_scaled(hipStream_t s, int n, int32_t* out, int scale);
 // ---- attn.hip
 size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx);
 hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                     int n_q_heads, void* ws, size_t ws_bytes, int impl);
+                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan = false);
 
 // ---- sample.hip
 hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
