@@ -77,6 +77,7 @@ __device__ __forceinline__ void dma_buf_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t
 // followed by the same BN/2 rows of W2 (up); each wave multiplies both halves for its columns and
 // the epilogue stores silu(gate) * up, so C is [M][N] with N counting gate columns and the two
 // intermediate matrices never exist.
+// (The kernel's N is only the row stride of C: which column tiles exist is decided by total_tiles.)
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
@@ -311,8 +312,10 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
 
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false>
 static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C,
-                              const void* W2 = nullptr, int ksplit = 1) {
+                              const void* W2 = nullptr, int ksplit = 1, int ldc = 0) {
+    // N counts the output columns this launch covers; ldc (default N) is the row stride of C
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
+    if (ldc == 0) ldc = N;
     const int nbm = (M + BM - 1) / BM, nbn = N / (GLU ? BN / 2 : BN);
     const int total = nbm * nbn * ksplit;
     const int per_xcd = (total + 7) / 8;
@@ -327,7 +330,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             if (e != hipSuccess) return e;                                                                            \
             attr_set = true;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL(kern, grid, block, lds, s, M, N, K, (const uint16_t*)A, (const uint16_t*)W,                \
+        hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
                            (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit);                                           \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
@@ -350,24 +353,59 @@ static hipError_t launch_generic(hipStream_t s, int out_mode, int M, int N, int 
     return hipGetLastError();
 }
 
+// 256x256 tiles over the columns that fill whole rounds of the chip's 256 CUs, 128x128 tiles (two
+// workgroups per CU) over the rest: a last round that would leave most CUs idle is replaced by a
+// shorter one.  glu: W/W2 are the gate/up matrices and N counts gate columns (a 256-row weight tile
+// then yields 128 output columns, a 128-row one 64).
+static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W,
+                               const void* W2, void* C, bool glu) {
+    const int bno256 = glu ? 128 : 256, bno128 = glu ? 64 : 128;
+    const int nbm256 = (M + 255) / 256, nbm128 = (M + 127) / 128;
+    const int nbn256 = N / bno256;   // whole 256-wide column tiles
+    const size_t c_elt = (glu || out_mode == OUT_T) ? 2 : 4;
+    auto small = [&](int n_cols, int col0) -> hipError_t {
+        const int tiles = nbm128 * (n_cols / bno128);
+        const void* w = (const uint16_t*)W + (int64_t)col0 * K;
+        const void* w2 = W2 ? (const uint16_t*)W2 + (int64_t)col0 * K : nullptr;
+        void* c = (char*)C + (size_t)col0 * c_elt;
+        if (glu) {
+            if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
+            return launch_pipe<2, 2, 2, 2, 3, 3, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
+        }
+        if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+        return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+    };
+    auto big = [&](int n_cols) -> hipError_t {
+        if (glu) return launch_pipe<2, 2, 4, 4, 3, 2, true>(s, OUT_T, M, n_cols, K, A, W, C, W2, 1, N);
+        return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, n_cols, K, A, W, C, nullptr, 1, N);
+    };
+    const int tiles256 = nbm256 * nbn256;
+    // (with M <= 64 three quarters of a 256-row tile would be padding: the 128x128 tiles stream the
+    // weights faster)
+    if (M <= 64 || tiles256 < 256) return small(N, 0);
+    const int full_rounds = tiles256 / 256;
+    const int main_nbn = full_rounds * 256 / nbm256;          // column tiles that make up the whole rounds
+    const int rest_cols = N - main_nbn * bno256;
+    const int rest_tiles256 = tiles256 - main_nbn * nbm256 + (N % bno256 ? nbm256 : 0);
+    if (main_nbn == 0) return N % bno256 == 0 ? big(N) : small(N, 0);
+    if (rest_cols == 0) return big(N);
+    if (rest_tiles256 > 160 && N % bno256 == 0) return big(N);   // the last round is well filled as it is
+    hipError_t e = big(main_nbn * bno256);
+    if (e != hipSuccess) return e;
+    return small(rest_cols, main_nbn * bno256);
+}
+
 hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
     if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
     if (dtype == F32) return launch_generic<float>(s, out_mode, M, N, K, A, W, C);
     const bool aligned = (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
-    // per-lane DMA offsets are 32-bit element offsets inside a 256-row panel
+    // per-lane DMA offsets are 32-bit byte offsets inside a 256-row panel
     if (aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)258 * K * 2 < ((int64_t)1 << 31)) {
         const int tiles256 = ((M + 255) / 256) * (N / 256);
-        const int tiles128 = ((M + 127) / 128) * (N / 128);
-        // 256x256 tiles (three A slots + two W slots = all 160 KB of LDS) when they fill the chip;
-        // otherwise 128x128 tiles: 80 KB of slots lets two workgroups share a CU when there are
-        // more tiles than CUs, 96 KB buys a deeper prefetch when there are not
-        // (with M <= 64 three quarters of a 256-row tile would be padding: the 128x128 tiles stream the
-        // weights faster)
-        if (N % 256 == 0 && tiles256 >= 256 && M > 64) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C);
         // too few 256x256 tiles for the chip but a long K and an accumulating fp32 output: split K
         // over several workgroups per tile, which add their partial sums with fp32 atomics (the
         // order of those additions, and so the last bit of the result, is not fixed)
-        if (out_mode == OUT_ADD_F32 && N % 256 == 0) {
+        if (out_mode == OUT_ADD_F32 && N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
             const int nk = K / kBK;
             int ks = 256 / tiles256;
             if (ks > nk / 16) ks = nk / 16;
@@ -376,8 +414,7 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
             const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
             if (pays && tiles256 * ks >= 128) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
         }
-        if (tiles128 > 256) return launch_pipe<2, 2, 2, 2, 3, 2>(s, out_mode, M, N, K, A, W, C);
-        return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N, K, A, W, C);
+        return launch_tiled(s, out_mode, M, N, K, A, W, nullptr, C, false);
     }
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
 }
@@ -389,11 +426,7 @@ bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const voi
 
 // act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 in and out; call only when gemm_glu_supported().
 hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
-    const int tiles256 = ((M + 255) / 256) * (N / 128);   // a 256-row weight tile yields 128 output columns
-    const int tiles128 = ((M + 127) / 128) * (N / 64);
-    if (tiles256 >= 256) return launch_pipe<2, 2, 4, 4, 3, 2, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
-    if (tiles128 > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
-    return launch_pipe<2, 2, 2, 2, 3, 3, true>(s, OUT_T, M, N, K, A, Wg, act, Wu);
+    return launch_tiled(s, OUT_T, M, N, K, A, Wg, Wu, act, true);
 }
 
 }  // namespace tlt

@@ -45,6 +45,7 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (1000, 16384, 128),   # 256x256 tiles (>= 256 of them), ragged M tail
     (50, 200, 96),        # shape the MFMA path cannot take -> generic kernel on bf16
     (1100, 3584, 2048),   # few 256x256 tiles, long K: split-K with atomic accumulation in mode 2, ragged M tail
+    (1000, 16768, 128),   # 256x256 tiles for the whole rounds of the chip + 128x128 tiles for the remaining columns
     (200, 512, 1600),     # 25 K tiles split unevenly over 3 workgroups per tile... when the chip is under-filled
 ])
 def test_gemm_bf16(M, N, K, out_mode):
