@@ -49,3 +49,29 @@ def rel_err(got, want):
     want = np.asarray(want, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
+
+
+class LazyLayers:
+    """Widens one decoder layer at a time to float64 on the host (all layers of a 7B shape at once
+    would be tens of GB); prints the layer index so a long oracle run shows progress."""
+
+    def __init__(self, layers):
+        self.layers = layers
+
+    def __len__(self):
+        return len(self.layers)
+
+    def __iter__(self):
+        for l, lw in enumerate(self.layers):
+            print(f"  oracle layer {l}", flush=True)
+            yield dec.weights_to_f64(lw)
+
+
+class EmbedRows:
+    """Embedding table kept on the device; rows are widened to float64 when the oracle indexes it."""
+
+    def __init__(self, w):
+        self.w = w
+
+    def __getitem__(self, idx):
+        return self.w[torch.as_tensor(np.asarray(idx), device=self.w.device).long()].double().cpu().numpy()

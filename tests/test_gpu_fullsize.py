@@ -30,6 +30,8 @@ from oracle import sd
 
 from paper_2511_16665_amd import binding as tlt
 
+from gpu_util import EmbedRows as _EmbedRows
+from gpu_util import LazyLayers as _LazyLayers
 from gpu_util import dense_cache, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -39,29 +41,6 @@ TOL = 2e-2
 
 def stack_tol(n_layers):
     return max(TOL, 1e-2 * np.sqrt(n_layers))
-
-
-class _LazyLayers:
-    """Widens one decoder layer at a time to float64 on the host (28 layers at once would be 52 GB)."""
-
-    def __init__(self, layers):
-        self.layers = layers
-
-    def __len__(self):
-        return len(self.layers)
-
-    def __iter__(self):
-        for l, lw in enumerate(self.layers):
-            print(f"  oracle layer {l}", flush=True)
-            yield dec.weights_to_f64(lw)
-
-
-class _EmbedRows:
-    def __init__(self, w):
-        self.w = w
-
-    def __getitem__(self, idx):
-        return self.w[torch.as_tensor(np.asarray(idx), device=self.w.device).long()].double().cpu().numpy()
 
 
 def test_full_size_step_properties_and_sampled_parity():
