@@ -185,6 +185,42 @@ enum { TLT_PROFILE_CLASSES = 6 };
 int tlt_profile_begin(tlt_ctx *ctx, int enable);
 int tlt_profile_read(tlt_ctx *ctx, double *ms, int64_t *launches, double *flops, double *bytes);
 
+/* ---- strategy selection (host only: no GPU work, no stream) ---------------------------------
+ * The Bucketed-Epsilon-Greedy selector of Algorithm 1 (Section 5.2) with the elastic activation
+ * rule of Section 5.1.  A strategy is (Draft_Depth, topK, Tokens_to_Verify).  Strategies are grouped
+ * by Tokens_to_Verify in descending order and group i serves the batch-size bucket
+ * [thresholds[i], thresholds[i+1] - 1] (the last bucket is open-ended; batch sizes below
+ * thresholds[0] use the first bucket), so n_thresholds must equal the number of distinct
+ * Tokens_to_Verify values and thresholds must increase strictly.  Every strategy keeps the rewards
+ * and mean emitted lengths of its last `window` recorded steps.
+ *
+ * tlt_mab_select: writes the chosen strategy's index (position in the `strategies` array given at
+ * creation) or -1 when batch_size >= sd_threshold (speculation off, decode normally).  A bucket with
+ * one strategy returns it.  Otherwise u = (u1 + 0.5) / 2^32 < epsilon explores: candidate number
+ * floor(u2 * |V| / 2^32) in creation order; else the candidate with the largest median reward over
+ * its window wins (an empty window counts as +infinity, so untried strategies go first; an even
+ * count takes the mean of the middle pair; ties go to the earlier candidate).  u1, u2 are the
+ * caller's uniform 32-bit random numbers.
+ *
+ * tlt_mab_record: for the step just run with `strategy`: a = sum(accept_lens) / batch_size + 1,
+ * reward = a * batch_size / elapsed_time (emitted tokens per unit time); both are appended to the
+ * strategy's windows and returned through a_bar / reward when those are not NULL.  accept_lens is
+ * a HOST array of batch_size entries (accepted draft tokens per sequence, bonus token excluded).
+ *
+ * All arrays are HOST memory and are copied; errors: TLT_EINVAL. */
+typedef struct tlt_strategy {
+    int32_t draft_depth, topk, tokens_to_verify;
+} tlt_strategy;
+typedef struct tlt_mab tlt_mab;
+int tlt_mab_create(const tlt_strategy *strategies, int n_strategies, const int32_t *thresholds, int n_thresholds,
+                   double epsilon, int window, int sd_threshold, tlt_mab **out);
+void tlt_mab_destroy(tlt_mab *mab);
+int tlt_mab_select(tlt_mab *mab, int batch_size, uint32_t u1, uint32_t u2, int32_t *strategy);
+int tlt_mab_record(tlt_mab *mab, int strategy, double elapsed_time, const int32_t *accept_lens, int batch_size,
+                   double *a_bar, double *reward);
+/* Median reward over the strategy's window (+infinity when empty) and the number of entries held. */
+int tlt_mab_median_reward(const tlt_mab *mab, int strategy, double *median, int32_t *count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,8 @@ ERRORS = {0: "TLT_OK", -1: "TLT_EINVAL", -2: "TLT_ESHAPE", -3: "TLT_ENOPAGES", -
 EXPORTS = [
     "tlt_strerror", "tlt_last_hip_error", "tlt_workspace_bytes", "tlt_create", "tlt_destroy", "tlt_draft_expand",
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
-    "tlt_profile_begin", "tlt_profile_read",
+    "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
+    "tlt_mab_median_reward",
 ]
 
 
@@ -44,6 +45,10 @@ class LayerWeightsC(C.Structure):
 class WeightsC(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
                 ("layers", C.POINTER(LayerWeightsC)), ("fc", C.c_void_p)]
+
+
+class StrategyC(C.Structure):
+    _fields_ = [("draft_depth", C.c_int32), ("topk", C.c_int32), ("tokens_to_verify", C.c_int32)]
 
 
 class KVC(C.Structure):
@@ -87,6 +92,14 @@ def load() -> C.CDLL:
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
+    lib.tlt_mab_create.argtypes = [C.POINTER(StrategyC), C.c_int, C.POINTER(C.c_int32), C.c_int, C.c_double, C.c_int, C.c_int,
+                                   C.POINTER(C.c_void_p)]
+    lib.tlt_mab_destroy.argtypes = [C.c_void_p]
+    lib.tlt_mab_destroy.restype = None
+    lib.tlt_mab_select.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.POINTER(C.c_int32)]
+    lib.tlt_mab_record.argtypes = [C.c_void_p, C.c_int, C.c_double, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_double),
+                                   C.POINTER(C.c_double)]
+    lib.tlt_mab_median_reward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -246,6 +259,53 @@ class Context:
         self._check(self.lib.tlt_profile_read(self.handle, ms, n, fl, by), "tlt_profile_read")
         names = ("gemm", "attention", "kv_commit", "other", "gemm_draft", "attention_draft")
         return {k: {"ms": ms[i], "launches": n[i], "flops": fl[i], "bytes": by[i]} for i, k in enumerate(names)}
+
+
+class Mab:
+    """tlt_mab_*: the strategy selector (host only).  strategies: (Draft_Depth, topK, Tokens_to_Verify) tuples."""
+
+    def __init__(self, strategies, thresholds, epsilon, window, sd_threshold=32):
+        arr = (StrategyC * len(strategies))(*[StrategyC(*map(int, s)) for s in strategies])
+        thr = (C.c_int32 * len(thresholds))(*map(int, thresholds))
+        self.h = C.c_void_p()
+        rc = load().tlt_mab_create(arr, len(strategies), thr, len(thresholds), float(epsilon), int(window),
+                                   int(sd_threshold), C.byref(self.h))
+        if rc:
+            raise TltError(rc, "tlt_mab_create")
+
+    def select(self, batch_size, u1, u2):
+        """Strategy index, or None while speculation is switched off for this batch size."""
+        out = C.c_int32()
+        rc = load().tlt_mab_select(self.h, int(batch_size), int(u1), int(u2), C.byref(out))
+        if rc:
+            raise TltError(rc, "tlt_mab_select")
+        return None if out.value < 0 else out.value
+
+    def record(self, strategy, elapsed_time, accept_lens, batch_size):
+        a, r = C.c_double(), C.c_double()
+        lens = (C.c_int32 * len(accept_lens))(*map(int, accept_lens))
+        rc = load().tlt_mab_record(self.h, int(strategy), float(elapsed_time), lens, int(batch_size), C.byref(a), C.byref(r))
+        if rc:
+            raise TltError(rc, "tlt_mab_record")
+        return a.value, r.value
+
+    def median_reward(self, strategy):
+        m, n = C.c_double(), C.c_int32()
+        rc = load().tlt_mab_median_reward(self.h, int(strategy), C.byref(m), C.byref(n))
+        if rc:
+            raise TltError(rc, "tlt_mab_median_reward")
+        return m.value, n.value
+
+    def close(self):
+        if self.h:
+            load().tlt_mab_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def gemm(dtype_code, out_mode, A, W, Cout):

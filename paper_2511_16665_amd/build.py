@@ -13,14 +13,16 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtlt.so")
-SOURCES = ["api.hip", "gemm.hip", "attn.hip", "elementwise.hip", "sample.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attn.hip", "elementwise.hip", "sample.hip", "mab.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    # host-only sources (.cpp) need none of the device flags
+    flags = FLAGS if src.endswith(".hip") else ["-O2", "-std=c++17", "-fPIC", "-Wall"]
+    cmd = ["hipcc", *flags, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
