@@ -538,15 +538,17 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     }
 }
 
-// One wave per (b, kv head, row): merges the chunks' partial outputs (running max in raw score units).
-__global__ __launch_bounds__(64) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
+// One wave per (b, kv head, row), four rows per workgroup: merges the chunks' partial outputs
+// (running max in raw score units).
+__global__ __launch_bounds__(256) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
                                                      const float* __restrict__ part_ml, uint16_t* __restrict__ out,
                                                      const AttnWork* __restrict__ work, int n_q_heads, int max_items,
                                                      int r_pad, float scale_log2) {
-    const int r = blockIdx.x, kh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), kh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x & 63;
     const int G = n_q_heads / kv.n_kv;
-    const int i = r / G, gq = r - i * G;
     const int n = rows.n;
+    if (r >= n * G) return;  // wave-uniform
+    const int i = r / G, gq = r - i * G;
     const int nv = rows.n_valid ? min(rows.n_valid[b], n) : n;
     uint32_t* o = (uint32_t*)(out + ((int64_t)(b * n + i) * n_q_heads + kh * G + gq) * kD);
     const int* slot0 = (const int*)(work + 1);
@@ -613,7 +615,7 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int R = rows.n * (n_q_heads / kv.n_kv);
-    hipLaunchKernelGGL(attn_combine_k, dim3(R, kv.n_kv, rows.B), dim3(64), 0, s, rows, kv, part_o, part_ml,
+    hipLaunchKernelGGL(attn_combine_k, dim3((R + 3) / 4, kv.n_kv, rows.B), dim3(256), 0, s, rows, kv, part_o, part_ml,
                        (uint16_t*)out, work, n_q_heads, p.max_items, p.r_pad, scale_log2);
     return hipGetLastError();
 }

@@ -41,6 +41,47 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, const float* __restrict_
     for (int c = threadIdx.x; c < h; c += 256) o[c] = from_float<T>(xr[c] * inv * to_float(gamma[c]));
 }
 
+// Same, for h % 4 == 0 and h <= 4096: the row is read once with 16-byte loads and stays in registers
+// between the reduction and the scaling.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, const float* __restrict__ x, const T* __restrict__ gamma,
+                                                     float eps, T* __restrict__ out, const int32_t* __restrict__ row_map) {
+    __shared__ float red[4];
+    const int r = blockIdx.x, h4 = h >> 2;
+    const int64_t src = row_map ? row_map[r] : r;
+    T* o = out + (int64_t)r * h;
+    float4 v[4];
+    float ss = 0.f;
+    if (src >= 0) {
+        const float4* xr = (const float4*)(x + src * h);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = threadIdx.x + k * 256;
+            v[k] = c < h4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float inv = src >= 0 ? 1.0f / sqrtf(tot / (float)h + eps) : 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = threadIdx.x + k * 256;
+        if (c >= h4) continue;
+        const T* g = gamma + 4 * c;
+        float y[4] = {v[k].x * inv * to_float(g[0]), v[k].y * inv * to_float(g[1]), v[k].z * inv * to_float(g[2]),
+                      v[k].w * inv * to_float(g[3])};
+        if (src < 0) y[0] = y[1] = y[2] = y[3] = 0.f;
+        if constexpr (sizeof(T) == 2) {
+            *(uint2*)(o + 4 * c) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+        } else {
+            *(float4*)(o + 4 * c) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    }
+}
+
 // One workgroup per row.  Angles are formed in double (positions reach 32K, where an fp32 product
 // pos * inv_freq already carries ~1e-3 rad of rounding), once per (row, pair index), then reused by
 // every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.
@@ -179,7 +220,11 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map) {
     if (M <= 0) return hipSuccess;
-    DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+    if (h % 4 == 0 && h <= 4096 && ((uintptr_t)x & 15) == 0) {
+        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_vec_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+    } else {
+        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+    }
     return hipGetLastError();
 }
 
