@@ -172,7 +172,7 @@ def recorded_traffic(key):
     """HBM-side bytes per launch from the committed counter summary (two rocprofv3 --pmc runs of this
     same command, scaled by a plain copy of known size); None when there is no such record."""
     import re
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_sd_step_7b_b32_n48.md")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_and_mfma_sd_step_7b_b32_n48.md")
     try:
         m = re.search(r"traffic_bytes_per_launch %s = (\d+)" % re.escape(key), open(path).read())
         return float(m.group(1)) if m else None
@@ -247,17 +247,16 @@ def main():
                                f"{args.ctx_median}, sigma 0.8, cap {args.ctx_cap}) = {int(ctx.sum())} cached tokens, "
                                f"16-token pages, tree depth {D} top-k {K} verify {N}, greedy",
                    "accepted_per_step": round(emitted / args.steps, 2), "drafter": "random-init (accept length ~0)"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dtl_k (verification forward GEMMs)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_k (GEMMs of the verification forward; one launch here = one library GEMM = one or two kernel launches)",
                      "achieved": round(gemm_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": recorded_traffic("gemm_bf16_dtl_k_verify") if default_workload else None,
+                     "traffic": recorded_traffic("gemm_bf16_pipe_k_verify") if default_workload else None,
                      "avg_launch_us": round(g["ms"] / max(g["launches"], 1) * 1e3, 2),
                      "flops_per_launch": round(g["flops"] / max(g["launches"], 1), 0),
-                     # every launch of the kernel in the step (drafter included): the figure a
-                     # kernel trace of the same command averages to over all its instantiations
-                     "avg_launch_us_all": round((g["ms"] + prof["gemm_draft"]["ms"])
-                                                / max(g["launches"] + prof["gemm_draft"]["launches"], 1) * 1e3, 2)},
-        "attention_roofline": {"bound": "hbm", "kernel": "attn_mfma_k + attn_combine_k (verification forward)",
+                     # the kernel's time per step over ALL its launches (drafter included): the figure a
+                     # kernel trace of the same command sums to over the kernel's instantiations
+                     "kernel_ms_per_step_all": round((g["ms"] + prof["gemm_draft"]["ms"]) / args.steps, 3)},
+        "attention_roofline": {"bound": "hbm", "kernel": "attn_plan_k + attn_mfma_k + attn_combine_k (verification forward)",
                                "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
                                "bytes_per_launch": round(attn_bytes_per_step / cfg.n_layers, 0),
