@@ -123,6 +123,11 @@ class Engine:
         self.pending_max_new = inc
         return al, out
 
+    # -- the same step replayed from captured HIP graphs
+    def graph_pool(self, capacity_bound=None) -> "GraphPool":
+        """Graph pool over this engine's buffers (see GraphPool)."""
+        return GraphPool(self, capacity_bound)
+
     def _buf(self, kind, n):
         key = (kind, n)
         if key not in self._trees:
@@ -131,3 +136,98 @@ class Engine:
             else:
                 self._trees[key] = torch.zeros((self.B, n), dtype=torch.int32, device="cuda")
         return self._trees[key]
+
+
+class GraphPool:
+    """Bucketed, disaggregated, merged HIP-graph capture of the SD step (Section 5.1, "Memory-Efficient
+    CUDAGraph Capture", re-thought for this library).
+
+    * Bucketed: a graph is captured per batch-size bucket, not per batch size; a step with B running
+      sequences replays the graph of the smallest bucket >= B over the first `bucket` slots of the
+      engine's buffers (slots B..bucket-1 must hold valid sequences: the caller keeps finished ones
+      there until it compacts).
+    * Disaggregated: the drafter's graph (tlt_draft_expand) is keyed by (bucket, Draft_Depth, topK,
+      Tokens_to_Verify, rows of the previous step's hidden buffer); the target's graph
+      (tlt_verify_forward + tlt_accept + tlt_kv_commit) by (bucket, nodes per tree).
+    * Merged: strategies that share a key share the graph.
+
+    What makes this cheap here: every buffer a kernel touches (workspace, trees, caches, outputs) is
+    owned by the caller and shared by all graphs, and sequence lengths are read on the device, so a graph
+    holds kernel nodes and their arguments only: no per-graph activation memory.  The host-side length
+    bounds that size the attention grids are frozen at capture time, so graphs are captured with the
+    caches' capacity as the bound (`capacity_bound`, default: what the block tables can hold).
+
+    Greedy acceptance only; the caller reads accept_len / out_tokens when it needs them (no host
+    synchronisation happens inside a replay)."""
+
+    def __init__(self, engine: Engine, capacity_bound=None, buckets=(1, 2, 4, 8, 16, 32, 64, 128)):
+        self.e = engine
+        self.buckets = tuple(b for b in buckets if b < engine.B) + (engine.B,)
+        page = engine.cfg.page_size
+        cap = min(engine.kv.block_table.shape[1], engine.dkv.block_table.shape[1]) * page
+        self.bound = int(capacity_bound) if capacity_bound is not None else cap - 2 * engine.max_n - 64
+        self.draft_graphs, self.target_graphs = {}, {}
+        self.stream = torch.cuda.Stream()          # default priority
+
+    def bucket(self, B):
+        for b in self.buckets:
+            if b >= B:
+                return b
+        raise ValueError(f"batch {B} exceeds the engine's {self.e.B}")
+
+    def _capture(self, fn, also_keep=()):
+        """Runs fn once eagerly (first-use set-up such as kernel attributes must not fall into a
+        capture), then captures it.  The eager run's side effects on the step's state are undone."""
+        e = self.e
+        saved = (e.kv.seq_len_bound, e.dkv.seq_len_bound)
+        e.kv.seq_len_bound = e.dkv.seq_len_bound = self.bound
+        # the eager run changes state (cache lengths, pending tokens): snapshot and restore it
+        state = (e.kv.seq_len, e.dkv.seq_len, e.accept_len, e.n_out, e.path_idx, e.out_tokens) + tuple(also_keep)
+        keep = [t.clone() for t in state]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(self.stream):
+            fn()
+        torch.cuda.synchronize()
+        for dst, src in zip(state, keep):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=self.stream):
+            fn()
+        torch.cuda.synchronize()
+        e.kv.seq_len_bound, e.dkv.seq_len_bound = saved
+        return g
+
+    def step(self, B, topk, depth, n_verify):
+        """One SD step for the first B slots, replayed from the pool (captured on first use).
+        Requires a pending hidden buffer from a previous step (Engine.step / set_pending)."""
+        e = self.e
+        assert e.have_pending and e.pending_hidden is not None
+        Bk = self.bucket(B)
+        pool = topk + (depth - 1) * topk * topk if depth >= 1 else 0
+        n = min(n_verify, 1 + pool)
+        t = e.tree(n)
+        hid_prev = e.pending_hidden
+        hid, am = e._buf("hid", n), e._buf("am", n)
+        dkey = (Bk, depth, topk, n_verify, hid_prev.data_ptr(), hid_prev.shape[1])
+        tkey = (Bk, n)
+        if dkey not in self.draft_graphs:
+            self.draft_graphs[dkey] = self._capture(lambda: e.ctx.draft_expand(
+                Bk, depth, topk, n_verify, e.out_tokens, e.path_idx, e.n_out, hid_prev, None, e.dkv, t))
+        if tkey not in self.target_graphs:
+            def target():
+                e.ctx.verify_forward(Bk, t, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
+                e.ctx.accept(Bk, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx,
+                             e.out_tokens, e.n_out)
+                e.ctx.kv_commit(Bk, e.kv, e.accept_len, e.path_idx, e.stride)
+            self.target_graphs[tkey] = self._capture(target, also_keep=(hid_prev,))   # hid may alias hid_prev
+        self.draft_graphs[dkey].replay()
+        self.target_graphs[tkey].replay()
+        e.pending_hidden = hid
+        inc = min(depth, n - 1) + 1
+        e.dkv.seq_len_bound += e.pending_max_new
+        e.kv.seq_len_bound += inc
+        e.pending_max_new = inc
+
+    def n_graphs(self):
+        return len(self.draft_graphs), len(self.target_graphs)
