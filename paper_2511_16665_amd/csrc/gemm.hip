@@ -382,7 +382,9 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     const int tiles256 = nbm256 * nbn256;
     // (with M <= 64 three quarters of a 256-row tile would be padding: the 128x128 tiles stream the
     // weights faster)
-    if (M <= 64 || tiles256 < 256) return small(N, 0);
+    if (M <= 64 || tiles256 < 100) return small(N, 0);
+    // a hundred or more big tiles stream cold weights faster than twice as many TA-bound small ones
+    if (tiles256 < 256) return N % bno256 == 0 ? big(N) : small(N, 0);
     const int full_rounds = tiles256 / 256;
     const int main_nbn = full_rounds * 256 / nbm256;          // column tiles that make up the whole rounds
     const int rest_cols = N - main_nbn * bno256;
