@@ -221,6 +221,32 @@ int tlt_mab_record(tlt_mab *mab, int strategy, double elapsed_time, const int32_
 /* Median reward over the strategy's window (+infinity when empty) and the number of entries held. */
 int tlt_mab_median_reward(const tlt_mab *mab, int strategy, double *median, int32_t *count);
 
+/* ---- model-free drafter (host only) ----------------------------------------------------------
+ * The n-gram retrieval drafter of Section 5.3: a database per prompt, filled from that prompt's
+ * rollout responses, that proposes a candidate tree from the tokens preceding the position to predict.
+ * It is a second producer of tlt_tree: the arrays it writes are HOST memory; copy them to the device
+ * and call tlt_tree_finalize, then tlt_verify_forward / tlt_accept / tlt_kv_commit as with the
+ * learned drafter's trees.
+ *
+ * order n: tlt_ngram_insert adds, for every window of k+1 consecutive tokens (k = 1 .. n-1) of the
+ * response, one count to (first k tokens) -> (last token), under prompt_id.
+ * tlt_ngram_propose: context = the last context_len tokens of the sequence, ending with the root
+ * token (the one emitted last).  A continuation list is that of the longest seen suffix (at most
+ * n-1 tokens) of a context, ranked by count, equal counts by lower token id, with confidence
+ * log(count / total).  Node 0 = root; level 1 = the topk best continuations of the context; for
+ * each further level up to `depth` every frontier node proposes its topk best continuations and
+ * the topk best new candidates by path score (ties: created earlier) form the next frontier; the
+ * n_nodes-1 best candidates by path score are kept in creation order.  If fewer exist, the tree is
+ * padded with children of the root carrying the smallest token ids it has no child for yet
+ * (score -infinity): exactly n_nodes nodes are always written.  token/parent hold n_nodes int32,
+ * score (may be NULL) n_nodes floats.  Errors: TLT_EINVAL. */
+typedef struct tlt_ngram tlt_ngram;
+int tlt_ngram_create(int order, tlt_ngram **out);
+void tlt_ngram_destroy(tlt_ngram *db);
+int tlt_ngram_insert(tlt_ngram *db, int64_t prompt_id, const int32_t *tokens, int len);
+int tlt_ngram_propose(const tlt_ngram *db, int64_t prompt_id, const int32_t *context, int context_len, int depth,
+                      int topk, int n_nodes, int32_t *token, int32_t *parent, float *score);
+
 #ifdef __cplusplus
 }
 #endif

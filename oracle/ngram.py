@@ -54,7 +54,7 @@ class NGramDB:
         context = [int(x) for x in context]
         pool = []                                    # (token, score, parent pool index or -1, path tokens)
         frontier = []
-        for tok, lp in self.continuations(prompt_id, context)[:K]:
+        for tok, lp in (self.continuations(prompt_id, context)[:K] if depth >= 1 else []):   # depth 0: no drafts
             pool.append((tok, lp, -1, [tok]))
             frontier.append(len(pool) - 1)
         for _ in range(1, depth):

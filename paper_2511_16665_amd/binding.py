@@ -11,6 +11,7 @@ import dataclasses
 import os
 from typing import Optional
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -23,7 +24,7 @@ EXPORTS = [
     "tlt_strerror", "tlt_last_hip_error", "tlt_workspace_bytes", "tlt_create", "tlt_destroy", "tlt_draft_expand",
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
-    "tlt_mab_median_reward",
+    "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
 ]
 
 
@@ -100,6 +101,12 @@ def load() -> C.CDLL:
     lib.tlt_mab_record.argtypes = [C.c_void_p, C.c_int, C.c_double, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     lib.tlt_mab_median_reward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.tlt_ngram_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
+    lib.tlt_ngram_destroy.argtypes = [C.c_void_p]
+    lib.tlt_ngram_destroy.restype = None
+    lib.tlt_ngram_insert.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int]
+    lib.tlt_ngram_propose.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float)]
     _lib = lib
     return lib
 
@@ -299,6 +306,45 @@ class Mab:
     def close(self):
         if self.h:
             load().tlt_mab_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class NGram:
+    """tlt_ngram_*: the model-free drafter (host only)."""
+
+    def __init__(self, order):
+        self.h = C.c_void_p()
+        rc = load().tlt_ngram_create(int(order), C.byref(self.h))
+        if rc:
+            raise TltError(rc, "tlt_ngram_create")
+
+    def insert(self, prompt_id, tokens):
+        arr = np.ascontiguousarray(tokens, dtype=np.int32)
+        rc = load().tlt_ngram_insert(self.h, int(prompt_id), arr.ctypes.data_as(C.POINTER(C.c_int32)), len(arr))
+        if rc:
+            raise TltError(rc, "tlt_ngram_insert")
+
+    def propose(self, prompt_id, context, depth, topk, n_nodes):
+        """(token [n], parent [n], score [n]) numpy arrays of the proposed tree."""
+        ctx = np.ascontiguousarray(context, dtype=np.int32)
+        token, parent = np.empty(n_nodes, np.int32), np.empty(n_nodes, np.int32)
+        score = np.empty(n_nodes, np.float32)
+        rc = load().tlt_ngram_propose(self.h, int(prompt_id), ctx.ctypes.data_as(C.POINTER(C.c_int32)), len(ctx), int(depth),
+                                      int(topk), int(n_nodes), token.ctypes.data_as(C.POINTER(C.c_int32)),
+                                      parent.ctypes.data_as(C.POINTER(C.c_int32)), score.ctypes.data_as(C.POINTER(C.c_float)))
+        if rc:
+            raise TltError(rc, "tlt_ngram_propose")
+        return token, parent, score
+
+    def close(self):
+        if self.h:
+            load().tlt_ngram_destroy(self.h)
             self.h = C.c_void_p()
 
     def __del__(self):

@@ -123,6 +123,28 @@ class Engine:
         self.pending_max_new = inc
         return al, out
 
+    # -- a step whose trees come from somewhere else (the model-free drafter, tlt_ngram_propose)
+    def step_trees(self, token: np.ndarray, parent: np.ndarray):
+        """token/parent [B, n] int32 host arrays (node 0 = root = last emitted token, parents before
+        children).  Verifies, accepts greedily and commits; returns (accept_len [B], out_tokens [B, stride]).
+        The learned drafter's cache is not advanced: switching back to it needs a catch-up extend."""
+        B, n = token.shape
+        assert B == self.B and n <= self.max_n
+        t = self.tree(n)
+        t.token.copy_(torch.from_numpy(np.ascontiguousarray(token, dtype=np.int32)).cuda())
+        t.parent.copy_(torch.from_numpy(np.ascontiguousarray(parent, dtype=np.int32)).cuda())
+        self.ctx.tree_finalize(B, t)
+        am = self._buf("am", n)
+        self.ctx.verify_forward(B, t, self.kv, out_logits=None, out_argmax=am, out_hidden=None)
+        self.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, self.stride, self.accept_len, self.path_idx,
+                        self.out_tokens, self.n_out)
+        self.ctx.kv_commit(B, self.kv, self.accept_len, self.path_idx, self.stride)
+        al = self.accept_len.cpu().numpy()
+        out = self.out_tokens.cpu().numpy()
+        self.kv.seq_len_bound += int(al.max()) + 1
+        self.have_pending = False
+        return al, out
+
     # -- the same step replayed from captured HIP graphs
     def graph_pool(self, capacity_bound=None) -> "GraphPool":
         """Graph pool over this engine's buffers (see GraphPool)."""

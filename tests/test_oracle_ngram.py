@@ -46,6 +46,7 @@ def test_equal_counts_rank_by_token_id_and_padding_fills_root_children():
     tok, par, sc = db.propose(1, [5], depth=1, K=2, N=6)
     assert tok == [5, 3, 7, 0, 1, 2] and par == [-1, 0, 0, 0, 0, 0]
     assert sc[3:] == [-math.inf] * 3
+    assert db.propose(1, [5], depth=0, K=2, N=3)[0] == [5, 0, 1]      # depth 0 proposes nothing: padding only
     tok, par, _ = db.propose(1, [4], depth=2, K=2, N=4)               # nothing known: root + padding only
     assert tok == [4, 0, 1, 2] and par == [-1, 0, 0, 0]
 
