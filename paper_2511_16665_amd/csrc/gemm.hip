@@ -90,9 +90,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 1 KB DMA instructions per wave per tile: A part, W part
     constexpr int NR = WTM + WTN;                     // fragment reads per slice
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split evenly over the waves");
-    static_assert(LA == 2 * WTM && LB == 2 * WTM && NR % WTM == 0, "schedule: one load per MFMA row, two slices per operand");
+    static_assert(LA % 2 == 0 && LB % 2 == 0 && WTM >= 2, "schedule: each operand's loads are split over two slices");
     static_assert(SA >= 2 && SB >= 2, "at least double buffering");
-    constexpr int RPR = NR / WTM;
+    constexpr int RQ = (NR + WTM / 2 - 1) / (WTM / 2);   // fragment reads issued by each of the first WTM/2 MFMA rows
     // loads that may still be in flight when tile t+1 must be complete (issue order per step: W, then A)
     constexpr int kInFlightA = (SA - 2) * (LA + LB), kInFlightB = (SB - 1) * LA + (SB - 2) * LB;
     constexpr int kInFlight = kInFlightA < kInFlightB ? kInFlightA : kInFlightB;
@@ -189,15 +189,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     }
 #define TLT_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     // one slice: the MFMA rows on fragment set `buf`; the reads of the next slice into the other set
-    // in its first rows; one load (LOADX) after each row
-#define TLT_SLICE(buf, pa, pb, rkk, LOADX)                                                                        \
+    // in its first rows; the H loads base .. base+H-1 of operand OP (0 = A, 1 = W) spread evenly
+    // over the rows, each issued after its row's MFMAs
+#define TLT_SLICE(buf, pa, pb, rkk, OP, slot, k0, base, H)                                                        \
     _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                              \
         if (i < WTM / 2) {                                                                                        \
-            _Pragma("unroll") for (int q = 0; q < 2 * RPR; ++q) TLT_READ1((buf) ^ 1, pa, pb, rkk, i * 2 * RPR + q) \
+            _Pragma("unroll") for (int q = i * RQ; q < (i + 1) * RQ && q < NR; ++q) TLT_READ1((buf) ^ 1, pa, pb, rkk, q) \
         }                                                                                                         \
         _Pragma("unroll") for (int j = 0; j < WTN; ++j) TLT_MFMA(buf, i, j)                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        LOADX                                                                                                     \
+        _Pragma("unroll") for (int d = (i * (H)) / WTM; d < ((i + 1) * (H)) / WTM; ++d) {                          \
+            if ((OP) == 0) TLT_DMA_A(slot, k0, (base) + d) else TLT_DMA_B(slot, k0, (base) + d)                    \
+        }                                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
     }
 
@@ -216,14 +219,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         // the first slice's fragments were requested a whole slice ago; waiting here, before the next
         // reads are issued, keeps the compiler from waiting for those as well
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        TLT_SLICE(0, pa, pb, 1, TLT_DMA_B(pb_, kBprev, LB / 2 + i))       // W tile t-1+SB, second half
-        TLT_SLICE(1, pa, pb, 2, TLT_DMA_A(pa_, kAprev, i))                // A tile t-1+SA, first half
-        TLT_SLICE(0, pa, pb, 3, TLT_DMA_A(pa_, kAprev, LA / 2 + i))       //               second half
+        TLT_SLICE(0, pa, pb, 1, 1, pb_, kBprev, LB / 2, LB / 2)           // W tile t-1+SB, second half
+        TLT_SLICE(1, pa, pb, 2, 0, pa_, kAprev, 0, LA / 2)                // A tile t-1+SA, first half
+        TLT_SLICE(0, pa, pb, 3, 0, pa_, kAprev, LA / 2, LA / 2)           //               second half
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInFlight));        // tile t+1 has landed
         __builtin_amdgcn_s_barrier();                            // ... for every wave; tile t's slots are free
         __builtin_amdgcn_sched_barrier(0);
-        TLT_SLICE(1, lds + na * ASZ, lds + SA * ASZ + nb * BSZ, 0, TLT_DMA_B(sb, kBnext, i))   // W tile t+SB, first half
+        TLT_SLICE(1, lds + na * ASZ, lds + SA * ASZ + nb * BSZ, 0, 1, sb, kBnext, 0, LB / 2)   // W tile t+SB, first half
         pa_ = sa; pb_ = sb; sa = na; sb = nb;
     }
 #undef TLT_READ1
@@ -382,9 +385,10 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     const int tiles256 = nbm256 * nbn256;
     // (with M <= 64 three quarters of a 256-row tile would be padding: the 128x128 tiles stream the
     // weights faster)
-    if (M <= 64 || tiles256 < 100) return small(N, 0);
-    // a hundred or more big tiles stream cold weights faster than twice as many TA-bound small ones
-    if (tiles256 < 256) return N % bno256 == 0 ? big(N) : small(N, 0);
+    // one row of big tiles, a hundred or more of them, streams cold weights faster than twice as
+    // many TA-bound small ones
+    if (nbm256 == 1 && M > 64 && tiles256 >= 100 && tiles256 < 256 && N % bno256 == 0) return big(N);
+    if (M <= 64 || tiles256 < 256) return small(N, 0);
     const int full_rounds = tiles256 / 256;
     const int main_nbn = full_rounds * 256 / nbm256;          // column tiles that make up the whole rounds
     const int rest_cols = N - main_nbn * bno256;
