@@ -5,14 +5,19 @@
 // bf16 path (gfx950): v_mfma_f32_32x32x16_bf16, fp32 accumulation.  A workgroup of 4 waves (2x2)
 // owns a (64*WTM) x (64*WTN) tile; each wave owns WTM x WTN MFMA tiles of 32x32.  K is walked in
 // steps of 64 through rings of LDS slots (SA for the activation rows, SB for the weight rows) filled
-// by direct global->LDS loads (no staging registers, no ds_write).  Workgroup ids are remapped so
-// that each XCD (ids are dealt round-robin over the 8 XCDs) walks a contiguous range of tiles, M
-// fastest: neighbours on one XCD share the same weight tile in that XCD's L2.
+// by direct global->LDS loads (no staging registers, no ds_write).  Workgroups are persistent: as
+// many as the chip holds at once, each walking several tiles with the load pipeline running across
+// tile boundaries; ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) walks
+// a contiguous range of tiles, M fastest: neighbours on one XCD share the same weight tile in that
+// XCD's L2.
 // Measured on MI355X, and what shapes the kernel: a register-only MFMA loop with one wave per SIMD
 // reaches ~2.0 PFLOP/s; the chip clocks down to ~1.6-1.8 GHz under sustained MFMA load; a CU's
 // vector-memory front end moves ~50 B/clk of global->LDS traffic when rows are fetched as whole
 // 128-byte lines (~110 GB/s per CU, half that for 64-byte pieces), so the 64 KB a 256x256 tile
-// needs per K step occupy it for ~1300 of the step's 2048 MFMA clocks.
+// needs per K step occupy it for ~1300 of the step's 2048 MFMA clocks.  With the output stores
+// switched off the 256x256 kernel runs at 1.34-1.42 PFLOP/s on the M = 1536 shapes; the stores of a
+// tile are not overlapped with compute (all workgroups finish their tiles together and the burst
+// runs at the HBM write rate, ~5-6 TB/s whatever the store shape), which costs 8-15 %.
 //
 // Generic path (fp32 mode, odd shapes): 64x64 LDS-tiled FMA kernel with full bounds checks.
 #include "dev_common.h"
@@ -65,7 +70,7 @@ constexpr uint32_t vmcnt_imm(int n) { return 0x0F70u | (uint32_t)(n & 15) | ((ui
 // The LDS has 64 banks (256 B per clock): a 16-byte fragment read is served 16 lanes at a time, and
 // with this swizzle 16 consecutive rows hit 16 distinct 16-byte columns (SQ_LDS_BANK_CONFLICT = 0;
 // swizzling with r & 7 instead costs a two-way conflict on every read).
-__device__ __forceinline__ void dma_buf_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff_bytes, uint32_t soff_bytes,
+__device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, uint32_t soff_bytes,
                                            uint32_t lds_bytes) {
     asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
                  :
@@ -82,7 +87,7 @@ template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU 
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
-                                                        int ksplit) {
+                                                        int ksplit, int wg_per_xcd) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -96,20 +101,66 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     // loads that may still be in flight when tile t+1 must be complete (issue order per step: W, then A)
     constexpr int kInFlightA = (SA - 2) * (LA + LB), kInFlightB = (SB - 1) * LA + (SB - 2) * LB;
     constexpr int kInFlight = kInFlightA < kInFlightB ? kInFlightA : kInFlightB;
-    extern __shared__ __align__(16) uint16_t lds[];   // SA A slots, then SB W slots
-
-    const int pid = blockIdx.x;
-    const int logical = (pid & 7) * per_xcd + (pid >> 3);
-    if (logical >= total_tiles) return;
-    // M fastest, then the K split, then N: the workgroups that share a weight tile stay neighbours
-    const int tile_m = logical % nbm, split = (logical / nbm) % ksplit, tile_n = logical / (nbm * ksplit);
     constexpr int BNO = GLU ? BN / 2 : BN;            // output columns per workgroup
     static_assert(!GLU || (NW % 2 == 0 && WTN % 2 == 0), "gate and up halves split over waves and over a wave's column tiles");
-    const int m0 = tile_m * BM, n0 = tile_n * BNO;
+    extern __shared__ __align__(16) uint16_t lds[];   // SA A slots, then SB W slots
+
+    // Persistent workgroups: XCD x (ids are dealt round-robin over the XCDs) owns the logical tiles
+    // x*per_xcd .. (x+1)*per_xcd-1 and its wg_per_xcd workgroups walk them with that stride, so at any
+    // time an XCD works on a contiguous run of tiles (M fastest: neighbours share a weight tile in L2).
+    // The K steps of all of a workgroup's tiles form one sequence that the slot rings run through
+    // without draining: while the last steps of a tile compute, the first K tiles of the next one load.
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, wslot = pid >> 3;
+    const int first = xcd * per_xcd + wslot;
+    int range_end = total_tiles - xcd * per_xcd;
+    range_end = range_end < per_xcd ? range_end : per_xcd;
+    if (wslot >= range_end) return;
+    const int n_my = (range_end - wslot + wg_per_xcd - 1) / wg_per_xcd;
+
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, lhi = lane >> 5;
+    const int nk_all = K / BKS;
+    const bool up_wave = GLU && wave >= NW / 2;
+
+    // tile j of this workgroup: M fastest, then the K split, then N
+    struct TileInfo { int m0, n0, kt0, nt; };
+    auto tile_info = [&](int j) {
+        const int logical = first + j * wg_per_xcd;
+        const int tile_m = logical % nbm, split = (logical / nbm) % ksplit, tile_n = logical / (nbm * ksplit);
+        TileInfo ti;
+        // (integer division runs on the vector ALU: pin the uniform results back into scalar registers)
+        ti.m0 = __builtin_amdgcn_readfirstlane(tile_m * BM);
+        ti.n0 = __builtin_amdgcn_readfirstlane(tile_n * BNO);
+        ti.kt0 = __builtin_amdgcn_readfirstlane(nk_all * split / ksplit);   // (nk_all * ksplit < 2^31 by the shape check)
+        ti.nt = __builtin_amdgcn_readfirstlane(nk_all * (split + 1) / ksplit) - ti.kt0;
+        return ti;
+    };
+    // raw buffer descriptors (four scalar words: base, base high bits, size in bytes, format) over a
+    // tile's two row panels.  The activation panel's size is its valid rows: lanes that would fetch rows
+    // past M are out of range and fetch nothing (their accumulator rows are never stored).  Every
+    // in-range offset is below 2^31 by the launcher's shape check.
+    auto desc = [&](const uint16_t* base, uint32_t bytes) {
+        const uint64_t p = (uint64_t)(uintptr_t)base;
+        u32x4_t d;
+        d[0] = __builtin_amdgcn_readfirstlane((uint32_t)p);
+        d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32) & 0xffffu);
+        d[2] = bytes;
+        d[3] = 0x00020000u;
+        return d;
+    };
+    auto desc_a = [&](const TileInfo& ti) {
+        int rows = M - ti.m0;
+        rows = rows < BM ? rows : BM;
+        return desc(A + (int64_t)ti.m0 * K, (uint32_t)(rows * K * 2));
+    };
+    // (GLU: the first half of the waves fetch the gate rows, the second half the up rows; a wave's
+    // LB blocks are BN / NW consecutive tile rows, so they never straddle the two halves)
+    auto desc_b = [&](const TileInfo& ti) {
+        return desc(up_wave ? W2 + ((int64_t)ti.n0 - BN / 2) * K : W + (int64_t)ti.n0 * K, 0x7fffffffu);
+    };
 
     // DMA addressing: wave w fills 1 KB blocks w*LA .. of an A slot (8 tile rows each) and w*LB .. of
     // a W slot; lane -> (row r of the block, stored chunk c) fetches the logical chunk that the
@@ -119,29 +170,66 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int trow = (wave * LA + i) * 8 + r;
-        int row = m0 + trow;
-        row = row < M ? row : M - 1;
-        offA[i] = ((uint32_t)(row - m0) * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
+        offA[i] = ((uint32_t)trow * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int trow = (wave * LB + i) * 8 + r;
         offB[i] = ((uint32_t)trow * (uint32_t)K + (c ^ ((trow >> 1) & 7)) * 8) * 2u;
     }
-    // raw buffer descriptors over the two row panels (range checking effectively off: every offset
-    // is below 2^31 by the launcher's shape check)
-    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)m0 * K), 0, 0x7fffffff, 0x00020000);
-    // (GLU: the first half of the waves fetch the gate rows, the second half the up rows; a wave's
-    // LB blocks are BN / NW consecutive tile rows, so they never straddle the two halves)
-    const bool up_wave = GLU && wave >= NW / 2;
-    const uint16_t* wsrc = up_wave ? W2 + ((int64_t)n0 - BN / 2) * K : W + (int64_t)n0 * K;
-    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)wsrc, 0, 0x7fffffff, 0x00020000);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
     const uint32_t lds_waveA = lds_base + (uint32_t)(wave * LA) * 1024u;
     const uint32_t lds_waveB = lds_base + (uint32_t)(SA * ASZ * 2) + (uint32_t)(wave * LB) * 1024u;
 
-#define TLT_DMA_A(slot, k0, d) dma_buf_16(rsA, offA[d], (uint32_t)(k0) * 2u, lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
-#define TLT_DMA_B(slot, k0, d) dma_buf_16(rsB, offB[d], (uint32_t)(k0) * 2u, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
+    // load cursors: the next K tile each operand fetches, in the order the compute side consumes them
+    // (descriptor, absolute K tile index, end of the tile's K range).  When a cursor reaches the end of
+    // its tile it jumps to the `next` triple, which the compute loop points at its following tile, or,
+    // after the last one, back at the last K tile (harmless re-fetches keep the schedule uniform).  All
+    // of it is scalar selects: the K loop stays one basic block.  A cursor runs at most SA-1 K tiles
+    // ahead, so with at least SA K tiles per tile (the launcher's condition for giving a workgroup more
+    // than one) it never needs more than the one following tile.
+    const TileInfo ti0 = tile_info(0);
+    u32x4_t rsA = desc_a(ti0), rsB = desc_b(ti0), rsA_nx = rsA, rsB_nx = rsB;
+    int a_kt = ti0.kt0, a_end = ti0.kt0 + ti0.nt, b_kt = a_kt, b_end = a_end;
+    int nx_kt0 = a_end - 1, nx_end = a_end;
+    uint32_t kA2 = (uint32_t)a_kt * (BKS * 2), kB2 = kA2;   // byte offset of the cursor's K tile in a row
+    auto advance_a = [&]() {
+        ++a_kt;
+        const bool wrap = a_kt == a_end;
+#pragma unroll
+        for (int w = 0; w < 3; ++w) rsA[w] = wrap ? rsA_nx[w] : rsA[w];
+        a_kt = wrap ? nx_kt0 : a_kt;
+        a_end = wrap ? nx_end : a_end;
+        kA2 = (uint32_t)a_kt * (BKS * 2);
+    };
+    auto advance_b = [&]() {
+        ++b_kt;
+        const bool wrap = b_kt == b_end;
+#pragma unroll
+        for (int w = 0; w < 3; ++w) rsB[w] = wrap ? rsB_nx[w] : rsB[w];
+        b_kt = wrap ? nx_kt0 : b_kt;
+        b_end = wrap ? nx_end : b_end;
+        kB2 = (uint32_t)b_kt * (BKS * 2);
+    };
+    // point `next` at tile j+1 (call while both cursors are inside tile j)
+    auto set_next = [&](int j, const TileInfo& tj) {
+        if (j + 1 < n_my) {
+            const TileInfo tn = tile_info(j + 1);
+            rsA_nx = desc_a(tn);
+            rsB_nx = desc_b(tn);
+            nx_kt0 = tn.kt0;
+            nx_end = tn.kt0 + tn.nt;
+        } else {
+            rsA_nx = desc_a(tj);
+            rsB_nx = desc_b(tj);
+            nx_kt0 = tj.kt0 + tj.nt - 1;
+            nx_end = tj.kt0 + tj.nt;
+        }
+    };
+    set_next(0, ti0);
+
+#define TLT_DMA_A(slot, d) dma_buf_16(rsA, offA[d], kA2, lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
+#define TLT_DMA_B(slot, d) dma_buf_16(rsB, offB[d], kB2, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
 
     f32x16_t acc[WTM][WTN];
 #pragma unroll
@@ -151,25 +239,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // this workgroup's share of the K tiles (all of them unless the launch splits K)
-    const int nk_all = K / BKS;
-    const int kt0 = (int)((int64_t)nk_all * split / ksplit), nt = (int)((int64_t)nk_all * (split + 1) / ksplit) - kt0;
-    auto ktile = [&](int t) { return (kt0 + (t < nt ? t : nt - 1)) * BKS; };   // past the end: harmless re-fetch of the last tile
-    // prologue: tile 0 first, then A tiles 1 .. SA-2, W tiles 1 .. SB-2 and the first half of W tile SB-1
+    // prologue: K tile 0 first, then A tiles 1 .. SA-2, W tiles 1 .. SB-2 and the first half of W tile SB-1
 #pragma unroll
-    for (int d = 0; d < LA; ++d) TLT_DMA_A(0, ktile(0), d)
+    for (int d = 0; d < LA; ++d) TLT_DMA_A(0, d)
+    advance_a();
 #pragma unroll
-    for (int d = 0; d < LB; ++d) TLT_DMA_B(0, ktile(0), d)
+    for (int d = 0; d < LB; ++d) TLT_DMA_B(0, d)
+    advance_b();
 #pragma unroll
-    for (int st = 1; st < SA - 1; ++st)
+    for (int st = 1; st < SA - 1; ++st) {
 #pragma unroll
-        for (int d = 0; d < LA; ++d) TLT_DMA_A(st, ktile(st), d)
+        for (int d = 0; d < LA; ++d) TLT_DMA_A(st, d)
+        advance_a();
+    }
 #pragma unroll
-    for (int st = 1; st < SB - 1; ++st)
+    for (int st = 1; st < SB - 1; ++st) {
 #pragma unroll
-        for (int d = 0; d < LB; ++d) TLT_DMA_B(st, ktile(st), d)
+        for (int d = 0; d < LB; ++d) TLT_DMA_B(st, d)
+        advance_b();
+    }
 #pragma unroll
-    for (int d = 0; d < LB / 2; ++d) TLT_DMA_B(SB - 1, ktile(SB - 1), d)
+    for (int d = 0; d < LB / 2; ++d) TLT_DMA_B(SB - 1, d)
 
     const int fragA = (wm * (WTM * 32) + l32) * BKS;
     // tile row of column tile j of this wave (GLU: j < WTN/2 are gate rows, the rest the matching up rows)
@@ -191,7 +281,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     // one slice: the MFMA rows on fragment set `buf`; the reads of the next slice into the other set
     // in its first rows; the H loads base .. base+H-1 of operand OP (0 = A, 1 = W) spread evenly
     // over the rows, each issued after its row's MFMAs
-#define TLT_SLICE(buf, pa, pb, rkk, OP, slot, k0, base, H)                                                        \
+#define TLT_SLICE(buf, pa, pb, rkk, OP, slot, base, H)                                                            \
     _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                              \
         if (i < WTM / 2) {                                                                                        \
             _Pragma("unroll") for (int q = i * RQ; q < (i + 1) * RQ && q < NR; ++q) TLT_READ1((buf) ^ 1, pa, pb, rkk, q) \
@@ -199,35 +289,70 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         _Pragma("unroll") for (int j = 0; j < WTN; ++j) TLT_MFMA(buf, i, j)                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
         _Pragma("unroll") for (int d = (i * (H)) / WTM; d < ((i + 1) * (H)) / WTM; ++d) {                          \
-            if ((OP) == 0) TLT_DMA_A(slot, k0, (base) + d) else TLT_DMA_B(slot, k0, (base) + d)                    \
+            if ((OP) == 0) TLT_DMA_A(slot, (base) + d) else TLT_DMA_B(slot, (base) + d)                            \
         }                                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
     }
 
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((SA - 2) * LA + (SB - 2) * LB + LB / 2));   // tile 0 has landed
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((SA - 2) * LA + (SB - 2) * LB + LB / 2));   // K tile 0 has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int q = 0; q < NR; ++q) TLT_READ1(0, lds, lds + SA * ASZ, 0, q)
 
-    // slot of tile t in each ring; pa_/pb_ = slot of tile t-1 (the one being refilled during step t)
+    // slot of the current K tile in each ring; pa_/pb_ = slot of the one before (refilled during this step)
     int sa = 0, sb = 0, pa_ = SA - 1, pb_ = SB - 1;
-    for (int t = 0; t < nt; ++t) {
-        const uint16_t* pa = lds + sa * ASZ;
-        const uint16_t* pb = lds + SA * ASZ + sb * BSZ;
-        const int na = sa + 1 == SA ? 0 : sa + 1, nb = sb + 1 == SB ? 0 : sb + 1;
-        const int kBprev = ktile(t - 1 + SB), kAprev = ktile(t - 1 + SA), kBnext = ktile(t + SB);
-        // the first slice's fragments were requested a whole slice ago; waiting here, before the next
-        // reads are issued, keeps the compiler from waiting for those as well
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        TLT_SLICE(0, pa, pb, 1, 1, pb_, kBprev, LB / 2, LB / 2)           // W tile t-1+SB, second half
-        TLT_SLICE(1, pa, pb, 2, 0, pa_, kAprev, 0, LA / 2)                // A tile t-1+SA, first half
-        TLT_SLICE(0, pa, pb, 3, 0, pa_, kAprev, LA / 2, LA / 2)           //               second half
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInFlight));        // tile t+1 has landed
-        __builtin_amdgcn_s_barrier();                            // ... for every wave; tile t's slots are free
-        __builtin_amdgcn_sched_barrier(0);
-        TLT_SLICE(1, lds + na * ASZ, lds + SA * ASZ + nb * BSZ, 0, 1, sb, kBnext, 0, LB / 2)   // W tile t+SB, first half
-        pa_ = sa; pb_ = sb; sa = na; sb = nb;
+    for (int j = 0; j < n_my; ++j) {
+        const TileInfo ti = tile_info(j);
+        if (j > 0) set_next(j, ti);
+        for (int t = 0; t < ti.nt; ++t) {
+            const uint16_t* pa = lds + sa * ASZ;
+            const uint16_t* pb = lds + SA * ASZ + sb * BSZ;
+            const int na = sa + 1 == SA ? 0 : sa + 1, nb = sb + 1 == SB ? 0 : sb + 1;
+            // the first slice's fragments were requested a whole slice ago; waiting here, before the next
+            // reads are issued, keeps the compiler from waiting for those as well
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            TLT_SLICE(0, pa, pb, 1, 1, pb_, LB / 2, LB / 2)           // W cursor, second half
+            advance_b();
+            TLT_SLICE(1, pa, pb, 2, 0, pa_, 0, LA / 2)                // A cursor, first half
+            TLT_SLICE(0, pa, pb, 3, 0, pa_, LA / 2, LA / 2)           //           second half
+            advance_a();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInFlight));        // the next K tile has landed
+            __builtin_amdgcn_s_barrier();                            // ... for every wave; this one's slots are free
+            __builtin_amdgcn_sched_barrier(0);
+            TLT_SLICE(1, lds + na * ASZ, lds + SA * ASZ + nb * BSZ, 0, 1, sb, 0, LB / 2)   // W cursor, first half
+            pa_ = sa; pb_ = sb; sa = na; sb = nb;
+        }
+        // the tile is complete: store it and clear the accumulators while the next tile's loads land
+#pragma unroll
+        for (int i = 0; i < WTM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = ti.m0 + wm * (WTM * 32) + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                if (row < M) {
+                    if (GLU) {
+#pragma unroll
+                        for (int jj = 0; jj < WTN / 2; ++jj) {
+                            int col = ti.n0 + wn * (WTN / 2 * 32) + jj * 32 + l32;
+                            const float g = acc[i][jj][v], u = acc[i][jj + WTN / 2][v];
+                            store_out<OUT>(C, (int64_t)row * N + col, g / (1.0f + __expf(-g)) * u);
+                        }
+                    } else {
+#pragma unroll
+                        for (int jj = 0; jj < WTN; ++jj) {
+                            int col = ti.n0 + wn * (WTN * 32) + jj * 32 + l32;
+                            store_out<OUT>(C, (int64_t)row * N + col, acc[i][jj][v]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < WTM; ++i)
+#pragma unroll
+            for (int jj = 0; jj < WTN; ++jj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
     }
 #undef TLT_READ1
 #undef TLT_MFMA
@@ -235,29 +360,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #undef TLT_DMA_A
 #undef TLT_DMA_B
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the redundant tail fetches before the LDS is released
-#pragma unroll
-    for (int i = 0; i < WTM; ++i) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int row = m0 + wm * (WTM * 32) + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-            if (row < M) {
-                if (GLU) {
-#pragma unroll
-                    for (int j = 0; j < WTN / 2; ++j) {
-                        int col = n0 + wn * (WTN / 2 * 32) + j * 32 + l32;
-                        const float g = acc[i][j][v], u = acc[i][j + WTN / 2][v];
-                        store_out<OUT>(C, (int64_t)row * N + col, g / (1.0f + __expf(-g)) * u);
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < WTN; ++j) {
-                        int col = n0 + wn * (WTN * 32) + j * 32 + l32;
-                        store_out<OUT>(C, (int64_t)row * N + col, acc[i][j][v]);
-                    }
-                }
-            }
-        }
-    }
 }
 
 template <typename T, int OUT>
@@ -323,7 +425,12 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
     const int total = nbm * nbn * ksplit;
     const int per_xcd = (total + 7) / 8;
     const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
-    dim3 grid(per_xcd * 8), block(64 * WGM * WGN);
+    // persistent workgroups: as many as the chip holds at once (32 CUs per XCD, LDS-limited occupancy)
+    const int occupancy = lds <= 80 * 1024 ? 2 : 1;
+    // (a workgroup that walks several tiles needs at least SA K tiles in each)
+    const bool persistent = (K / 64) / ksplit >= SA;
+    const int wg_per_xcd = (!persistent || per_xcd < 32 * occupancy) ? per_xcd : 32 * occupancy;
+    dim3 grid(wg_per_xcd * 8), block(64 * WGM * WGN);
 #define LAUNCH(OUT)                                                                                                   \
     {                                                                                                                 \
         auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU>;                                          \
@@ -334,7 +441,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             attr_set = true;                                                                                          \
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
-                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit);                                           \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd);                                           \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
