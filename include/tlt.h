@@ -124,11 +124,41 @@ int tlt_destroy(tlt_ctx *ctx);
  * sequence b (new_tokens[b][n_new[b]-1]: the bonus token of the previous step).  Ties prefer the candidate created first / the lower token.
  * out_tree->n must equal min(n_verify, 1 + topk + (depth-1)*topk^2).
  * Provisional drafter entries use rows seq_len .. seq_len + (depth-1)*topk - 1 of draft_kv.
- * All pointers DEVICE except the structs themselves.  mode must be 0 (deterministic top-k). */
+ * All pointers DEVICE except the structs themselves.  mode must be 0 (deterministic top-k); sampled
+ * drafting has its own entry point, tlt_draft_sample. */
 int tlt_draft_expand(tlt_ctx *ctx, void *stream, int B, int depth, int topk, int n_verify, int mode,
                      const int32_t *new_tokens, const int32_t *new_src, const int32_t *n_new, int new_stride,
                      const float *hidden, int hidden_n, const int32_t *root_tokens, tlt_kv *draft_kv,
                      tlt_tree *out_tree);
+
+/* Static tree template of sampled drafting, HOST arrays of n_verify entries each (no GPU work).
+ * The paper samples its rollouts (temperature 0.9, Section 6.1) and requires the output
+ * distribution to stay the target's (Section 1, Section 3 principle (a)); that only holds when the
+ * shape of the tree does not depend on the drawn tokens, so the shape is fixed by the three
+ * parameters of Section 5.1: of the full topk-ary tree of `depth` levels keep the n_verify-1 nodes of
+ * highest prior weight prod_j 0.6 * 0.4^(r_j) (r_j = child ranks on the way down), plus the root.
+ * Equal weights: the shallower node, then the smaller rank sequence.  Nodes are numbered by depth,
+ * then parent number, then rank, so parents precede children and siblings are consecutive.
+ * Outputs: parent (-1 for the root), rank among its siblings (-1 for the root), node_depth, and
+ * *n_nodes = min(n_verify, size of the full tree + 1).  TLT_EINVAL on bad arguments. */
+int tlt_template_build(int topk, int depth, int n_verify, int32_t *parent, int32_t *rank, int32_t *node_depth,
+                       int32_t *n_nodes);
+
+/* Sampled drafting on that template (the drafting half of the sampling mode; same drafter and same
+ * extend step as tlt_draft_expand, whose argument meanings carry over).  For every node i that has
+ * children, out_draft_q[b][i][:] = softmax(drafter logits at node i / temperature) in fp32, and
+ * its children's tokens are drawn from it one after the other without replacement: with weights
+ * floor(q_j * 2^32), the child with uniform U = u_draw[b][child] is the first token whose running
+ * weight sum exceeds (U * total) >> 32, and its weight is then zeroed.  This is the process
+ * tlt_accept's mode 1 presupposes (pass out_draft_q as its draft_q).  Rows of out_draft_q for nodes
+ * without children are not written.  out_tree->n must equal the template's node count; parent,
+ * depth and anc_mask are filled from the template, score with zeros.  depth >= 1.
+ * Provisional drafter entries use rows seq_len .. seq_len + (nodes with children, root excluded) - 1
+ * of draft_kv.  u_draw [B][n] uint32 and out_draft_q [B][n][V] fp32 are DEVICE pointers. */
+int tlt_draft_sample(tlt_ctx *ctx, void *stream, int B, int depth, int topk, int n_verify, float temperature,
+                     const int32_t *new_tokens, const int32_t *new_src, const int32_t *n_new, int new_stride,
+                     const float *hidden, int hidden_n, const int32_t *root_tokens, tlt_kv *draft_kv,
+                     const uint32_t *u_draw, tlt_tree *out_tree, float *out_draft_q);
 
 /* Fills depth and anc_mask of a caller-made tree from token/parent (parents must precede
  * children; parent[0] = -1). */

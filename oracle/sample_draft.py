@@ -125,10 +125,13 @@ def softmax_temperature(logits, temperature):
     return (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
 
 
-def draft_sample(cfg, tw, dw, st: sd.SeqState, root_token: int, K: int, D: int, N: int, temperature: float, u_draw):
+def draft_sample(cfg, tw, dw, st: sd.SeqState, root_token: int, K: int, D: int, N: int, temperature: float, u_draw,
+                 forced_tokens=None):
     """Sampled drafting of one sequence on the static template.  u_draw [n] uint32: entry i is the
     uniform that draws node i (entry 0 unused).  Returns (Tree, q [n, V] fp32) where row i of q is
     the distribution node i's children were drawn from (zero rows for nodes without children).
+    With forced_tokens [n] the nodes take those tokens instead of drawn ones (the distributions of
+    somebody else's tree: used to compare q where a draw may legitimately differ).
 
     A node at depth s with children becomes drafter entry ctx+s-1 exactly as in the deterministic
     expansion: input = its token's embedding joined with its parent's drafter output; it attends to
@@ -146,7 +149,10 @@ def draft_sample(cfg, tw, dw, st: sd.SeqState, root_token: int, K: int, D: int, 
     base_len = st.draft_len
 
     def draw(i):
-        if kids[i]:
+        if kids[i] and forced_tokens is not None:
+            for c in kids[i]:
+                token[c] = int(forced_tokens[c])
+        elif kids[i]:
             for c, t in zip(kids[i], draw_children(q[i], [u_draw[c] for c in kids[i]])):
                 token[c] = t
 

@@ -25,6 +25,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
+    "tlt_template_build", "tlt_draft_sample",
 ]
 
 
@@ -83,6 +84,9 @@ def load() -> C.CDLL:
     lib.tlt_draft_expand.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p, C.c_int,
                                                                                          C.c_void_p, C.POINTER(KVC),
                                                                                          C.POINTER(TreeC)]
+    lib.tlt_template_build.argtypes = [C.c_int] * 3 + [C.POINTER(C.c_int32)] * 4
+    lib.tlt_draft_sample.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 3 + \
+        [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(KVC), C.c_void_p, C.POINTER(TreeC), C.c_void_p]
     lib.tlt_tree_finalize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC)]
     lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 3
     lib.tlt_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 5 + \
@@ -234,6 +238,16 @@ class Context:
                                               _ptr(new_src), _ptr(n_new), new_stride, _ptr(hidden), hidden_n,
                                               _ptr(root_tokens), C.byref(kvc), tree_ref), "tlt_draft_expand")
 
+    def draft_sample(self, B, depth, topk, n_verify, temperature, new_tokens, new_src, n_new, hidden, root_tokens,
+                     draft_kv: KV, u_draw, out_tree: Tree, out_draft_q):
+        new_stride = 0 if new_tokens is None else new_tokens.shape[1]
+        hidden_n = 0 if hidden is None else hidden.shape[1]
+        kvc, tc = draft_kv.c(), out_tree.c()
+        self._check(self.lib.tlt_draft_sample(self.handle, _stream(), B, depth, topk, n_verify, temperature,
+                                              _ptr(new_tokens), _ptr(new_src), _ptr(n_new), new_stride, _ptr(hidden),
+                                              hidden_n, _ptr(root_tokens), C.byref(kvc), _ptr(u_draw), C.byref(tc),
+                                              _ptr(out_draft_q)), "tlt_draft_sample")
+
     def tree_finalize(self, B, tree: Tree):
         tc = tree.c()
         self._check(self.lib.tlt_tree_finalize(self.handle, _stream(), B, C.byref(tc)), "tlt_tree_finalize")
@@ -266,6 +280,18 @@ class Context:
         self._check(self.lib.tlt_profile_read(self.handle, ms, n, fl, by), "tlt_profile_read")
         names = ("gemm", "attention", "kv_commit", "other", "gemm_draft", "attention_draft")
         return {k: {"ms": ms[i], "launches": n[i], "flops": fl[i], "bytes": by[i]} for i, k in enumerate(names)}
+
+
+def template_build(topk: int, depth: int, n_verify: int):
+    """Static tree template of sampled drafting: (parent, rank, depth) int32 arrays (host side)."""
+    lib = load()
+    par, rank, dep = (np.zeros(n_verify, dtype=np.int32) for _ in range(3))
+    n = C.c_int32(0)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    rc = lib.tlt_template_build(topk, depth, n_verify, p(par), p(rank), p(dep), C.byref(n))
+    if rc:
+        raise TltError(rc, "tlt_template_build")
+    return par[: n.value].copy(), rank[: n.value].copy(), dep[: n.value].copy()
 
 
 class Mab:

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtlt.so")
-SOURCES = ["api.hip", "gemm.hip", "attn.hip", "elementwise.hip", "sample.hip", "mab.cpp", "ngram.cpp"]
+SOURCES = ["api.hip", "gemm.hip", "attn.hip", "elementwise.hip", "sample.hip", "mab.cpp", "ngram.cpp", "tmpl.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -40,7 +40,9 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     const size_t qkv_dim = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     p.max_rows = (int)R;
     p.pool_cap = K + std::max(0, D - 1) * K * K;
-    p.feat_rows = 1 + std::max(0, D - 1) * K;
+    // feature rows per sequence: the root's + one per drafter row of an expansion (deterministic:
+    // K per level after the first; sampled: one per template node with children, fewer than n)
+    p.feat_rows = std::max(1 + std::max(0, D - 1) * K, n);
     size_t o = 0;
     auto take = [&](size_t bytes) {
         size_t at = o;
@@ -64,10 +66,11 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.pool_parent = take((size_t)B * p.pool_cap * 4);
     p.pool_depth = take((size_t)B * p.pool_cap * 4);
     p.pool_mask = take((size_t)B * p.pool_cap * 16);
-    p.fr_token = take((size_t)B * K * 4);
-    p.fr_src = take((size_t)B * K * 4);
-    p.fr_pool = take((size_t)B * K * 4);
-    p.fr_mask = take((size_t)B * K * 16);
+    const size_t FRN = (size_t)B * std::max(n, K);   // rows of one drafter pass
+    p.fr_token = take(FRN * 4);
+    p.fr_src = take(FRN * 4);
+    p.fr_pool = take(FRN * 4);
+    p.fr_mask = take(FRN * 16);
     p.row_map = take((size_t)B * 4);
     p.attn_ws_bytes = attention_workspace_bytes(B, std::max(n, K), c.n_q_heads, c.n_kv_heads, c.head_dim, max_ctx);
     p.attn_ws = take(p.attn_ws_bytes);
@@ -349,6 +352,38 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
     return TLT_OK;
 }
 
+// Drafter catch-up shared by both expansion modes: entries for the newly committed positions, the
+// last one's output as feature row 0, committed length advanced.
+static int draft_extend_rows(tlt_ctx* ctx, hipStream_t s, int B, const int32_t* new_tokens, const int32_t* new_src,
+                             const int32_t* n_new, int new_stride, const float* hidden, int hidden_n, tlt_kv* draft_kv,
+                             KVLayer& kvl) {
+    const tlt_model_cfg& c = ctx->cfg;
+    const Plan& p = ctx->plan;
+    char* ws = ctx->ws;
+    const int h = c.hidden, V = c.vocab, dt = c.dtype;
+    const double e = (double)esz_of(ctx);
+    float* x = (float*)(ws + p.x);
+    float* feat = (float*)(ws + p.feat);
+    const int FR = p.feat_rows;
+    int rc;
+    const int M = B * new_stride;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
+            draft_input(s, dt, B, new_stride, h, V, new_tokens, new_src, n_new, hidden_n, (int64_t)B * hidden_n, hidden,
+                        ctx->target.embed, ws + p.xn));
+    if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+    Rows rows;
+    rows.B = B;
+    rows.n = new_stride;
+    rows.n_valid = n_new;
+    rows.pos_stride = 1;
+    rows.n_region = new_stride;
+    if ((rc = layer_forward(ctx, s, ctx->draft.layers[0], rows, kvl))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * 8, gather_last_rows(s, B, new_stride, h, n_new, x, feat, FR));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, add_i32(s, B, draft_kv->seq_len, n_new, 0));
+    kvl.seq_len_bound += new_stride;
+    return TLT_OK;
+}
+
 int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int n_verify, int mode,
                      const int32_t* new_tokens, const int32_t* new_src, const int32_t* n_new, int new_stride,
                      const float* hidden, int hidden_n, const int32_t* root_tokens, tlt_kv* draft_kv, tlt_tree* out_tree) {
@@ -388,23 +423,8 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     const tlt_layer_weights& lw = ctx->draft.layers[0];
     KVLayer kvl = kv_layer(ctx, draft_kv, 0);
 
-    if (do_extend) {
-        const int M = B * new_stride;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
-                draft_input(s, dt, B, new_stride, h, V, new_tokens, new_src, n_new, hidden_n, (int64_t)B * hidden_n, hidden,
-                            ctx->target.embed, ws + p.xn));
-        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
-        Rows rows;
-        rows.B = B;
-        rows.n = new_stride;
-        rows.n_valid = n_new;
-        rows.pos_stride = 1;
-        rows.n_region = new_stride;
-        if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * 8, gather_last_rows(s, B, new_stride, h, n_new, x, feat, FR));
-        TLT_RUN(ctx, s, CLS_OTHER, 0, 0, add_i32(s, B, draft_kv->seq_len, n_new, 0));
-        kvl.seq_len_bound += new_stride;
-    }
+    if (do_extend && (rc = draft_extend_rows(ctx, s, B, new_tokens, new_src, n_new, new_stride, hidden, hidden_n, draft_kv, kvl)))
+        return rc;
     if (!do_expand) return TLT_OK;
 
     DraftState st;
@@ -453,6 +473,123 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
             draft_prune(s, B, pool_n, out_tree->n, root_tokens, new_tokens, n_new, new_stride, st, out_tree->token, out_tree->parent, out_tree->depth,
                         out_tree->anc_mask, out_tree->score));
+    return TLT_OK;
+}
+
+int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int n_verify, float temperature,
+                     const int32_t* new_tokens, const int32_t* new_src, const int32_t* n_new, int new_stride,
+                     const float* hidden, int hidden_n, const int32_t* root_tokens, tlt_kv* draft_kv, const uint32_t* u_draw,
+                     tlt_tree* out_tree, float* out_draft_q) {
+    if (!ctx || !ctx->have_draft || B < 1 || depth < 1 || new_stride < 0 || topk < 1 || n_verify < 1 || !(temperature > 0.f))
+        return TLT_EINVAL;
+    const bool do_extend = new_stride > 0;
+    if (do_extend && (!new_tokens || !new_src || !n_new || !hidden || hidden_n < 1)) return TLT_EINVAL;
+    if (!tree_ok(out_tree) || !out_tree->score || (!root_tokens && !do_extend) || !u_draw || !out_draft_q) return TLT_EINVAL;
+    if (B > ctx->max_batch || new_stride > std::max(ctx->max_n, ctx->max_topk)) return TLT_ESHAPE;
+    if (depth > ctx->max_depth || topk > ctx->max_topk || n_verify > ctx->max_n) return TLT_ESHAPE;
+    // the template and, from it, the work of every level
+    int32_t t_parent[TLT_MAX_TREE], t_rank[TLT_MAX_TREE], t_depth[TLT_MAX_TREE], n = 0;
+    int rc = tlt_template_build(topk, depth, n_verify, t_parent, t_rank, t_depth, &n);
+    if (rc) return rc;
+    if (out_tree->n != n) return TLT_EINVAL;
+    int first_child[TLT_MAX_TREE], n_child[TLT_MAX_TREE] = {}, inner_idx[TLT_MAX_TREE];
+    for (int i = n - 1; i >= 1; --i) {
+        first_child[t_parent[i]] = i;   // children are consecutive: the last write is the lowest index
+        ++n_child[t_parent[i]];
+    }
+    int n_inner = 0;   // nodes other than the root that have children = provisional drafter rows
+    for (int i = 1; i < n; ++i) inner_idx[i] = n_child[i] ? n_inner++ : -1;
+    rc = check_kv(ctx, draft_kv, new_stride + n_inner);
+    if (rc) return rc;
+
+    struct DraftFlag {
+        tlt_ctx* c;
+        explicit DraftFlag(tlt_ctx* x) : c(x) { c->in_draft = true; }
+        ~DraftFlag() { c->in_draft = false; }
+    } draft_flag(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    const tlt_model_cfg& c = ctx->cfg;
+    const Plan& p = ctx->plan;
+    char* ws = ctx->ws;
+    const int h = c.hidden, V = c.vocab, dt = c.dtype;
+    const double e = (double)esz_of(ctx);
+    float* x = (float*)(ws + p.x);
+    float* feat = (float*)(ws + p.feat);
+    float* logits = (float*)(ws + p.logits);
+    int32_t* row_map = (int32_t*)(ws + p.row_map);
+    int32_t* fr_token = (int32_t*)(ws + p.fr_token);
+    int32_t* fr_src = (int32_t*)(ws + p.fr_src);
+    uint64_t* fr_mask = (uint64_t*)(ws + p.fr_mask);
+    const int FR = p.feat_rows;
+    const tlt_layer_weights& lw = ctx->draft.layers[0];
+    KVLayer kvl = kv_layer(ctx, draft_kv, 0);
+
+    if (do_extend && (rc = draft_extend_rows(ctx, s, B, new_tokens, new_src, n_new, new_stride, hidden, hidden_n, draft_kv, kvl)))
+        return rc;
+
+    TmplParents tp;
+    for (int i = 0; i < TLT_MAX_TREE; ++i) tp.parent[i] = (int8_t)(i < n ? t_parent[i] : -1);
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
+            tmpl_tree_init(s, B, n, tp, root_tokens, new_tokens, n_new, new_stride, out_tree->token, out_tree->parent,
+                           out_tree->score));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, tree_finalize(s, B, n, out_tree->parent, out_tree->depth, out_tree->anc_mask));
+    if (n == 1) return TLT_OK;
+
+    // the root's distribution (feature row 0 -> final norm -> LM head) and its children
+    TmplRows lv;
+    lv.R = 1;
+    lv.node[0] = 0;
+    lv.first_child[0] = (uint8_t)first_child[0];
+    lv.n_child[0] = (uint8_t)n_child[0];
+    TLT_RUN(ctx, s, CLS_OTHER, 0, 0, iota_scaled(s, B, row_map, FR));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * (4 + e),
+            rmsnorm(s, dt, B, h, feat, ctx->target.final_norm, c.rms_eps, ws + p.xn, row_map));
+    if ((rc = run_gemm(ctx, s, OUT_F32, B, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * V * 12,
+            softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q));
+
+    // level d: the nodes of depth d that have children, one drafter row each (provisional cache row
+    // and feature row 1 + its index among such nodes)
+    uint64_t mask_of[TLT_MAX_TREE] = {};
+    for (int d = 1; d < depth; ++d) {
+        lv.R = 0;
+        int slot_base = -1;
+        for (int i = 1; i < n; ++i) {
+            if (t_depth[i] != d || !n_child[i]) continue;
+            const int par = t_parent[i];
+            mask_of[i] = (par > 0 ? mask_of[par] : 0ull) | (1ull << inner_idx[i]);
+            if (slot_base < 0) slot_base = inner_idx[i];
+            const int r = lv.R++;
+            lv.node[r] = (uint8_t)i;
+            lv.first_child[r] = (uint8_t)first_child[i];
+            lv.n_child[r] = (uint8_t)n_child[i];
+            lv.src[r] = (uint8_t)(par > 0 ? 1 + inner_idx[par] : 0);
+            lv.mask[r] = mask_of[i];
+        }
+        if (lv.R == 0) break;
+        const int M = B * lv.R;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0, tmpl_level_rows(s, B, n, lv, out_tree->token, fr_token, fr_src, fr_mask));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
+                draft_input(s, dt, B, lv.R, h, V, fr_token, fr_src, nullptr, FR, (int64_t)B * FR, feat, ctx->target.embed,
+                            ws + p.xn));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+        Rows rows;
+        rows.B = B;
+        rows.n = lv.R;
+        rows.pos_base = d - 1;
+        rows.pos_stride = 0;
+        rows.slot_base = slot_base;
+        rows.mask = fr_mask;
+        rows.mask_words = 1;
+        rows.n_region = slot_base + lv.R;
+        if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, scatter_rows(s, M, lv.R, h, x, feat, FR, 1 + slot_base));
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
+                rmsnorm(s, dt, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
+        if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 12,
+                softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q));
+    }
     return TLT_OK;
 }
 

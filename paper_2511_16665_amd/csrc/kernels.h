@@ -95,6 +95,29 @@ hipError_t draft_prune(hipStream_t s, int B, int pool_n, int n_tree, const int32
                        const int32_t* new_tokens, const int32_t* n_new, int new_stride, DraftState st, int32_t* token, int32_t* parent, int32_t* depth, uint64_t* anc_mask, float* score);
 hipError_t tree_finalize(hipStream_t s, int B, int n, const int32_t* parent, int32_t* depth, uint64_t* anc_mask);
 
+// ---- sampled drafting on a static template (the same for every sequence; passed by value)
+struct TmplRows {   // the R template nodes one drafter pass / one sampling pass works on, per sequence
+    int R = 0;
+    uint8_t node[64];          // tree node index
+    uint8_t first_child[64];   // its children are nodes first_child .. first_child + n_child - 1, in rank order
+    uint8_t n_child[64];
+    uint8_t src[64];           // feature-buffer row holding its parent's drafter output
+    uint64_t mask[64];         // its visibility over the provisional drafter rows (itself and its ancestors)
+};
+struct TmplParents {
+    int8_t parent[64];
+};
+// token[b][0] = root (root_tokens, or the last new token), parent[b][i] = template parent, score = 0.
+hipError_t tmpl_tree_init(hipStream_t s, int B, int n, TmplParents tp, const int32_t* root_tokens, const int32_t* new_tokens,
+                          const int32_t* n_new, int new_stride, int32_t* token, int32_t* parent, float* score);
+// drafter input rows of one level: token of each node, feature row of its parent, visibility mask.
+hipError_t tmpl_level_rows(hipStream_t s, int B, int n, TmplRows rows, const int32_t* token, int32_t* fr_token, int32_t* fr_src,
+                           uint64_t* fr_mask);
+// per row (b, r): q[b][node] = softmax(logits[b*R + r] / temperature); then the node's children are
+// drawn from it one after the other without replacement with the uniforms u_draw[b][child].
+hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, TmplRows rows, const float* logits,
+                        const uint32_t* u_draw, int32_t* token, float* q);
+
 hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const int32_t* token, const int32_t* parent,
                          const float* logits, const int32_t* argmax, int32_t* accept_len, int32_t* path_idx,
                          int32_t* out_tokens, int32_t* n_out);

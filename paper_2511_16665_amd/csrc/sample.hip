@@ -418,6 +418,122 @@ __global__ void tree_finalize_k(int B, int n, const int32_t* __restrict__ parent
 }
 
 // ------------------------------------------------------------------------------------------------
+// Sampled drafting on a static template: a node's children are consecutive draws without
+// replacement from q = softmax(logits / temperature) at that node.  The draw is the integer rule
+// of the sampling acceptance (which presupposes exactly this process): weights floor(q_j * 2^32)
+// from the fp32 q that is handed to the caller, pick the first index whose running sum exceeds
+// (U * sum) >> 32, then zero the picked weight.  Given q, every pick is exact integer arithmetic.
+__global__ void tmpl_tree_init_k(int B, int n, TmplParents tp, const int32_t* __restrict__ root_tokens,
+                                 const int32_t* __restrict__ new_tokens, const int32_t* __restrict__ n_new, int new_stride,
+                                 int32_t* __restrict__ token, int32_t* __restrict__ parent, float* __restrict__ score) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * n) return;
+    int b = idx / n, i = idx - b * n;
+    parent[idx] = tp.parent[i];
+    score[idx] = 0.f;
+    if (i == 0) {
+        int t = -1;
+        if (root_tokens) {
+            t = root_tokens[b];
+        } else {
+            int k = n_new[b];
+            if (k >= 1 && k <= new_stride) t = new_tokens[(int64_t)b * new_stride + k - 1];
+        }
+        token[idx] = t;
+    }
+}
+
+__global__ void tmpl_level_rows_k(int B, int n, TmplRows rows, const int32_t* __restrict__ token,
+                                  int32_t* __restrict__ fr_token, int32_t* __restrict__ fr_src,
+                                  uint64_t* __restrict__ fr_mask) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * rows.R) return;
+    int b = idx / rows.R, r = idx - b * rows.R;
+    fr_token[idx] = token[(int64_t)b * n + rows.node[r]];
+    fr_src[idx] = rows.src[r];
+    fr_mask[idx] = rows.mask[r];
+}
+
+__device__ __forceinline__ unsigned long long q_weight(float q) {
+    return (unsigned long long)floor((double)q * 4294967296.0);
+}
+
+__global__ __launch_bounds__(256) void softmax_draw_k(int n, int V, float inv_temperature, TmplRows rows,
+                                                      const float* __restrict__ logits, const uint32_t* __restrict__ u_draw,
+                                                      int32_t* __restrict__ token, float* __restrict__ q_out) {
+    __shared__ float sf[4];
+    __shared__ unsigned long long su[4];
+    __shared__ unsigned long long scan[256];
+    __shared__ int pick_s;
+    __shared__ int removed[16];   // a node has at most 16 children (the largest topK)
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x / rows.R, r = blockIdx.x - b * rows.R;
+    const int node = rows.node[r], first = rows.first_child[r], n_child = rows.n_child[r];
+    const float* l = logits + (int64_t)blockIdx.x * V;
+    float* q = q_out + ((int64_t)b * n + node) * V;
+
+    float m = -INFINITY;
+    for (int j = tid; j < V; j += 256) m = fmaxf(m, l[j]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((tid & 63) == 0) sf[tid >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(sf[0], sf[1]), fmaxf(sf[2], sf[3]));
+    float part = 0.f;
+    for (int j = tid; j < V; j += 256) part += expf((l[j] - m) * inv_temperature);
+    const float inv = 1.0f / block_sum_f(part, sf);
+    for (int j = tid; j < V; j += 256) q[j] = expf((l[j] - m) * inv_temperature) * inv;
+    __syncthreads();   // the row is complete (and visible to the whole workgroup) before it is read back
+
+    // thread t owns the contiguous index range [j0, j1): running sums in index order
+    const int chunk = (V + 255) / 256;
+    const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
+    unsigned long long local = 0;
+    for (int j = j0; j < j1; ++j) local += q_weight(q[j]);
+    for (int c = 0; c < n_child; ++c) {
+        const unsigned long long S = block_sum_u64(local, su);
+        const unsigned long long thr =
+            (unsigned long long)(((unsigned __int128)u_draw[(int64_t)b * n + first + c] * (unsigned __int128)S) >> 32);
+        scan[tid] = local;
+        if (tid == 0) pick_s = V - 1;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long run = 0;
+            for (int t = 0; t < 256; ++t) {
+                unsigned long long v = scan[t];
+                scan[t] = run;
+                run += v;
+            }
+        }
+        __syncthreads();
+        const unsigned long long excl = scan[tid];
+        if (local > 0 && excl <= thr && thr < excl + local) {
+            unsigned long long run = excl;
+            for (int j = j0; j < j1; ++j) {
+                bool gone = false;
+                for (int k = 0; k < c; ++k) gone |= removed[k] == j;
+                if (!gone) run += q_weight(q[j]);
+                if (run > thr) {
+                    pick_s = j;
+                    break;
+                }
+            }
+        }
+        __syncthreads();
+        const int pick = pick_s;
+        bool gone = false;
+        for (int k = 0; k < c; ++k) gone |= removed[k] == pick;
+        if (!gone && pick >= j0 && pick < j1) local -= q_weight(q[pick]);
+        __syncthreads();
+        if (tid == 0) {
+            token[(int64_t)b * n + first + c] = pick;
+            removed[c] = pick;
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Acceptance.
 __global__ void accept_greedy_k(int B, int n, int stride, const int32_t* __restrict__ token,
                                 const int32_t* __restrict__ parent, const int32_t* __restrict__ argmax,
@@ -703,6 +819,27 @@ hipError_t draft_prune(hipStream_t s, int B, int pool_n, int n_tree, const int32
 
 hipError_t tree_finalize(hipStream_t s, int B, int n, const int32_t* parent, int32_t* depth, uint64_t* anc_mask) {
     hipLaunchKernelGGL(tree_finalize_k, dim3((B * n + 255) / 256), dim3(256), 0, s, B, n, parent, depth, anc_mask);
+    return hipGetLastError();
+}
+
+hipError_t tmpl_tree_init(hipStream_t s, int B, int n, TmplParents tp, const int32_t* root_tokens, const int32_t* new_tokens,
+                          const int32_t* n_new, int new_stride, int32_t* token, int32_t* parent, float* score) {
+    hipLaunchKernelGGL(tmpl_tree_init_k, dim3((B * n + 255) / 256), dim3(256), 0, s, B, n, tp, root_tokens, new_tokens, n_new,
+                       new_stride, token, parent, score);
+    return hipGetLastError();
+}
+
+hipError_t tmpl_level_rows(hipStream_t s, int B, int n, TmplRows rows, const int32_t* token, int32_t* fr_token, int32_t* fr_src,
+                           uint64_t* fr_mask) {
+    hipLaunchKernelGGL(tmpl_level_rows_k, dim3((B * rows.R + 255) / 256), dim3(256), 0, s, B, n, rows, token, fr_token, fr_src,
+                       fr_mask);
+    return hipGetLastError();
+}
+
+hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, TmplRows rows, const float* logits,
+                        const uint32_t* u_draw, int32_t* token, float* q) {
+    hipLaunchKernelGGL(softmax_draw_k, dim3(B * rows.R), dim3(256), 0, s, n, V, 1.0f / temperature, rows, logits, u_draw, token,
+                       q);
     return hipGetLastError();
 }
 

@@ -123,6 +123,48 @@ class Engine:
         self.pending_max_new = inc
         return al, out
 
+    # -- one sampled speculative-decoding step (static template, rejection-sampling acceptance)
+    def step_sampled(self, topk, depth, n_verify, temperature, u_draw, u_accept, u_final):
+        """u_draw, u_accept [B, n] and u_final [B]: uint32 device tensors (as int32 storage) with the
+        step's random numbers, n = node count of the template.  Returns (accept_len [B], out_tokens
+        [B, stride]) as numpy arrays; the tree, the draft distributions and the target logits of the
+        step stay available as self.tree(n), self.draft_q(n), self.logits(n)."""
+        B = self.B
+        n = len(tlt.template_build(topk, depth, n_verify)[0])
+        t, q, logits = self.tree(n), self.draft_q(n), self.logits(n)
+        if self.have_pending:
+            self.ctx.draft_sample(B, depth, topk, n_verify, temperature, self.out_tokens, self.path_idx, self.n_out,
+                                  self.pending_hidden, None, self.dkv, u_draw, t, q)
+            self.dkv.seq_len_bound += self.pending_max_new
+        else:
+            self.ctx.draft_sample(B, depth, topk, n_verify, temperature, None, None, None, None, self.root, self.dkv,
+                                  u_draw, t, q)
+        hid = self._buf("hid", n)
+        self.ctx.verify_forward(B, t, self.kv, out_logits=logits, out_argmax=None, out_hidden=hid)
+        self.ctx.accept(B, 1, temperature, t, logits, None, q, u_accept, u_final, self.stride, self.accept_len,
+                        self.path_idx, self.out_tokens, self.n_out)
+        self.ctx.kv_commit(B, self.kv, self.accept_len, self.path_idx, self.stride)
+        self.pending_hidden = hid
+        self.have_pending = True
+        al = self.accept_len.cpu().numpy()
+        out = self.out_tokens.cpu().numpy()
+        inc = int(al.max()) + 1
+        self.kv.seq_len_bound += inc
+        self.pending_max_new = inc
+        return al, out
+
+    def draft_q(self, n):
+        return self._big("q", n)
+
+    def logits(self, n):
+        return self._big("logits", n)
+
+    def _big(self, kind, n):
+        key = (kind, n)
+        if key not in self._trees:
+            self._trees[key] = torch.zeros((self.B, n, self.cfg.vocab), dtype=torch.float32, device="cuda")
+        return self._trees[key]
+
     # -- a step whose trees come from somewhere else (the model-free drafter, tlt_ngram_propose)
     def step_trees(self, token: np.ndarray, parent: np.ndarray):
         """token/parent [B, n] int32 host arrays (node 0 = root = last emitted token, parents before
