@@ -39,7 +39,10 @@ def build_workload(args):
 
     cfg = {"7b": QWEN7B, "32b": QWEN32B, "mid": MID}[args.model]
     B, K, D, N = args.batch, args.topk, args.depth, args.verify
-    ctx = lognormal_contexts(B, args.ctx_median, 0.8, args.ctx_cap, min(256, args.ctx_median), seed=0)
+    if getattr(args, "ctx_lo", None):   # the long-tail phase's few, long sequences: uniform lengths
+        ctx = np.random.default_rng(0).integers(args.ctx_lo, args.ctx_cap + 1, size=B).astype(np.int32)
+    else:
+        ctx = lognormal_contexts(B, args.ctx_median, 0.8, args.ctx_cap, min(256, args.ctx_median), seed=0)
     grow = (args.steps + args.warmup + 8) * (min(D, N - 1) + 1) * 2 + 64 + N
     caps = ctx + grow + max(D - 1, 0) * K
     table, n_pages = random_block_table(caps, cfg.page_size, seed=1, extra_pages=8)

@@ -168,3 +168,74 @@ def test_full_size_step_properties_and_sampled_parity():
     print(f"  committed cache rows rel err {worst:.3e}", flush=True)
     assert worst <= tol
     e.ctx.close()
+
+
+def test_full_size_sampled_step_long_tail_shape():
+    """One SAMPLED step at the long-tail phase's shape (7B, 4 sequences of 24k-32k tokens, static
+    template of depth 8 / topK 10 / 64 nodes, temperature 0.9), all 28 blocks and the full
+    vocabulary: template shape, every child draw exact given the GPU's own distribution, acceptance
+    bit-exact against the oracle's rule on the GPU's logits and distributions, cache lengths; and
+    the drafter's distributions of one sequence against the oracle's drafter on the same tokens."""
+    import bench
+    from oracle import sample_draft as osd
+
+    B, K, D, N, tau = 4, 10, 8, 64, 0.9
+    args = argparse.Namespace(model="7b", batch=B, topk=K, depth=D, verify=N, ctx_median=28672, ctx_cap=32768, ctx_lo=24576,
+                              steps=1, warmup=0, sweep=False)
+    print("building the long-tail workload", flush=True)
+    cfg, e, ctx, tw, dw, table, dtable, _ = bench.build_workload(args)
+    assert ctx.min() >= 24576 and ctx.max() <= 32768
+    parent, rank, depth = osd.static_template(K, D, N)
+    n = len(parent)
+    rng = np.random.default_rng(17)
+    u32 = lambda *s: rng.integers(0, 2**32, size=s, dtype=np.uint64).astype(np.uint32)
+    u_d, u_a, u_f = u32(B, n), u32(B, n), u32(B)
+    dev = lambda a: torch.from_numpy(a.view(np.int32)).cuda()
+    tok0 = e.out_tokens[:, 0].cpu().numpy().copy()
+    hid0 = e.pending_hidden.cpu().numpy().astype(np.float64).copy()
+    print("one sampled SD step on the GPU", flush=True)
+    al, out = e.step_sampled(K, D, N, tau, dev(u_d), dev(u_a), dev(u_f))
+    tree = e.tree(n)
+    g_tok, g_par, g_dep = (x.cpu().numpy() for x in (tree.token, tree.parent, tree.depth))
+    g_q, g_logits = e.draft_q(n).cpu().numpy(), e.logits(n).cpu().numpy()
+    kids = [[c for c in range(n) if parent[c] == i] for i in range(n)]
+    inner = [i for i in range(n) if kids[i]]
+    for b in range(B):
+        np.testing.assert_array_equal(g_par[b], parent)
+        np.testing.assert_array_equal(g_dep[b], depth)
+        assert g_tok[b, 0] == tok0[b]
+        rows = g_q[b, inner]
+        assert np.abs(rows.astype(np.float64).sum(axis=1) - 1.0).max() < 1e-3
+        for i in inner:          # exact draws, given the GPU's distribution
+            want = osd.draw_children_rows(g_q[b, i][None, :], u_d[b, kids[i]][None, :])[0]
+            np.testing.assert_array_equal(g_tok[b, kids[i]], want)
+    print("acceptance against the oracle's rule", flush=True)
+    o_al, o_path, o_out, o_nout = oacc.accept_sample(g_tok, g_par, g_logits, g_q, u_a, u_f, tau, e.stride)
+    np.testing.assert_array_equal(al, o_al)
+    np.testing.assert_array_equal(out, o_out)
+    np.testing.assert_array_equal(e.path_idx.cpu().numpy(), o_path)
+    np.testing.assert_array_equal(e.kv.seq_len.cpu().numpy(), ctx + al + 1)
+    np.testing.assert_array_equal(e.dkv.seq_len.cpu().numpy(), ctx + 1)
+    print("  accept lengths", al, flush=True)
+
+    # the drafter's distributions of the shortest sequence
+    b = int(np.argmin(ctx))
+    c = int(ctx[b])
+    print(f"oracle drafter on sequence {b} (context {c})", flush=True)
+    st = sd.SeqState(dataclasses.replace(cfg, n_layers=1), c + n + 16, dec.round_to_bf16)
+    # (the committed drafter cache was not touched by the step: provisional rows sit past it)
+    st.draft.k[:c] = dense_cache(e.dkv.k_pool, dtable, b, c, cfg.page_size)[0]
+    st.draft.v[:c] = dense_cache(e.dkv.v_pool, dtable, b, c, cfg.page_size)[0]
+    st.draft_len = c
+    tw64 = {"embed": _EmbedRows(tw["embed"]), "lm_head": dec.weights_to_f64(tw["lm_head"]),
+            "final_norm": dec.weights_to_f64(tw["final_norm"])}
+    dw64 = dec.weights_to_f64(dw)
+    sd.draft_extend(cfg, tw64, dw64, st, [int(tok0[b])], hid0[b, :1])
+    _, o_q = osd.draft_sample(cfg, tw64, dw64, st, int(tok0[b]), K, D, N, tau, u_d[b], forced_tokens=g_tok[b])
+    worst = 0.0
+    for i in inner:
+        lq = np.log(o_q[i][o_q[i] > 0].astype(np.float64))
+        worst = max(worst, rel_err(g_q[b, i], o_q[i]) / (lq.max() - lq.min()))
+    print(f"  worst rel err of q / spread of log q {worst:.3e}", flush=True)
+    assert worst <= TOL
+    e.ctx.close()
