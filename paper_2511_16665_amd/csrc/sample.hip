@@ -35,30 +35,57 @@ __device__ __forceinline__ void block_best(float& v, int& i, float* sv, int* si)
         }
 }
 
+// (NW waves per workgroup; the partial results are combined in wave order, so a float sum is
+// reproducible from run to run)
+template <int NW = 4>
 __device__ __forceinline__ float block_sum_f(float v, float* sv) {
     v = wave_sum(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
     __syncthreads();
-    return sv[0] + sv[1] + sv[2] + sv[3];
+    float r = sv[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r += sv[w];
+    return r;
 }
 
+template <int NW = 4>
+__device__ __forceinline__ float block_max_f(float v, float* sv) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sv[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r = fmaxf(r, sv[w]);
+    return r;
+}
+
+template <int NW = 4>
 __device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v, unsigned long long* sv) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
     __syncthreads();
-    return sv[0] + sv[1] + sv[2] + sv[3];
+    unsigned long long r = sv[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r += sv[w];
+    return r;
 }
 
+template <int NW = 4>
 __device__ __forceinline__ double block_max_d(double v, double* sv) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = v;
     __syncthreads();
-    return fmax(fmax(sv[0], sv[1]), fmax(sv[2], sv[3]));
+    double r = sv[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r = fmax(r, sv[w]);
+    return r;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -458,74 +485,143 @@ __device__ __forceinline__ unsigned long long q_weight(float q) {
     return (unsigned long long)floor((double)q * 4294967296.0);
 }
 
-__global__ __launch_bounds__(256) void softmax_draw_k(int n, int V, float inv_temperature, TmplRows rows,
-                                                      const float* __restrict__ logits, const uint32_t* __restrict__ u_draw,
-                                                      int32_t* __restrict__ token, float* __restrict__ q_out) {
-    __shared__ float sf[4];
-    __shared__ unsigned long long su[4];
-    __shared__ unsigned long long scan[256];
+// One workgroup of 16 waves per (sequence, node).  Wave w owns the contiguous index range
+// [w*Vw, (w+1)*Vw), Vw a multiple of 256, and walks it 256 elements at a time (four consecutive
+// elements per lane: 16-byte accesses when the row allows), so a wave's weight total is the total of
+// a contiguous range and the threshold search goes wave -> 256-element step -> lane -> element.
+constexpr int kDrawThreads = 1024, kDrawWaves = kDrawThreads / 64;
+
+template <bool VEC4>
+__device__ __forceinline__ void load4(const float* __restrict__ p, int idx, int V, float (&x)[4], float fill) {
+    if (VEC4) {   // V % 4 == 0 and idx % 4 == 0: all four in range or none
+        if (idx < V) {
+            const float4 v = *(const float4*)(p + idx);
+            x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        } else {
+            x[0] = x[1] = x[2] = x[3] = fill;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = idx + e < V ? p[idx + e] : fill;
+    }
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, float inv_temperature, TmplRows rows,
+                                                               const float* __restrict__ logits,
+                                                               const uint32_t* __restrict__ u_draw,
+                                                               int32_t* __restrict__ token, float* __restrict__ q_out) {
+    __shared__ float sf[kDrawWaves];
+    __shared__ unsigned long long wsum[kDrawWaves];
     __shared__ int pick_s;
     __shared__ int removed[16];   // a node has at most 16 children (the largest topK)
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x / rows.R, r = blockIdx.x - b * rows.R;
     const int node = rows.node[r], first = rows.first_child[r], n_child = rows.n_child[r];
     const float* l = logits + (int64_t)blockIdx.x * V;
     float* q = q_out + ((int64_t)b * n + node) * V;
+    float x[4];
 
     float m = -INFINITY;
-    for (int j = tid; j < V; j += 256) m = fmaxf(m, l[j]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    if ((tid & 63) == 0) sf[tid >> 6] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(sf[0], sf[1]), fmaxf(sf[2], sf[3]));
+    for (int i = tid * 4; i < V; i += kDrawThreads * 4) {
+        load4<VEC4>(l, i, V, x, -INFINITY);
+        m = fmaxf(fmaxf(m, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
+    }
+    m = block_max_f<kDrawWaves>(m, sf);
     float part = 0.f;
-    for (int j = tid; j < V; j += 256) part += expf((l[j] - m) * inv_temperature);
-    const float inv = 1.0f / block_sum_f(part, sf);
-    for (int j = tid; j < V; j += 256) q[j] = expf((l[j] - m) * inv_temperature) * inv;
-    __syncthreads();   // the row is complete (and visible to the whole workgroup) before it is read back
+    for (int i = tid * 4; i < V; i += kDrawThreads * 4) {
+        load4<VEC4>(l, i, V, x, -INFINITY);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) part += expf((x[e] - m) * inv_temperature);   // exp(-inf) = 0 past the end
+    }
+    const float inv = 1.0f / block_sum_f<kDrawWaves>(part, sf);
 
-    // thread t owns the contiguous index range [j0, j1): running sums in index order
-    const int chunk = (V + 255) / 256;
-    const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
-    unsigned long long local = 0;
-    for (int j = j0; j < j1; ++j) local += q_weight(q[j]);
+    // q, and each wave's integer weight total over its own range
+    const int Vw = (V + kDrawWaves * 256 - 1) / (kDrawWaves * 256) * 256;
+    const int w0 = wave * Vw, w1 = min(V, w0 + Vw);
+    unsigned long long acc = 0;
+    for (int i = w0 + lane * 4; i < w1; i += 256) {
+        load4<VEC4>(l, i, V, x, -INFINITY);
+        float qv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            qv[e] = expf((x[e] - m) * inv_temperature) * inv;
+            if (i + e < V) acc += q_weight(qv[e]);
+        }
+        if (VEC4) {
+            *(float4*)(q + i) = make_float4(qv[0], qv[1], qv[2], qv[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i + e < V) q[i + e] = qv[e];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) wsum[wave] = acc;
+    __syncthreads();   // totals published; the row is complete before any of it is read back
+
     for (int c = 0; c < n_child; ++c) {
-        const unsigned long long S = block_sum_u64(local, su);
+        unsigned long long S = 0;
+#pragma unroll
+        for (int w = 0; w < kDrawWaves; ++w) S += wsum[w];
         const unsigned long long thr =
             (unsigned long long)(((unsigned __int128)u_draw[(int64_t)b * n + first + c] * (unsigned __int128)S) >> 32);
-        scan[tid] = local;
+        // the wave whose range holds the threshold (none when every weight is zero)
+        int hit = -1;
+        unsigned long long base = 0;
+#pragma unroll
+        for (int w = 0; w < kDrawWaves; ++w) {
+            if (hit < 0) {
+                if (base + wsum[w] > thr) hit = w;
+                else base += wsum[w];
+            }
+        }
         if (tid == 0) pick_s = V - 1;
         __syncthreads();
-        if (tid == 0) {
-            unsigned long long run = 0;
-            for (int t = 0; t < 256; ++t) {
-                unsigned long long v = scan[t];
-                scan[t] = run;
-                run += v;
-            }
-        }
-        __syncthreads();
-        const unsigned long long excl = scan[tid];
-        if (local > 0 && excl <= thr && thr < excl + local) {
-            unsigned long long run = excl;
-            for (int j = j0; j < j1; ++j) {
-                bool gone = false;
-                for (int k = 0; k < c; ++k) gone |= removed[k] == j;
-                if (!gone) run += q_weight(q[j]);
-                if (run > thr) {
-                    pick_s = j;
+        if (wave == hit) {
+            for (int i0 = w0; i0 < w1; i0 += 256) {
+                const int i = i0 + lane * 4;
+                load4<VEC4>(q, i, V, x, 0.f);
+                unsigned long long wt[4], mine = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bool gone = i + e >= V;
+                    for (int k = 0; k < c; ++k) gone |= removed[k] == i + e;
+                    wt[e] = gone ? 0ull : q_weight(x[e]);
+                    mine += wt[e];
+                }
+                // inclusive scan of the lanes' sums
+                unsigned long long incl = mine;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const unsigned long long up = __shfl_up(incl, o, 64);
+                    if (lane >= o) incl += up;
+                }
+                const unsigned long long step_total = __shfl(incl, 63, 64);
+                if (base + step_total > thr) {   // uniform over the wave: the pick is in this step
+                    unsigned long long run = base + incl - mine;
+                    if (mine > 0 && run <= thr && thr < run + mine) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            run += wt[e];
+                            if (run > thr) {
+                                pick_s = i + e;
+                                break;
+                            }
+                        }
+                    }
                     break;
                 }
+                base += step_total;
             }
         }
         __syncthreads();
-        const int pick = pick_s;
-        bool gone = false;
-        for (int k = 0; k < c; ++k) gone |= removed[k] == pick;
-        if (!gone && pick >= j0 && pick < j1) local -= q_weight(q[pick]);
-        __syncthreads();
         if (tid == 0) {
+            const int pick = pick_s;
+            bool gone = false;
+            for (int k = 0; k < c; ++k) gone |= removed[k] == pick;
+            if (!gone) wsum[pick / Vw] -= q_weight(q[pick]);
             token[(int64_t)b * n + first + c] = pick;
             removed[c] = pick;
         }
@@ -575,7 +671,9 @@ __global__ void accept_greedy_k(int B, int n, int stride, const int32_t* __restr
 // reduction order.
 __device__ __forceinline__ double u64_to_d(unsigned long long x) { return (double)x; }
 
-__global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride, float temperature,
+constexpr int kAcceptThreads = 1024;   // one workgroup per sequence: as wide as a workgroup gets
+
+__global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, int stride, float temperature,
                                                        const int32_t* __restrict__ token,
                                                        const int32_t* __restrict__ parent,
                                                        const float* __restrict__ logits,
@@ -585,9 +683,9 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
                                                        int32_t* __restrict__ accept_len, int32_t* __restrict__ path_idx,
                                                        int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_out,
                                                        unsigned long long* __restrict__ ws) {
-    __shared__ unsigned long long su[4];
-    __shared__ double sd[4];
-    __shared__ unsigned long long scan[256];
+    __shared__ unsigned long long su[kAcceptThreads / 64];
+    __shared__ double sd[kAcceptThreads / 64];
+    __shared__ unsigned long long scan[kAcceptThreads];
     __shared__ int pick_s;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int32_t* tok = token + (int64_t)b * n;
@@ -597,7 +695,7 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
     unsigned long long* W = ws + (int64_t)b * 2 * V;
     unsigned long long* Qw = W + V;
     const double tau = (double)temperature;
-    for (int j = tid; j < stride; j += 256) {
+    for (int j = tid; j < stride; j += kAcceptThreads) {
         path[j] = -1;
         out[j] = -1;
     }
@@ -609,10 +707,10 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
         const float* l = logits + ((int64_t)b * n + cur) * V;
         const float* q = draft_q + ((int64_t)b * n + cur) * V;
         double m = -INFINITY;
-        for (int j = tid; j < V; j += 256) m = fmax(m, (double)l[j] / tau);
-        m = block_max_d(m, sd);
+        for (int j = tid; j < V; j += kAcceptThreads) m = fmax(m, (double)l[j] / tau);
+        m = block_max_d<kAcceptThreads / 64>(m, sd);
         unsigned long long s = 0, sq = 0;
-        for (int j = tid; j < V; j += 256) {
+        for (int j = tid; j < V; j += kAcceptThreads) {
             unsigned long long w = (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0);
             unsigned long long qw = (unsigned long long)floor((double)q[j] * 4294967296.0);
             W[j] = w;
@@ -620,8 +718,8 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
             s += w;
             sq += qw;
         }
-        S = block_sum_u64(s, su);
-        SQ = block_sum_u64(sq, su);
+        S = block_sum_u64<kAcceptThreads / 64>(s, su);
+        SQ = block_sum_u64<kAcceptThreads / 64>(sq, su);
         int next = -1;
         for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
             if (par[c] != cur) continue;  // uniform: every thread reads the same tree
@@ -635,16 +733,16 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
                 break;
             }
             unsigned long long s2 = 0;
-            for (int j = tid; j < V; j += 256) {
+            for (int j = tid; j < V; j += kAcceptThreads) {
                 double pj = u64_to_d(W[j]) / u64_to_d(S);
                 double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
                 double r = pj - qj;
                 if (r < 0.0) r = 0.0;
                 s2 += (unsigned long long)floor(r * 4294967296.0);
             }
-            s2 = block_sum_u64(s2, su);
+            s2 = block_sum_u64<kAcceptThreads / 64>(s2, su);
             if (s2 > 0) {
-                for (int j = tid; j < V; j += 256) {
+                for (int j = tid; j < V; j += kAcceptThreads) {
                     double pj = u64_to_d(W[j]) / u64_to_d(S);
                     double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
                     double r = pj - qj;
@@ -657,8 +755,8 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
             if (tid == 0) Qw[t] = 0;
             __syncthreads();
             unsigned long long sq2 = 0;
-            for (int j = tid; j < V; j += 256) sq2 += Qw[j];
-            SQ = block_sum_u64(sq2, su);
+            for (int j = tid; j < V; j += kAcceptThreads) sq2 += Qw[j];
+            SQ = block_sum_u64<kAcceptThreads / 64>(sq2, su);
         }
         if (next < 0) break;
         if (tid == 0) out[a] = tok[next];
@@ -671,8 +769,8 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
     __syncthreads();
     const unsigned long long thr =
         (unsigned long long)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32);
-    const int chunk = (V + 255) / 256;
-    const int j0 = tid * chunk, j1 = min(V, j0 + chunk);
+    const int chunk = (V + kAcceptThreads - 1) / kAcceptThreads;
+    const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
     unsigned long long local = 0;
     for (int j = j0; j < j1; ++j) local += W[j];
     scan[tid] = local;
@@ -680,7 +778,7 @@ __global__ __launch_bounds__(256) void accept_sample_k(int n, int V, int stride,
     __syncthreads();
     if (tid == 0) {
         unsigned long long run = 0;
-        for (int t = 0; t < 256; ++t) {
+        for (int t = 0; t < kAcceptThreads; ++t) {
             unsigned long long v = scan[t];
             scan[t] = run;
             run += v;
@@ -838,8 +936,14 @@ hipError_t tmpl_level_rows(hipStream_t s, int B, int n, TmplRows rows, const int
 
 hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, TmplRows rows, const float* logits,
                         const uint32_t* u_draw, int32_t* token, float* q) {
-    hipLaunchKernelGGL(softmax_draw_k, dim3(B * rows.R), dim3(256), 0, s, n, V, 1.0f / temperature, rows, logits, u_draw, token,
-                       q);
+    // 16-byte accesses need every row of the logits and of q to start on a 16-byte boundary
+    const bool vec4 = V % 4 == 0 && (((uintptr_t)logits | (uintptr_t)q) & 15) == 0;
+    if (vec4)
+        hipLaunchKernelGGL(softmax_draw_k<true>, dim3(B * rows.R), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                           logits, u_draw, token, q);
+    else
+        hipLaunchKernelGGL(softmax_draw_k<false>, dim3(B * rows.R), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                           logits, u_draw, token, q);
     return hipGetLastError();
 }
 
@@ -858,7 +962,7 @@ hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float t
                          const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
                          const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
                          int32_t* n_out, void* ws) {
-    hipLaunchKernelGGL(accept_sample_k, dim3(B), dim3(256), 0, s, n, V, stride, temperature, token, parent, logits,
+    hipLaunchKernelGGL(accept_sample_k, dim3(B), dim3(kAcceptThreads), 0, s, n, V, stride, temperature, token, parent, logits,
                        draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out, (unsigned long long*)ws);
     return hipGetLastError();
 }
