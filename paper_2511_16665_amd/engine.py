@@ -166,25 +166,45 @@ class Engine:
         return self._trees[key]
 
     # -- a step whose trees come from somewhere else (the model-free drafter, tlt_ngram_propose)
-    def step_trees(self, token: np.ndarray, parent: np.ndarray):
+    def _flush_pending(self):
+        """Brings the learned drafter's cache up to the committed length (extend only, no tree)."""
+        if self.have_pending:
+            self.ctx.draft_expand(self.B, 0, 1, 1, self.out_tokens, self.path_idx, self.n_out, self.pending_hidden, None,
+                                  self.dkv, None)
+            self.dkv.seq_len_bound += self.pending_max_new
+            self.have_pending = False
+
+    def step_trees(self, token: np.ndarray, parent: np.ndarray, keep_drafter=False):
         """token/parent [B, n] int32 host arrays (node 0 = root = last emitted token, parents before
         children).  Verifies, accepts greedily and commits; returns (accept_len [B], out_tokens [B, stride]).
-        The learned drafter's cache is not advanced: switching back to it needs a catch-up extend."""
+        With keep_drafter the learned drafter's cache follows along (one extend per step over the
+        accepted positions, from the target's hidden states), so that `step` can take over at any
+        time; without it the drafter's cache is left where it was."""
         B, n = token.shape
         assert B == self.B and n <= self.max_n
+        if keep_drafter:
+            self._flush_pending()
         t = self.tree(n)
         t.token.copy_(torch.from_numpy(np.ascontiguousarray(token, dtype=np.int32)).cuda())
         t.parent.copy_(torch.from_numpy(np.ascontiguousarray(parent, dtype=np.int32)).cuda())
         self.ctx.tree_finalize(B, t)
         am = self._buf("am", n)
-        self.ctx.verify_forward(B, t, self.kv, out_logits=None, out_argmax=am, out_hidden=None)
+        hid = self._buf("hid", n) if keep_drafter else None
+        self.ctx.verify_forward(B, t, self.kv, out_logits=None, out_argmax=am, out_hidden=hid)
         self.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, self.stride, self.accept_len, self.path_idx,
                         self.out_tokens, self.n_out)
         self.ctx.kv_commit(B, self.kv, self.accept_len, self.path_idx, self.stride)
         al = self.accept_len.cpu().numpy()
         out = self.out_tokens.cpu().numpy()
-        self.kv.seq_len_bound += int(al.max()) + 1
-        self.have_pending = False
+        inc = int(al.max()) + 1
+        self.kv.seq_len_bound += inc
+        if keep_drafter:
+            self.pending_hidden, self.pending_max_new, self.have_pending = hid, inc, True
+            self._flush_pending()
+            # the next root: each sequence's bonus token
+            self.root.copy_(self.out_tokens.gather(1, (self.n_out - 1).long().unsqueeze(1)).squeeze(1))
+        else:
+            self.have_pending = False
         return al, out
 
     # -- the same step replayed from captured HIP graphs

@@ -63,3 +63,68 @@ def test_ngram_trees_give_the_autoregressive_output_and_accept_planted_repeats()
     assert mean_accept > 1.0
     for e in (ref_e, sd_e):
         e.ctx.close()
+
+
+def test_switching_between_the_model_free_and_the_learned_drafter_keeps_the_drafter_cache_in_step():
+    """Steps alternate between n-gram trees (the learned drafter's cache following along) and the
+    learned drafter.  The output must stay the plain greedy continuation, and every tree the learned
+    drafter builds after a model-free phase must be the oracle's, whose drafter state is advanced
+    over the same accepted tokens: a stale or misaligned drafter cache would change those trees."""
+    from oracle import decoder as dec
+    from oracle import sd
+
+    cfg = TINY
+    B, P, depth, topk, n_nodes = 2, 24, 4, 2, 8
+    tw_dev, dw_dev, tw, dw = make_models(cfg, 31, "fp32", std=0.08)
+    pr = prompts(B, P, cfg.vocab, seed=9)
+    e, _, _ = make_engine(cfg, "fp32", tw_dev, dw_dev, B, n_nodes, depth, topk, P + 160, seed=3)
+    e.prefill(pr)
+    states, roots = [], []
+    for b in range(B):
+        st = sd.SeqState(cfg, P + 160)
+        roots.append(sd.prefill(cfg, tw, dw, st, [int(t) for t in pr[b]]))
+        states.append(st)
+    db = tlt.NGram(3)
+    for b in range(B):
+        db.insert(b, [int(t) for t in pr[b]])
+    seqs = [[int(t) for t in pr[b]] for b in range(B)]
+    plan = ["ngram", "ngram", "learned", "ngram", "learned", "learned", "ngram", "ngram", "ngram", "learned"]
+    same_trees = 0
+    for step, kind in enumerate(plan):
+        print(f"step {step}: {kind}", flush=True)
+        if kind == "ngram":
+            tok = np.zeros((B, n_nodes), np.int32)
+            par = np.zeros((B, n_nodes), np.int32)
+            for b in range(B):
+                tok[b], par[b], _ = db.propose(b, seqs[b][-8:], depth, topk, n_nodes)
+            al, out = e.step_trees(tok, par, keep_drafter=True)
+        else:
+            al, out = e.step(topk, depth, n_nodes)
+            g_tree = e.tree(n_nodes)
+            g_tok, g_par = g_tree.token.cpu().numpy(), g_tree.parent.cpu().numpy()
+        for b in range(B):
+            st = states[b]
+            if kind == "ngram":
+                depth_b = np.zeros(n_nodes, np.int64)
+                for i in range(1, n_nodes):
+                    depth_b[i] = depth_b[par[b, i]] + 1
+                fixed = sd.Tree(tok[b].astype(np.int64), par[b].astype(np.int64), depth_b, np.zeros(n_nodes))
+                o_out, o_a, *_ = sd.sd_step(cfg, tw, dw, st, roots[b], topk, depth, n_nodes, tree_fn=lambda s_, r_: fixed)
+            else:
+                o_out, o_a, o_tree, *_ = sd.sd_step(cfg, tw, dw, st, roots[b], topk, depth, n_nodes)
+                if np.array_equal(o_tree.token, g_tok[b]) and np.array_equal(o_tree.parent, g_par[b]):
+                    same_trees += 1
+                else:
+                    # only a near-tie between path scores may reorder the tree in fp32
+                    sc = np.sort(o_tree.score[1:])
+                    assert np.min(np.diff(sc)) < 1e-4, (step, b, "learned drafter's tree differs from the oracle's")
+            assert o_a == al[b] and o_out == [int(x) for x in out[b, : al[b] + 1]], (step, b)
+            roots[b] = o_out[-1]
+            seqs[b] += o_out
+            db.insert(b, seqs[b])
+    print("learned-drafter trees identical to the oracle's:", same_trees, "of", B * plan.count("learned"), flush=True)
+    assert same_trees >= B * plan.count("learned") - 1
+    for b in range(B):   # and the whole output is the plain greedy continuation
+        gen = seqs[b][P:]
+        assert gen == sd.ar_greedy(cfg, tw, [int(t) for t in pr[b]], len(gen))
+    e.ctx.close()
