@@ -24,9 +24,19 @@
  * Quantising to 2^-32 perturbs each probability by at most 2^-32 / p_max, which bounds the
  * departure from exact losslessness by V * 2^-32 in total variation.
  *
+ * Sampling on trees whose shape DOES depend on the drafter's values (the deterministic top-K trees of
+ * Section 5.1): the draft distribution may then not enter the rule at all.  "Target only": with the
+ * current target weights, child c is accepted with probability weight(c) / total -- the chance that
+ * a draw from the target would have been c -- and on rejection its weight is removed; when no child
+ * is left the emitted token is drawn from what remains.  By the chain rule this emits exactly a draw
+ * from the target at every node, for any tree.  All integer: accept iff (U * total) >> 32 < weight(c)
+ * (the inverse-CDF draw with c placed first), then total -= weight(c), weight(c) = 0; the final draw as above.
+ *
  * Pins (tests/test_oracle_accept.py): brute force over all root-to-leaf paths (greedy); a
  * chi-square test of two generated tokens against p(x1) p(x2|x1) on a 16-token vocabulary over
- * 1e6 draws with a negative control; the closed form sum_v min(p_v, q_v) for the first accept.
+ * 1e6 draws with a negative control; the closed form sum_v min(p_v, q_v) for the first accept;
+ * for the target-only rule the same chi-square test on deterministic top-K trees (the ones the
+ * p/q rule is biased on), the closed form P(accept first child) = p(c) and hand-worked thresholds.
  */
 #include <math.h>
 #include <stdint.h>
@@ -153,4 +163,48 @@ void oracle_accept_sample(int B, int n, int V, int stride, float temperature, co
     free(W);
     free(Qw);
     free(R);
+}
+
+/* Target-only rule (see the header): u_accept [B][n] is the uniform used when node i is tested,
+ * u_final [B] the uniform of the final draw. */
+void oracle_accept_target_only(int B, int n, int V, int stride, float temperature, const int32_t *token,
+                               const int32_t *parent, const float *logits, const uint32_t *u_accept,
+                               const uint32_t *u_final, int32_t *accept_len, int32_t *path_idx,
+                               int32_t *out_tokens, int32_t *n_out) {
+    uint64_t *W = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
+    const double tau = (double)temperature;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *tok = token + (size_t)b * n, *par = parent + (size_t)b * n;
+        int32_t *path = path_idx + (size_t)b * stride, *out = out_tokens + (size_t)b * stride;
+        for (int j = 0; j < stride; ++j) { path[j] = -1; out[j] = -1; }
+        int cur = 0, a = 0;
+        path[0] = 0;
+        uint64_t S;
+        for (;;) {
+            target_weights(logits + ((size_t)b * n + cur) * V, V, tau, W, &S);
+            int next = -1;
+            for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
+                if (par[c] != cur) continue;
+                int t = tok[c];
+                uint64_t thr = (uint64_t)(((unsigned __int128)u_accept[(size_t)b * n + c] * (unsigned __int128)S) >> 32);
+                if (thr < W[t]) { next = c; break; }
+                S -= W[t];
+                W[t] = 0;
+            }
+            if (next < 0) break;
+            out[a] = tok[next];
+            cur = next;
+            path[++a] = cur;
+        }
+        uint64_t thr = (uint64_t)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32), run = 0;
+        int pick = V - 1;
+        for (int j = 0; j < V; ++j) {
+            run += W[j];
+            if (run > thr) { pick = j; break; }
+        }
+        out[a] = pick;
+        accept_len[b] = a;
+        n_out[b] = a + 1;
+    }
+    free(W);
 }

@@ -75,6 +75,24 @@ def accept_sample(token, parent, logits, draft_q, u_accept, u_final, temperature
     return al, path, out, n_out
 
 
+def accept_target_only(token, parent, logits, u_accept, u_final, temperature, stride):
+    """The rule for trees whose shape depends on the drafter's values (deterministic top-K trees)."""
+    token = np.ascontiguousarray(token, np.int32)
+    parent = np.ascontiguousarray(parent, np.int32)
+    logits = np.ascontiguousarray(logits, np.float32)
+    u_accept = np.ascontiguousarray(u_accept, np.uint32)
+    u_final = np.ascontiguousarray(u_final, np.uint32)
+    B, n, V = logits.shape
+    assert u_accept.shape == (B, n) and u_final.shape == (B,)
+    al, path, out, n_out = _outputs(B, stride)
+    _load().oracle_accept_target_only(B, n, V, stride, ctypes.c_float(temperature), _p(token, ctypes.c_int32),
+                                      _p(parent, ctypes.c_int32), _p(logits, ctypes.c_float),
+                                      _p(u_accept, ctypes.c_uint32), _p(u_final, ctypes.c_uint32),
+                                      _p(al, ctypes.c_int32), _p(path, ctypes.c_int32), _p(out, ctypes.c_int32),
+                                      _p(n_out, ctypes.c_int32))
+    return al, path, out, n_out
+
+
 def draw_without_replacement(q, k, rng):
     """k distinct tokens per row of q [..., V]: the first from q, the next from q with the first
     removed and renormalised, and so on (done with the Gumbel-top-k identity).  Sibling lists of a

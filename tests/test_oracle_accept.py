@@ -170,3 +170,80 @@ def test_sampling_with_no_children_is_a_plain_draw_by_inverse_cdf():
     al, path, out, n_out = oa.accept_sample(token, parent, np.tile(logit, (B, 1, 1)), np.full((B, 1, 4), 0.25, np.float32),
                                             np.zeros((B, 1), np.uint32), us, 1.0, 1)
     assert list(out[:, 0]) == [0, 0, 1, 1, 2, 2, 3, 3] and (al == 0).all()
+
+
+# ---------------------------------------------------------------- target-only rule (any tree)
+def _step_target_only(rng, P, Q, roots):
+    """One SD step on root -> (c1 -> g, c2) with DETERMINISTIC top-k children of the drafter table."""
+    B = len(roots)
+    top = np.argsort(-Q, axis=-1)
+    kids = top[roots][:, :2]
+    g = top[kids[:, 0]][:, 0]
+    token = np.stack([roots, kids[:, 0], kids[:, 1], g], axis=1).astype(np.int32)
+    parent = np.tile(np.array([-1, 0, 0, 1], dtype=np.int32), (B, 1))
+    with np.errstate(divide="ignore"):
+        logits = np.log(P[token]).astype(np.float32)
+    u_acc = rng.integers(0, 2**32, size=(B, 4), dtype=np.uint64).astype(np.uint32)
+    u_fin = rng.integers(0, 2**32, size=B, dtype=np.uint64).astype(np.uint32)
+    return oa.accept_target_only(token, parent, logits, u_acc, u_fin, 1.0, 4)
+
+
+def test_target_only_rule_is_lossless_on_deterministic_topk_trees_chi_square():
+    """The trees of the negative control above (on which the p/q rule is biased): two generated
+    tokens against p(x1) p(x2|x1) over 1e6 draws."""
+    P, Q = _tables(0)
+    n_draws = 1_000_000
+    rng = np.random.default_rng(77)
+    x0 = 3
+    al, _, out, n_out = _step_target_only(rng, P, Q, np.full(n_draws, x0))
+    x1, x2 = out[:, 0].copy(), out[:, 1].copy()
+    need = n_out < 2
+    _, _, out2, _ = _step_target_only(rng, P, Q, x1[need])
+    x2[need] = out2[:, 0]
+    hist = np.zeros((V16, V16))
+    np.add.at(hist, (x1, x2), 1)
+    expected = (P[x0][:, None] * P) * n_draws
+    assert al.max() == 2 and (al == 0).mean() > 0.05
+    keep = expected > 5
+    chi2 = ((hist[keep] - expected[keep]) ** 2 / expected[keep]).sum() + \
+        (hist[~keep].sum() - expected[~keep].sum()) ** 2 / max(expected[~keep].sum(), 1e-9)
+    assert stats.chi2.sf(chi2, keep.sum()) > 1e-3
+
+
+def test_target_only_accept_probabilities_closed_form_and_hand_worked_thresholds():
+    # p = (.5, .25, .125, .125); children of the root: tokens 1 then 0
+    logit = np.log(np.array([0.5, 0.25, 0.125, 0.125])).astype(np.float32)
+    token = np.array([[9, 1, 0]], dtype=np.int32) % 4
+    parent = np.array([[-1, 0, 0]], dtype=np.int32)
+    e = 4096      # fp32 logs are not exact: stay a few thousand units clear of each boundary
+
+    def run(u1, u2, uf):
+        al, path, out, n_out = oa.accept_target_only(token, parent, np.tile(logit, (1, 3, 1)),
+                                                     np.array([[0, u1, u2]], dtype=np.uint64).astype(np.uint32),
+                                                     np.array([uf], dtype=np.uint64).astype(np.uint32), 1.0, 2)
+        return int(al[0]), [int(x) for x in path[0]], [int(x) for x in out[0]]
+    # child 1 (token 1, p = .25) is accepted iff U < .25
+    assert run(2**30 - e, 0, 0)[:2] == (1, [0, 1])
+    a, path, out = run(2**30 + e, 0, 0)
+    # rejected: token 1 removed (remaining mass .75); child 2 (token 0) accepted iff U * .75 < .5
+    assert (a, path) == (1, [0, 2]) and out[0] == 0
+    assert run(2**30 + e, int(2**32 * 2 / 3) - e, 0)[1] == [0, 2]
+    a, path, out = run(2**30 + e, int(2**32 * 2 / 3) + e, 0)
+    # both rejected: the emitted token is drawn from (0, 0, .125, .125): halves of the final uniform
+    assert (a, path) == (0, [0, -1]) and out[0] == 2
+    assert run(2**30 + e, int(2**32 * 2 / 3) + e, 2**31 + e)[2][0] == 3
+    # closed form over many draws: P(accept first child) = p(c), and the emitted token ~ p
+    rng = np.random.default_rng(3)
+    B = 400_000
+    lg = rng.normal(size=V16) * 1.5
+    p = np.exp(lg / 0.8) / np.exp(lg / 0.8).sum()
+    tok = np.tile(np.array([0, 5, 11], dtype=np.int32), (B, 1))
+    par = np.tile(np.array([-1, 0, 0], dtype=np.int32), (B, 1))
+    al, path, out, n_out = oa.accept_target_only(tok, par, np.tile(lg.astype(np.float32), (B, 3, 1)),
+                                                 rng.integers(0, 2**32, size=(B, 3), dtype=np.uint64).astype(np.uint32),
+                                                 rng.integers(0, 2**32, size=B, dtype=np.uint64).astype(np.uint32), 0.8, 2)
+    first = (path[:, 1] == 1).mean()
+    assert abs(first - p[5]) < 5 * np.sqrt(p[5] * (1 - p[5]) / B)
+    second = (path[:, 1] == 2).mean()
+    assert abs(second - p[11]) < 5 * np.sqrt(p[11] * (1 - p[11]) / B)
+    assert stats.chisquare(np.bincount(out[:, 0], minlength=V16), p * B).pvalue > 1e-3
