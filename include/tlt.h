@@ -181,6 +181,12 @@ int tlt_verify_forward(tlt_ctx *ctx, void *stream, int B, const tlt_tree *tree, 
  *   distribution node i's children were drawn from without replacement, u_accept [B][n] and
  *   u_final [B] are caller-supplied 32-bit uniforms.  Integer/double arithmetic as documented in
  *   the design notes makes every decision reproducible bit for bit.
+ * mode 2, sampling at `temperature` on trees whose shape depends on the drafter's values (the
+ *   deterministic top-k trees of tlt_draft_expand), where the draft distribution may not enter the
+ *   rule: with the node's integer target weights W (sum S), a child with token t and uniform U =
+ *   u_accept[b][child] is accepted iff (U * S) >> 32 < W[t], i.e. with the probability that a draw
+ *   from the target would have been t; a rejected child's weight leaves W and S; when no child is
+ *   left the token is drawn from what remains with u_final.  Lossless for any tree; draft_q unused.
  * Outputs (DEVICE): accept_len [B] (drafted tokens kept, without the bonus token); path_idx
  * [B][stride] node indices root..last accepted; out_tokens [B][stride] accepted tokens then the
  * bonus token; n_out [B] = accept_len+1; unused entries = -1.  stride >= 1 caps accept_len+1. */

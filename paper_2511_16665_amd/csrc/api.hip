@@ -623,6 +623,13 @@ int tlt_accept(tlt_ctx* ctx, void* stream, int B, int mode, float temperature, c
                               u_final, accept_len, path_idx, out_tokens, n_out, ctx->ws + ctx->plan.accept_ws));
         return TLT_OK;
     }
+    if (mode == 2) {
+        if (!target_logits || !u_accept || !u_final || !(temperature > 0.f)) return TLT_EINVAL;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
+                accept_target_only(s, B, n, V, stride, temperature, tree->token, tree->parent, target_logits, u_accept,
+                                   u_final, accept_len, path_idx, out_tokens, n_out));
+        return TLT_OK;
+    }
     return TLT_EINVAL;
 }
 

@@ -126,6 +126,9 @@ hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float t
                          const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
                          const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
                          int32_t* n_out, void* ws);
+hipError_t accept_target_only(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
+                              const int32_t* parent, const float* logits, const uint32_t* u_accept, const uint32_t* u_final,
+                              int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens, int32_t* n_out);
 hipError_t kv_commit(hipStream_t s, int dtype, int B, int n_layers, void* k_pool, void* v_pool, int64_t n_pages,
                      const int32_t* block_table, int32_t* seq_len, int max_pages, int page_size, int n_kv, int d,
                      const int32_t* accept_len, const int32_t* path_idx, int stride);

@@ -804,6 +804,120 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
     }
 }
 
+// Target-only rule (for trees whose shape depends on the drafter's values): child c is accepted
+// iff (U * S) >> 32 < W[token(c)] with the node's current integer target weights, a rejected child's
+// weight leaves S; no child left -> the same final draw from what remains.  Weights are recomputed
+// from the logits where needed (W_j = floor(exp(l_j/tau - max) * 2^32), exp in double), the tokens
+// removed at the current node are kept in a short list; no workspace.
+__global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, int V, int stride, float temperature,
+                                                                      const int32_t* __restrict__ token,
+                                                                      const int32_t* __restrict__ parent,
+                                                                      const float* __restrict__ logits,
+                                                                      const uint32_t* __restrict__ u_accept,
+                                                                      const uint32_t* __restrict__ u_final,
+                                                                      int32_t* __restrict__ accept_len,
+                                                                      int32_t* __restrict__ path_idx,
+                                                                      int32_t* __restrict__ out_tokens,
+                                                                      int32_t* __restrict__ n_out) {
+    __shared__ unsigned long long su[kAcceptThreads / 64];
+    __shared__ double sd[kAcceptThreads / 64];
+    __shared__ unsigned long long scan[kAcceptThreads];
+    __shared__ int pick_s;
+    __shared__ int removed[64];   // a node has fewer than 64 children
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int32_t* tok = token + (int64_t)b * n;
+    const int32_t* par = parent + (int64_t)b * n;
+    int32_t* path = path_idx + (int64_t)b * stride;
+    int32_t* out = out_tokens + (int64_t)b * stride;
+    const double tau = (double)temperature;
+    for (int j = tid; j < stride; j += kAcceptThreads) {
+        path[j] = -1;
+        out[j] = -1;
+    }
+    __syncthreads();
+    int cur = 0, a = 0, n_removed = 0;
+    if (tid == 0) path[0] = 0;
+    unsigned long long S = 0;
+    double m = 0.0;
+    const float* l = logits;
+    auto weight = [&](int j) { return (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0); };
+    auto is_removed = [&](int j) {
+        bool gone = false;
+        for (int k = 0; k < n_removed; ++k) gone |= removed[k] == j;
+        return gone;
+    };
+    for (;;) {
+        l = logits + ((int64_t)b * n + cur) * V;
+        m = -INFINITY;
+        for (int j = tid; j < V; j += kAcceptThreads) m = fmax(m, (double)l[j] / tau);
+        m = block_max_d<kAcceptThreads / 64>(m, sd);
+        unsigned long long s = 0;
+        for (int j = tid; j < V; j += kAcceptThreads) s += weight(j);
+        S = block_sum_u64<kAcceptThreads / 64>(s, su);
+        n_removed = 0;
+        int next = -1;
+        for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
+            if (par[c] != cur) continue;   // uniform: every thread reads the same tree
+            const int t = tok[c];
+            __syncthreads();               // the removed list as left by the previous child
+            const unsigned long long wt = (t >= 0 && t < V && !is_removed(t)) ? weight(t) : 0ull;
+            const unsigned long long thr =
+                (unsigned long long)(((unsigned __int128)u_accept[(int64_t)b * n + c] * (unsigned __int128)S) >> 32);
+            if (thr < wt) {
+                next = c;
+                break;
+            }
+            S -= wt;
+            __syncthreads();
+            if (tid == 0 && wt > 0) removed[n_removed] = t;
+            if (wt > 0) ++n_removed;
+        }
+        if (next < 0) break;
+        if (tid == 0) out[a] = tok[next];
+        cur = next;
+        ++a;
+        if (tid == 0) path[a] = cur;
+        __syncthreads();
+    }
+    // final draw from what remains at the last node
+    __syncthreads();
+    const unsigned long long thr =
+        (unsigned long long)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32);
+    const int chunk = (V + kAcceptThreads - 1) / kAcceptThreads;
+    const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
+    unsigned long long local = 0;
+    for (int j = j0; j < j1; ++j) local += is_removed(j) ? 0ull : weight(j);
+    scan[tid] = local;
+    if (tid == 0) pick_s = V - 1;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long run = 0;
+        for (int t = 0; t < kAcceptThreads; ++t) {
+            unsigned long long v = scan[t];
+            scan[t] = run;
+            run += v;
+        }
+    }
+    __syncthreads();
+    const unsigned long long excl = scan[tid];
+    if (local > 0 && excl <= thr && thr < excl + local) {
+        unsigned long long run = excl;
+        for (int j = j0; j < j1; ++j) {
+            run += is_removed(j) ? 0ull : weight(j);
+            if (run > thr) {
+                pick_s = j;
+                break;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        out[a] = pick_s;
+        accept_len[b] = a;
+        n_out[b] = a + 1;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // KV commit: row seq_len+path[j] -> row seq_len+j, j = 1..accept_len, for one (sequence, layer,
 // kv head) per workgroup.  A thread owns one 16-byte column chunk of K or V for all j and walks j
@@ -964,6 +1078,14 @@ hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float t
                          int32_t* n_out, void* ws) {
     hipLaunchKernelGGL(accept_sample_k, dim3(B), dim3(kAcceptThreads), 0, s, n, V, stride, temperature, token, parent, logits,
                        draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out, (unsigned long long*)ws);
+    return hipGetLastError();
+}
+
+hipError_t accept_target_only(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
+                              const int32_t* parent, const float* logits, const uint32_t* u_accept, const uint32_t* u_final,
+                              int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens, int32_t* n_out) {
+    hipLaunchKernelGGL(accept_target_only_k, dim3(B), dim3(kAcceptThreads), 0, s, n, V, stride, temperature, token, parent,
+                       logits, u_accept, u_final, accept_len, path_idx, out_tokens, n_out);
     return hipGetLastError();
 }
 

@@ -90,10 +90,12 @@ class Engine:
         self.have_pending = True
 
     # -- one speculative-decoding step
-    def step(self, topk, depth, n_verify, sync=True, logits_out=None):
+    def step(self, topk, depth, n_verify, sync=True, logits_out=None, sample=None):
         """Runs the four calls.  With sync=True returns (accept_len [B], out_tokens [B, stride]) as
         numpy arrays and keeps the host-side length bounds exact; with sync=False nothing is read
-        back and the bounds advance by the largest possible accept length."""
+        back and the bounds advance by the largest possible accept length.
+        sample = (temperature, u_accept [B, n], u_final [B]) switches the acceptance from greedy to
+        the target-only sampling rule (the drafter's top-k tree stays as it is)."""
         B = self.B
         pool = topk + (depth - 1) * topk * topk if depth >= 1 else 0
         n = min(n_verify, 1 + pool)
@@ -106,9 +108,16 @@ class Engine:
         else:
             self.ctx.draft_expand(B, depth, topk, n_verify, None, None, None, None, self.root, self.dkv, t)
         hid, am = self._buf("hid", n), self._buf("am", n)
-        self.ctx.verify_forward(B, t, self.kv, out_logits=logits_out, out_argmax=am, out_hidden=hid)
-        self.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, self.stride, self.accept_len, self.path_idx,
-                        self.out_tokens, self.n_out)
+        if sample is None:
+            self.ctx.verify_forward(B, t, self.kv, out_logits=logits_out, out_argmax=am, out_hidden=hid)
+            self.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, self.stride, self.accept_len, self.path_idx,
+                            self.out_tokens, self.n_out)
+        else:
+            temperature, u_accept, u_final = sample
+            logits = logits_out if logits_out is not None else self.logits(n)
+            self.ctx.verify_forward(B, t, self.kv, out_logits=logits, out_argmax=None, out_hidden=hid)
+            self.ctx.accept(B, 2, temperature, t, logits, None, None, u_accept, u_final, self.stride, self.accept_len,
+                            self.path_idx, self.out_tokens, self.n_out)
         self.ctx.kv_commit(B, self.kv, self.accept_len, self.path_idx, self.stride)
         self.pending_hidden = hid
         self.have_pending = True

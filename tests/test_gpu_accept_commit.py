@@ -105,6 +105,41 @@ def test_sampling_accept_bit_exact(B, n, V, tau, k):
     ctx.close()
 
 
+@pytest.mark.parametrize("B,n,V,tau,k", [(256, 4, 16, 1.0, 2), (16, 21, 1000, 0.9, 4), (4, 64, 152064, 0.9, 3), (8, 64, 97, 0.7, 63)])
+def test_target_only_sampling_accept_bit_exact(B, n, V, tau, k):
+    """Deterministic top-k trees of a noisy copy of the target (the trees the target-only rule is
+    for); the last case hangs 63 children (with repeated tokens) under the root."""
+    rng = np.random.default_rng(V + n + 1)
+    cfg, ctx = _ctx(V, B, n)
+    logits = synthetic_logits((B, n, V), seed=8)
+    if V == 16:
+        logits = logits * 3                             # peaked targets: accepts happen often
+    ql = logits + rng.standard_normal(size=logits.shape).astype(np.float32)
+    token = np.zeros((B, n), dtype=np.int32)
+    parent = np.full((B, n), -1, dtype=np.int32)
+    for b in range(B):                                 # breadth-first k-ary tree of the k most likely tokens
+        nxt = 1
+        for p in range(n):
+            if nxt >= n:
+                break
+            kids = np.argsort(-ql[b, p])[:k] if k <= V else rng.integers(0, V, size=k)
+            if k == 63:
+                kids = rng.integers(0, V, size=k)       # arbitrary tokens, some repeated
+            for t in kids:
+                if nxt < n:
+                    token[b, nxt], parent[b, nxt] = t, p
+                    nxt += 1
+    u_acc, u_fin = uniforms_u32((B, n), 21), uniforms_u32((B,), 22)
+    stride = 6
+    want = oa.accept_target_only(token, parent, logits, u_acc, u_fin, tau, stride)
+    print(f"target-only accept B={B} n={n} V={V}: accept lengths up to {want[0].max()}", flush=True)
+    got = _run_accept(ctx, B, n, stride, 2, _tree_dev(token, parent), logits=_dev(logits), u_accept=_dev(u_acc),
+                      u_final=_dev(u_fin), temperature=tau)
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype", [tlt.TLT_F32, tlt.TLT_BF16])
 def test_kv_commit_bit_exact_and_touches_nothing_else(dtype):
     cfg = dataclasses.replace(TINY, n_layers=3)

@@ -146,3 +146,40 @@ def test_sampled_sd_steps_end_to_end_decisions_match_the_oracle_rule():
     print("accepted drafts over 6 steps:", total, flush=True)
     assert total > 0
     e.ctx.close()
+
+
+def test_topk_tree_steps_with_target_only_sampling_acceptance_match_the_oracle_rule():
+    """The drafter's deterministic top-k trees with the target-only sampling rule (the variant for
+    trees whose shape depends on the drafter): six steps, every decision equal to the oracle's rule on
+    the GPU's own tree and logits, lengths and roots carried from step to step.  (A child is accepted
+    with the target's own probability of its token, which is tiny for a random model's flat
+    distribution at temperature 0.9; a low temperature makes the targets peaked so that accepts occur.)"""
+    cfg = TINY
+    B, K, D, N, tau = 4, 3, 4, 12, 0.02
+    tw_dev, dw_dev, tw, dw = make_models(cfg, 7, "fp32", std=0.08)
+    P = 24
+    e, table, dtable = make_engine(cfg, "fp32", tw_dev, dw_dev, B, max(N, P), D, K, P + 6 * (D + 1) + N + 32, seed=2)
+    pr = np.stack(prompts(B, P, cfg.vocab, seed=4)).astype(np.int32)
+    e.prefill(pr)
+    rng = np.random.default_rng(19)
+    lens = np.full(B, P - 1)
+    root = pr[:, -1].copy()
+    total = 0
+    for step in range(6):
+        u_a, u_f = _u32(rng, B, N), _u32(rng, B)
+        print(f"target-only step {step}", flush=True)
+        al, out = e.step(K, D, N, sample=(tau, _dev_u32(u_a), _dev_u32(u_f)))
+        tree = e.tree(N)
+        g_tok, g_par = tree.token.cpu().numpy(), tree.parent.cpu().numpy()
+        np.testing.assert_array_equal(g_tok[:, 0], root)
+        o_al, o_path, o_out, o_nout = oacc.accept_target_only(g_tok, g_par, e.logits(N).cpu().numpy(), u_a, u_f, tau, e.stride)
+        np.testing.assert_array_equal(al, o_al)
+        np.testing.assert_array_equal(out, o_out)
+        np.testing.assert_array_equal(e.path_idx.cpu().numpy(), o_path)
+        lens = lens + al + 1
+        np.testing.assert_array_equal(e.kv.seq_len.cpu().numpy(), lens)
+        root = np.array([out[b, al[b]] for b in range(B)])
+        total += int(al.sum())
+    print("accepted drafts over 6 steps:", total, flush=True)
+    assert total > 0
+    e.ctx.close()
