@@ -93,6 +93,13 @@ def mlp(cfg, w, x):
 
 
 # ----------------------------------------------------------------------------- cache-free definition
+def qkv_projection(lw, xn):
+    """Query/key/value projection; `bqkv` (optional) is the additive bias that the Qwen2.5 family of
+    Section 6.1's target models carries on exactly these three projections."""
+    qkv = xn @ lw["wqkv"].T
+    return qkv + lw["bqkv"] if "bqkv" in lw else qkv
+
+
 def dense_forward(cfg, w, tokens, n_layers=None):
     """Textbook causal forward of the whole token sequence with no cache.
 
@@ -107,7 +114,7 @@ def dense_forward(cfg, w, tokens, n_layers=None):
     layers = w["layers"] if n_layers is None else w["layers"][:n_layers]
     for lw in layers:
         xn = rmsnorm(x, lw["attn_norm"], cfg.rms_eps)
-        qkv = xn @ lw["wqkv"].T
+        qkv = qkv_projection(lw, xn)
         q = qkv[:, : cfg.q_dim].reshape(T, cfg.n_q_heads, cfg.head_dim)
         k = qkv[:, cfg.q_dim : cfg.q_dim + cfg.kv_dim].reshape(T, cfg.n_kv_heads, cfg.head_dim)
         v = qkv[:, cfg.q_dim + cfg.kv_dim :].reshape(T, cfg.n_kv_heads, cfg.head_dim)
@@ -138,7 +145,7 @@ def block_rows(cfg, lw, x, pos, slots, visible, cache: LayerCache, store=identit
     visible [n, T] says which cache rows 0..T-1 (T > max slot) each new row may attend to."""
     n = x.shape[0]
     xn = rmsnorm(x, lw["attn_norm"], cfg.rms_eps)
-    qkv = xn @ lw["wqkv"].T
+    qkv = qkv_projection(lw, xn)
     q = qkv[:, : cfg.q_dim].reshape(n, cfg.n_q_heads, cfg.head_dim)
     k = qkv[:, cfg.q_dim : cfg.q_dim + cfg.kv_dim].reshape(n, cfg.n_kv_heads, cfg.head_dim)
     v = qkv[:, cfg.q_dim + cfg.kv_dim :].reshape(n, cfg.n_kv_heads, cfg.head_dim)

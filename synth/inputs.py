@@ -80,9 +80,11 @@ def _gain(n, seed, device, dtype, jitter):
     return (1.0 + t).to(dtype)
 
 
-def _layer(cfg: ModelCfg, seed: int, device, dtype, std, jitter):
+def _layer(cfg: ModelCfg, seed: int, device, dtype, std, jitter, qkv_bias=False):
     h, F = cfg.hidden, cfg.mlp
+    bias = {"bqkv": _normal((cfg.qkv_dim,), 10 * std, seed + 8, device, dtype)} if qkv_bias else {}
     return {
+        **bias,
         "attn_norm": _gain(h, seed + 1, device, dtype, jitter),
         "wqkv": _normal((cfg.qkv_dim, h), std, seed + 2, device, dtype),
         "wo": _normal((h, cfg.q_dim), std, seed + 3, device, dtype),
@@ -94,8 +96,9 @@ def _layer(cfg: ModelCfg, seed: int, device, dtype, std, jitter):
 
 
 def make_decoder_weights(cfg: ModelCfg, seed: int, device="cpu", dtype=torch.float32, std=0.02,
-                         norm_jitter=0.1, n_layers=None):
-    """Random-init decoder: every matrix iid N(0, std^2), norm gains 1 + N(0, norm_jitter^2).
+                         norm_jitter=0.1, n_layers=None, qkv_bias=False):
+    """Random-init decoder: every matrix iid N(0, std^2), norm gains 1 + N(0, norm_jitter^2);
+    qkv_bias adds a bias N(0, (10 std)^2) on the query/key/value projections.
 
     Matrices are stored [out_features, in_features] row-major.  `wqkv` stacks the q heads, then
     the k heads, then the v heads along the output dimension.  One seed per tensor, derived from
@@ -107,7 +110,7 @@ def make_decoder_weights(cfg: ModelCfg, seed: int, device="cpu", dtype=torch.flo
         "embed": _normal((cfg.vocab, cfg.hidden), std, base + 11, device, dtype),
         "lm_head": _normal((cfg.vocab, cfg.hidden), std, base + 12, device, dtype),
         "final_norm": _gain(cfg.hidden, base + 13, device, dtype, norm_jitter),
-        "layers": [_layer(cfg, base + 1000 * (l + 1), device, dtype, std, norm_jitter) for l in range(L)],
+        "layers": [_layer(cfg, base + 1000 * (l + 1), device, dtype, std, norm_jitter, qkv_bias) for l in range(L)],
     }
 
 

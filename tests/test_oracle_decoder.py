@@ -94,7 +94,7 @@ def _torch_reference_forward(cfg, w, tokens):
 
     for lw in w["layers"]:
         xn = F.rms_norm(x, (cfg.hidden,), t(lw["attn_norm"]), eps=cfg.rms_eps)
-        qkv = F.linear(xn, t(lw["wqkv"]))
+        qkv = F.linear(xn, t(lw["wqkv"]), t(lw["bqkv"]) if "bqkv" in lw else None)
         q, k, v = torch.split(qkv, [cfg.q_dim, cfg.kv_dim, cfg.kv_dim], dim=-1)
         q = rotary(q.reshape(T, cfg.n_q_heads, cfg.head_dim)).permute(1, 0, 2)[None]
         k = rotary(k.reshape(T, cfg.n_kv_heads, cfg.head_dim)).permute(1, 0, 2)[None]
@@ -106,9 +106,10 @@ def _torch_reference_forward(cfg, w, tokens):
     return F.linear(F.rms_norm(x, (cfg.hidden,), t(w["final_norm"]), eps=cfg.rms_eps), t(w["lm_head"])).numpy(), x.numpy()
 
 
-@pytest.mark.parametrize("std", [0.02, 0.3])
-def test_dense_forward_matches_torch_assembly(std):
-    w = dec.weights_to_f64(make_decoder_weights(SMALL, seed=5, std=std))
+@pytest.mark.parametrize("std,bias", [(0.02, False), (0.3, False), (0.1, True)])
+def test_dense_forward_matches_torch_assembly(std, bias):
+    w = dec.weights_to_f64(make_decoder_weights(SMALL, seed=5, std=std, qkv_bias=bias))
+    assert ("bqkv" in w["layers"][0]) == bias
     tokens = list(np.random.default_rng(6).integers(0, SMALL.vocab, size=12))
     logits, hidden, ks, vs = dec.dense_forward(SMALL, w, tokens)
     want_logits, want_hidden = _torch_reference_forward(SMALL, w, tokens)

@@ -14,8 +14,8 @@ MICRO = dataclasses.replace(TINY, name="micro", hidden=64, n_q_heads=4, n_kv_hea
                             vocab=40, n_layers=2)
 
 
-def _models(cfg, seed, std=0.02):
-    tw = dec.weights_to_f64(make_decoder_weights(cfg, seed, std=std))
+def _models(cfg, seed, std=0.02, qkv_bias=False):
+    tw = dec.weights_to_f64(make_decoder_weights(cfg, seed, std=std, qkv_bias=qkv_bias))
     dw = dec.weights_to_f64(make_drafter_weights(cfg, seed, std=std))
     return tw, dw
 
@@ -92,10 +92,10 @@ def _random_tree(rng, n, vocab):
     return sd.Tree(rng.integers(0, vocab, size=n), parent, depth, np.zeros(n))
 
 
-@pytest.mark.parametrize("ctx", [0, 7])
-def test_tree_verification_equals_per_path_causal_forward(ctx):
+@pytest.mark.parametrize("ctx,bias", [(0, False), (7, False), (7, True)])
+def test_tree_verification_equals_per_path_causal_forward(ctx, bias):
     cfg = MICRO
-    tw, dw = _models(cfg, 21, std=0.3)
+    tw, dw = _models(cfg, 21, std=0.3, qkv_bias=bias)
     rng = np.random.default_rng(ctx)
     context = [int(t) for t in rng.integers(0, cfg.vocab, size=ctx)]
     st = sd.SeqState(cfg, 64)
