@@ -51,9 +51,12 @@ typedef struct tlt_model_cfg {
 } tlt_model_cfg;
 
 /* DEVICE pointers to one decoder block's parameters, all of the model dtype.
- * wqkv [(Hq+2Hkv)*d][h] stacks q heads, k heads, v heads; wo [h][Hq*d]; wg, wu [F][h]; wd [h][F]. */
+ * wqkv [(Hq+2Hkv)*d][h] stacks q heads, k heads, v heads; wo [h][Hq*d]; wg, wu [F][h]; wd [h][F].
+ * bqkv [(Hq+2Hkv)*d] is the bias of the query/key/value projections (the Qwen2.5 targets of
+ * Section 6.1 have one), added before the rotary embedding; NULL = no bias. */
 typedef struct tlt_layer_weights {
     const void *attn_norm, *wqkv, *wo, *mlp_norm, *wg, *wu, *wd;
+    const void *bqkv;
 } tlt_layer_weights;
 
 /* embed, lm_head [V][h], final_norm [h]: DEVICE.  layers: HOST array of n_layers entries (copied by

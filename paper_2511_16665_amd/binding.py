@@ -41,7 +41,7 @@ class ModelCfgC(C.Structure):
 
 
 class LayerWeightsC(C.Structure):
-    _fields_ = [(k, C.c_void_p) for k in ("attn_norm", "wqkv", "wo", "mlp_norm", "wg", "wu", "wd")]
+    _fields_ = [(k, C.c_void_p) for k in ("attn_norm", "wqkv", "wo", "mlp_norm", "wg", "wu", "wd", "bqkv")]
 
 
 class WeightsC(C.Structure):
@@ -174,7 +174,8 @@ def _weights_c(w: dict, n_layers: int, fc=None, keep=None):
     src = w["layers"] if "layers" in w else [w["layer"]]
     for i in range(n_layers):
         for k, _ in LayerWeightsC._fields_:
-            setattr(layers[i], k, src[i][k].data_ptr())
+            if k in src[i]:                 # (bqkv is optional: a missing entry stays NULL)
+                setattr(layers[i], k, src[i][k].data_ptr())
     keep.append(layers)
     return layers
 

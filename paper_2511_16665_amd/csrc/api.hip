@@ -194,7 +194,7 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     int rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr));
     if ((rc = run_gemm(ctx, s, OUT_T, M, qkv_dim, h, ws + p.xn, w.wqkv, ws + p.qkv))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2, rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta));
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2, rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv));
     {
         // algorithmic traffic: one pass over the cached K and V of every sequence (bounded by the
         // host-known length) plus q in / out; flops: 4 * d per (query row, head, key)

@@ -84,10 +84,11 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, const float* __restr
 
 // One workgroup per row.  Angles are formed in double (positions reach 32K, where an fp32 product
 // pos * inv_freq already carries ~1e-3 rad of rounding), once per (row, pair index), then reused by
-// every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.
+// every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.  An
+// optional projection bias is added first (to q, k and v).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T* __restrict__ qkv, int n_q_heads,
-                                                       float theta) {
+                                                       float theta, const T* __restrict__ bias) {
     extern __shared__ float cs[];  // [d/2] cos, [d/2] sin
     const int d = kv.d, half = d >> 1;
     int r = blockIdx.x;
@@ -115,6 +116,10 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
         int hd = e / half, j = e - hd * half;
         T* p = row + (int64_t)hd * d;
         float x1 = to_float(p[j]), x2 = to_float(p[j + half]);
+        if (bias) {
+            x1 += to_float(bias[hd * d + j]);
+            x2 += to_float(bias[hd * d + j + half]);
+        }
         float c = cs[j], sn = cs[half + j];
         T y1 = from_float<T>(x1 * c - x2 * sn), y2 = from_float<T>(x2 * c + x1 * sn);
         if (hd < n_q_heads) {
@@ -129,9 +134,11 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
     }
     if (have) {
         const T* vsrc = row + (int64_t)(n_q_heads + kv.n_kv) * d;
+        const T* vbias = bias ? bias + (int64_t)(n_q_heads + kv.n_kv) * d : nullptr;
         for (int e = threadIdx.x; e < kv.n_kv * d; e += 256) {
             int kh = e / d, j = e - kh * d;
-            vc[((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d + j] = vsrc[e];
+            vc[((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d + j] =
+                vbias ? from_float<T>(to_float(vsrc[e]) + to_float(vbias[e])) : vsrc[e];
         }
     }
 }
@@ -229,11 +236,12 @@ hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const
 }
 
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta) {
+                         float theta, const void* bias) {
     int M = rows.B * rows.n;
     if (M <= 0) return hipSuccess;
     size_t lds = sizeof(float) * kv.d;
-    DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta));
+    DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta,
+                                         (const T*)bias));
     return hipGetLastError();
 }
 

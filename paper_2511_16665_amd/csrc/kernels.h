@@ -46,8 +46,9 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 // out[r] = rmsnorm(x[row_map ? row_map[r] : r]) * gamma, stored in dtype.  Rows with row_map < 0 give zeros.
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map);
+// (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation)
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta);
+                         float theta, const void* bias);
 hipError_t swiglu(hipStream_t s, int dtype, int64_t count, const void* g, const void* u, void* out);
 // Rows [B][n]: xin[r] = [embed[tok[r]] ; hidden[src row]] in dtype (2h wide).  The hidden row is
 // b*src_seq_stride + src[r] when src_seq_stride > 0, else src[r].  Rows with tok < 0, src < 0,

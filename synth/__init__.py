@@ -10,6 +10,7 @@ from .inputs import (  # noqa: F401
     MID,
     QWEN7B,
     QWEN32B,
+    LLAMA70B,
     make_decoder_weights,
     make_drafter_weights,
     lognormal_contexts,

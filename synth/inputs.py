@@ -58,6 +58,7 @@ TINY = ModelCfg("tiny", 2, 256, 4, 2, 64, 768, 1024)
 MID = ModelCfg("mid", 3, 512, 8, 2, 128, 1280, 4096)
 QWEN7B = ModelCfg("qwen2.5-7b-shape", 28, 3584, 28, 4, 128, 18944, 152064)
 QWEN32B = ModelCfg("qwen2.5-32b-shape", 64, 5120, 40, 8, 128, 27648, 152064)
+LLAMA70B = ModelCfg("llama-3.3-70b-shape", 80, 8192, 64, 8, 128, 28672, 128256)
 
 
 def _gen(device, seed: int) -> torch.Generator:

@@ -12,10 +12,10 @@ def dtype_code(name):
     return tlt.TLT_F32 if name == "fp32" else tlt.TLT_BF16
 
 
-def make_models(cfg, seed, dtype_name, std=0.02):
+def make_models(cfg, seed, dtype_name, std=0.02, qkv_bias=False):
     """Weights drawn on the CPU in the storage dtype; returns (device dicts, float64 oracle dicts)."""
     dt = torch.float32 if dtype_name == "fp32" else torch.bfloat16
-    tw = make_decoder_weights(cfg, seed, device="cpu", dtype=dt, std=std)
+    tw = make_decoder_weights(cfg, seed, device="cpu", dtype=dt, std=std, qkv_bias=qkv_bias)
     dw = make_drafter_weights(cfg, seed, device="cpu", dtype=dt, std=std)
     to_dev = lambda w: {k: ([{kk: vv.cuda() for kk, vv in l.items()} for l in v] if isinstance(v, list)
                             else ({kk: vv.cuda() for kk, vv in v.items()} if isinstance(v, dict) else v.cuda()))

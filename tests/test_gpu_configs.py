@@ -6,7 +6,10 @@ against the oracle:
   24k-32k context, trees of 64 nodes with depth <= 8 and at most 10 children per node
   (448 query rows per kv head: two row groups of three row tiles per wave, 6-7 work items per sequence);
 * 32B block shape (40 query / 8 kv heads, 5 per kv head, hidden 5120, MLP 27648), 16 sequences with
-  lognormal contexts (median 8k, cap 32k), trees of 32 nodes (160 rows per kv head: two row tiles per wave).
+  lognormal contexts (median 8k, cap 32k), trees of 32 nodes (160 rows per kv head: two row tiles per wave);
+* 70B block shape of the paper's largest target (64 query / 8 kv heads, 8 per kv head, hidden 8192,
+  MLP 28672), with a bias on the q/k/v projections switched on to cover that path at width, 8
+  sequences, trees of 32 nodes (256 rows per kv head).
 """
 import dataclasses
 
@@ -18,7 +21,7 @@ from oracle import decoder as dec
 from oracle import sd
 from paper_2511_16665_amd import binding as tlt
 from paper_2511_16665_amd import engine as eng
-from synth import (QWEN7B, QWEN32B, fill_kv_pool, lognormal_contexts, make_decoder_weights, random_block_table)
+from synth import (LLAMA70B, QWEN7B, QWEN32B, fill_kv_pool, lognormal_contexts, make_decoder_weights, random_block_table)
 
 from gpu_util import EmbedRows, LazyLayers, dense_cache, rel_err
 
@@ -41,12 +44,12 @@ def _bounded_tree(rng, n, vocab, max_depth, max_children):
     return sd.Tree(rng.integers(0, vocab, size=n), np.array(parent), np.array(depth), np.zeros(n))
 
 
-def _run(cfg, ctx, n, max_depth, max_children, sample, seed):
+def _run(cfg, ctx, n, max_depth, max_children, sample, seed, qkv_bias=False, std=0.02):
     B = len(ctx)
     rng = np.random.default_rng(seed)
     table, n_pages = random_block_table(ctx + n + 16, cfg.page_size, seed=seed, extra_pages=8)
     dt = torch.bfloat16
-    tw = make_decoder_weights(cfg, 77, device="cuda", dtype=dt)
+    tw = make_decoder_weights(cfg, 77, device="cuda", dtype=dt, qkv_bias=qkv_bias, std=std)
     k, v = fill_kv_pool(cfg.n_layers, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, seed + 1, "cuda", dt)
     k0, v0 = k.clone(), v.clone()
     kv = eng.alloc_kv(cfg, tlt.TLT_BF16, cfg.n_layers, table, n_pages, ctx, fill=(k, v))
@@ -95,3 +98,13 @@ def test_32b_block_shape_lognormal_contexts_tree_32():
     ctx = lognormal_contexts(16, 8192, 0.8, 32768, 256, seed=3)
     order = np.argsort(ctx)
     _run(cfg, ctx, 32, 6, 8, sample=[int(order[0]), int(order[len(order) // 2])], seed=13)
+
+
+def test_70b_block_shape_with_qkv_bias_tree_32():
+    cfg = dataclasses.replace(LLAMA70B, name="70b-blocks-x2", n_layers=2, vocab=4096)
+    ctx = lognormal_contexts(8, 4096, 0.8, 16384, 256, seed=5)
+    order = np.argsort(ctx)
+    # weights N(0, 0.013^2): the 7B shape's 0.02 scaled by sqrt(3584 / 8192), so that queries and keys
+    # (and with them the sharpness of the attention, which sets how much a bf16 rounding of q or k
+    # moves the output) have the size they have there
+    _run(cfg, ctx, 32, 6, 8, sample=[int(order[0]), int(order[len(order) // 2])], seed=17, qkv_bias=True, std=0.013)

@@ -27,6 +27,8 @@ def _random_tree(rng, n, vocab):
 
 @pytest.mark.parametrize("cfg,dtype,tol,n,ctxs,std,impl", [
     (TINY, "fp32", 1e-4, 13, [0, 37, 150], 0.02, -1),
+    (TINY, "fp32", 1e-4, 13, [0, 37, 150], 0.02, -2),     # with a bias on the q/k/v projections (impl -2 = automatic + bias)
+    (MID7, "bf16", 2e-2, 48, [700, 90], 0.02, -2),
     (TINY, "fp32", 1e-4, 64, [1, 200], 0.1, -1),
     (TINY, "fp32", 1e-4, 1, [5, 64], 0.02, -1),           # N = 1: plain decode
     (MID, "bf16", 2e-2, 13, [0, 37, 150], 0.02, 0),       # wave-per-row attention in bf16
@@ -40,7 +42,10 @@ def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std, impl):
     rng = np.random.default_rng(n)
     B = len(ctxs)
     ctxs = np.array(ctxs, dtype=np.int32)
-    tw_dev, dw_dev, tw, dw = make_models(cfg, 3, dtype, std=std)
+    qkv_bias = impl == -2
+    impl = max(impl, -1)
+    tw_dev, dw_dev, tw, dw = make_models(cfg, 3, dtype, std=std, qkv_bias=qkv_bias)
+    assert ("bqkv" in tw["layers"][0]) == qkv_bias
     cap = int(ctxs.max()) + n + 16
     e, table, _ = make_engine(cfg, dtype, tw_dev, dw_dev, B, n, 4, 2, cap, seed=5, seq_len=ctxs)
     dt = tlt.torch_dtype(e.ctx.dtype_code)
