@@ -216,6 +216,48 @@ class Engine:
             self.have_pending = False
         return al, out
 
+    # -- switching speculative decoding on in the middle of a rollout
+    def activate_drafter(self, tokens: np.ndarray, lens: np.ndarray, chunk=None):
+        """Builds the learned drafter's cache for sequences that were decoded without it (Section 5.1:
+        SD is switched on once the running batch has shrunk).  tokens [B, >= max(lens)+1] int32 holds
+        each sequence's committed tokens 0 .. lens[b]-1 followed by its pending root at lens[b]; lens
+        must equal the target cache's lengths.  A drafter entry needs the target's hidden state of its
+        position, which is not kept, so the target is run again over the context, `chunk` positions
+        at a time (chain trees at a rewound length; the rows it rewrites in the target cache are the
+        ones already there, recomputed), each chunk followed by the drafter's extend.  Sequences
+        shorter than the longest simply run out of valid rows."""
+        B = self.B
+        m = chunk or self.max_n
+        lens = np.ascontiguousarray(lens, dtype=np.int32)
+        assert tokens.shape[0] == B and tokens.shape[1] >= int(lens.max()) + 1
+        np.testing.assert_array_equal(self.kv.seq_len.cpu().numpy(), lens)
+        full_bound = self.kv.seq_len_bound
+        t = self.tree(m)
+        t.parent.copy_(torch.arange(-1, m - 1, dtype=torch.int32, device="cuda").expand(B, m))
+        hid = self._buf("hid", m)
+        src = torch.arange(m, dtype=torch.int32, device="cuda").expand(B, m).contiguous()
+        padded = np.zeros((B, int(lens.max()) + m + 1), dtype=np.int32)
+        padded[:, : tokens.shape[1]] = tokens[:, : padded.shape[1]]
+        for o in range(0, int(lens.max()), m):
+            start = np.minimum(o, lens).astype(np.int32)                 # rewound length of each sequence
+            n_new = np.clip(lens - o, 0, m).astype(np.int32)
+            rows = np.stack([padded[b, start[b]: start[b] + m] for b in range(B)])
+            nxt = np.stack([padded[b, start[b] + 1: start[b] + 1 + m] for b in range(B)])
+            t.token.copy_(torch.from_numpy(rows).cuda())
+            self.ctx.tree_finalize(B, t)
+            self.kv.seq_len.copy_(torch.from_numpy(start).cuda())
+            self.dkv.seq_len.copy_(torch.from_numpy(start).cuda())
+            self.kv.seq_len_bound = self.dkv.seq_len_bound = int(start.max())
+            self.ctx.verify_forward(B, t, self.kv, out_hidden=hid)
+            self.ctx.draft_expand(B, 0, 1, 1, torch.from_numpy(nxt).cuda(), src, torch.from_numpy(n_new).cuda(), hid, None,
+                                  self.dkv, None)
+        self.kv.seq_len.copy_(torch.from_numpy(lens).cuda())
+        self.dkv.seq_len.copy_(torch.from_numpy(lens).cuda())
+        self.kv.seq_len_bound = full_bound
+        self.dkv.seq_len_bound = int(lens.max())
+        self.root.copy_(torch.from_numpy(np.array([tokens[b, lens[b]] for b in range(B)], dtype=np.int32)).cuda())
+        self.have_pending = False
+
     # -- the same step replayed from captured HIP graphs
     def graph_pool(self, capacity_bound=None) -> "GraphPool":
         """Graph pool over this engine's buffers (see GraphPool)."""

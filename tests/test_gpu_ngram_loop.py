@@ -128,3 +128,76 @@ def test_switching_between_the_model_free_and_the_learned_drafter_keeps_the_draf
         gen = seqs[b][P:]
         assert gen == sd.ar_greedy(cfg, tw, [int(t) for t in pr[b]], len(gen))
     e.ctx.close()
+
+
+def test_activating_the_drafter_in_the_middle_of_a_rollout():
+    """Sequences of different lengths are decoded for a while without the learned drafter (its cache
+    empty), then it is switched on: after Engine.activate_drafter the trees it builds must be the
+    oracle's, whose drafter has seen every token from the start, and decoding stays plain greedy."""
+    import torch
+
+    from oracle import sd
+
+    cfg = TINY
+    B, depth, topk, n_nodes = 3, 4, 2, 8
+    tw_dev, dw_dev, tw, dw = make_models(cfg, 31, "fp32", std=0.08)
+    P = 20
+    pr = prompts(B, P, cfg.vocab, seed=12)
+    e, _, _ = make_engine(cfg, "fp32", tw_dev, dw_dev, B, 16, depth, topk, P + 200, seed=3)
+    e.prefill(pr)
+    # no drafter so far: forget what prefill put into its cache
+    e.dkv.k_pool.zero_()
+    e.dkv.v_pool.zero_()
+    e.dkv.seq_len.zero_()
+    e.dkv.seq_len_bound = 0
+    seqs = [[int(t) for t in pr[b]] for b in range(B)]
+    ref = [sd.ar_greedy(cfg, tw, seqs[b], 40) for b in range(B)]
+    rng = np.random.default_rng(1)
+    for step in range(9):     # decoding with guessed chains: sequence 0 is guessed right twice per step,
+        tok = np.zeros((B, 3), np.int32)   # sequence 1 once, sequence 2 never, so the lengths drift apart
+        par = np.tile(np.array([-1, 0, 1], np.int32), (B, 1))
+        for b in range(B):
+            done = len(seqs[b]) - P
+            guess = [ref[b][done + j] if j < 2 - b else int(rng.integers(cfg.vocab)) for j in range(2)]
+            tok[b] = [seqs[b][-1]] + guess
+        al, out = e.step_trees(tok, par)
+        for b in range(B):
+            seqs[b] += [int(x) for x in out[b, : al[b] + 1]]
+    lens = np.array([len(s) - 1 for s in seqs], dtype=np.int32)
+    assert len(set(lens)) == B          # ragged: the 5-position chunks end at different places
+    width = int(lens.max()) + 1
+    tokens = np.zeros((B, width), np.int32)
+    for b in range(B):
+        tokens[b, : len(seqs[b])] = seqs[b]
+    print("activating the drafter at lengths", lens, flush=True)
+    e.activate_drafter(tokens, lens, chunk=5)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(e.dkv.seq_len.cpu().numpy(), lens)
+    np.testing.assert_array_equal(e.kv.seq_len.cpu().numpy(), lens)
+    # oracle: the same sequences with the drafter following from the start
+    states, roots = [], []
+    for b in range(B):
+        st = sd.SeqState(cfg, P + 200)
+        roots.append(sd.prefill(cfg, tw, dw, st, seqs[b], chunk=7))
+        states.append(st)
+    same = 0
+    for step in range(3):
+        al, out = e.step(topk, depth, n_nodes)
+        g_tree = e.tree(n_nodes)
+        g_tok, g_par = g_tree.token.cpu().numpy(), g_tree.parent.cpu().numpy()
+        for b in range(B):
+            o_out, o_a, o_tree, *_ = sd.sd_step(cfg, tw, dw, states[b], roots[b], topk, depth, n_nodes)
+            if np.array_equal(o_tree.token, g_tok[b]) and np.array_equal(o_tree.parent, g_par[b]):
+                same += 1
+            else:
+                sc = np.sort(o_tree.score[1:])
+                assert np.min(np.diff(sc)) < 1e-4, (step, b, "tree differs from the oracle's after activation")
+            assert o_a == al[b] and o_out == [int(x) for x in out[b, : al[b] + 1]], (step, b)
+            roots[b] = o_out[-1]
+            seqs[b] += o_out
+    print("trees identical to the oracle's after activation:", same, "of", 3 * B, flush=True)
+    assert same >= 3 * B - 1
+    for b in range(B):
+        gen = seqs[b][P:]
+        assert gen == sd.ar_greedy(cfg, tw, [int(t) for t in pr[b]], len(gen))
+    e.ctx.close()
