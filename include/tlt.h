@@ -211,6 +211,13 @@ int tlt_kv_commit(tlt_ctx *ctx, void *stream, int B, tlt_kv *kv, const int32_t *
  * out_mode 0: C stored in dtype; 1: C stored as fp32; 2: fp32 C += product. */
 int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const void *A, const void *W, void *C);
 
+/* out[m] = argmax_n (A W^T)[m][n] (lowest n on ties) for bf16 DEVICE operands, without storing the
+ * product: what tlt_verify_forward runs as its LM head when only out_argmax is asked for.  ws: DEVICE
+ * scratch of at least M * (N/128) * 8 bytes.  TLT_ENOTIMPL when the shape is not covered (N % 256,
+ * K % 64, M <= 64, misaligned operands): callers then take tlt_gemm + their own argmax. */
+int tlt_gemm_argmax(void *stream, int M, int N, int K, const void *A, const void *W, void *ws, size_t ws_bytes,
+                    int32_t *out);
+
 /* Attention kernel choice for cross-checks: -1 automatic (default), 0 wave-per-row kernel,
  * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
 int tlt_set_attention_impl(tlt_ctx *ctx, int impl);

@@ -25,7 +25,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax",
 ]
 
 
@@ -93,6 +93,7 @@ def load() -> C.CDLL:
         [C.c_int] + [C.c_void_p] * 4
     lib.tlt_kv_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(KVC), C.c_void_p, C.c_void_p, C.c_int]
     lib.tlt_gemm.argtypes = [C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3
+    lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
@@ -388,3 +389,10 @@ def gemm(dtype_code, out_mode, A, W, Cout):
     rc = load().tlt_gemm(_stream(), dtype_code, out_mode, M, N, K, _ptr(A), _ptr(W), _ptr(Cout))
     if rc:
         raise TltError(rc, "tlt_gemm")
+
+
+def gemm_argmax(A, W, ws, out):
+    """out[m] = argmax_n (A W^T)[m, n] for bf16 device tensors A [M, K], W [N, K]; returns the library's code."""
+    M, K = A.shape
+    N = W.shape[0]
+    return load().tlt_gemm_argmax(_stream(), M, N, K, _ptr(A), _ptr(W), _ptr(ws), ws.numel() * ws.element_size(), _ptr(out))

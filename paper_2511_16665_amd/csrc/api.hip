@@ -346,8 +346,15 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
         float* logits = out_logits ? out_logits : (float*)(ws + p.logits);
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
                 rmsnorm(s, c.dtype, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
-        if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
-        if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
+        if (!out_logits && gemm_argmax_supported(c.dtype, M, V, h, ws + p.xn, ctx->target.lm_head)) {
+            // only the most likely tokens are wanted: the logits never leave the LM head's registers
+            // (block partials go where the logits would have gone: M * V/128 * 8 bytes of M * V * 4)
+            TLT_RUN(ctx, s, CLS_GEMM, 2.0 * M * V * h, ((double)M * h + (double)V * h) * e,
+                    gemm_argmax(s, M, V, h, ws + p.xn, ctx->target.lm_head, logits, out_argmax));
+        } else {
+            if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
+            if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
+        }
     }
     return TLT_OK;
 }
@@ -647,6 +654,14 @@ int tlt_kv_commit(tlt_ctx* ctx, void* stream, int B, tlt_kv* kv, const int32_t* 
             kv_commit(s, c.dtype, B, c.n_layers, kv->k_pool, kv->v_pool, kv->n_pages, kv->block_table, kv->seq_len,
                       kv->max_pages, c.page_size, c.n_kv_heads, c.head_dim, accept_len, path_idx, stride));
     return TLT_OK;
+}
+
+int tlt_gemm_argmax(void* stream, int M, int N, int K, const void* A, const void* W, void* ws, size_t ws_bytes,
+                    int32_t* out) {
+    if (M < 1 || N < 1 || K < 1 || !A || !W || !ws || !out) return TLT_EINVAL;
+    if (!gemm_argmax_supported(TLT_BF16, M, N, K, A, W)) return TLT_ENOTIMPL;
+    if (ws_bytes < gemm_argmax_workspace_bytes(M, N)) return TLT_ESHAPE;
+    return gemm_argmax((hipStream_t)stream, M, N, K, A, W, ws, out) == hipSuccess ? TLT_OK : TLT_EHIP;
 }
 
 int tlt_gemm(void* stream, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {

@@ -39,7 +39,7 @@ __device__ __forceinline__ void store_out(void* C, int64_t idx, float v) {
         ((float*)C)[idx] = v;
     else if (OUT == OUT_ADD_F32)
         ((float*)C)[idx] += v;
-    else
+    else if (OUT == OUT_ATOMIC_ADD_F32)
         unsafeAtomicAdd((float*)C + idx, v);   // split-K partial sums: hardware fp32 add at the L2
 }
 
@@ -87,7 +87,7 @@ template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU 
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
-                                                        int ksplit, int wg_per_xcd) {
+                                                        int ksplit, int wg_per_xcd, int32_t* __restrict__ C2) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -324,6 +324,61 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
             pa_ = sa; pb_ = sb; sa = na; sb = nb;
         }
         // the tile is complete: store it and clear the accumulators while the next tile's loads land
+        if constexpr (OUT == OUT_ROWMAX) {
+            // best (value, column) of each of this wave's WTM*32 rows over its WTN*32 columns: first over a
+            // lane's own WTN columns of the row, then across the 32 lanes that hold the row's other
+            // columns.  That second reduction is a reduce-scatter: every exchange halves the rows a lane
+            // still carries, so it costs 2*NV exchanges instead of 5*NV; a lane ends with rows
+            // k = lane32*NV/32 .. of the wave's NV = WTM*16 (row index k = i*16 + v within its half).
+            constexpr int NV = WTM * 16;
+            float bv[NV];
+            int bi[NV];
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float m = acc[i][0][v];
+                    int mi = ti.n0 + wn * (WTN * 32) + l32;
+#pragma unroll
+                    for (int jj = 1; jj < WTN; ++jj)
+                        if (acc[i][jj][v] > m) {   // strictly greater: the lower column wins a tie
+                            m = acc[i][jj][v];
+                            mi = ti.n0 + wn * (WTN * 32) + jj * 32 + l32;
+                        }
+                    bv[i * 16 + v] = m;
+                    bi[i * 16 + v] = mi;
+                }
+#pragma unroll
+            for (int H = NV / 2, mask = 16; mask >= 1; H >>= 1, mask >>= 1) {
+                const bool upper = (l32 & mask) != 0;   // this lane keeps the upper half of what it carries
+#pragma unroll
+                for (int k = 0; k < (H > 0 ? H : 1); ++k) {
+                    if (H > 0) {
+                        const float send_v = upper ? bv[k] : bv[k + H];
+                        const int send_i = upper ? bi[k] : bi[k + H];
+                        const float keep_v = upper ? bv[k + H] : bv[k];
+                        const int keep_i = upper ? bi[k + H] : bi[k];
+                        const float ov = __shfl_xor(send_v, mask, 64);
+                        const int oi = __shfl_xor(send_i, mask, 64);
+                        const bool take = ov > keep_v || (ov == keep_v && oi < keep_i);
+                        bv[k] = take ? ov : keep_v;
+                        bi[k] = take ? oi : keep_i;
+                    }
+                }
+            }
+            constexpr int PER = NV / 32;   // rows a lane ends with
+            const int P = N;               // partial blocks per row of the whole product
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int k = l32 * PER + e, i = k >> 4, v = k & 15;
+                const int row = ti.m0 + wm * (WTM * 32) + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                if (row < M) {
+                    const int64_t o = (int64_t)row * P + ti.n0 / (WTN * 32) + wn;
+                    ((float*)C)[o] = bv[e];
+                    C2[o] = bi[e];
+                }
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < WTM; ++i) {
 #pragma unroll
@@ -346,6 +401,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                     }
                 }
             }
+        }
         }
 #pragma unroll
         for (int i = 0; i < WTM; ++i)
@@ -441,7 +497,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             attr_set = true;                                                                                          \
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
-                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd);                                           \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr);                                           \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
@@ -530,6 +586,64 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
         return launch_tiled(s, out_mode, M, N, K, A, W, nullptr, C, false);
     }
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
+}
+
+// ---- fused row argmax (big tiles only: every 256-row weight tile yields two 128-column blocks)
+__global__ __launch_bounds__(256) void argmax_blocks_k(int M, int P, const float* __restrict__ pv,
+                                                       const int32_t* __restrict__ pi, int32_t* __restrict__ out) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= M) return;
+    float v = -INFINITY;
+    int i = 0x7fffffff;
+    for (int p = lane; p < P; p += 64) {
+        const float ov = pv[(int64_t)row * P + p];
+        const int oi = pi[(int64_t)row * P + p];
+        if (ov > v || (ov == v && oi < i)) {
+            v = ov;
+            i = oi;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, 64);
+        const int oi = __shfl_xor(i, o, 64);
+        if (ov > v || (ov == v && oi < i)) {
+            v = ov;
+            i = oi;
+        }
+    }
+    if (lane == 0) out[row] = i;
+}
+
+bool gemm_argmax_supported(int dtype, int M, int N, int K, const void* A, const void* W) {
+    const bool aligned = (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
+    return dtype == BF16 && M > 64 && aligned && K % kBK == 0 && K / kBK >= 3 && N % 256 == 0 &&
+           (int64_t)258 * K * 2 < ((int64_t)1 << 31);
+}
+
+size_t gemm_argmax_workspace_bytes(int M, int N) { return (size_t)M * (N / 128) * 8; }
+
+hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const void* W, void* ws, int32_t* out) {
+    constexpr int SA = 3, SB = 2;
+    const int P = N / 128;
+    float* pv = (float*)ws;
+    int32_t* pi = (int32_t*)(pv + (size_t)M * P);
+    const int nbm = (M + 255) / 256, nbn = N / 256, total = nbm * nbn, per_xcd = (total + 7) / 8;
+    const size_t lds = ((size_t)SA * 256 + (size_t)SB * 256) * 64 * sizeof(uint16_t);
+    const int wg_per_xcd = per_xcd < 32 ? per_xcd : 32;
+    auto kern = gemm_bf16_pipe_k<2, 2, 4, 4, SA, SB, OUT_ROWMAX, false>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(wg_per_xcd * 8), dim3(256), lds, s, M, P, K, (const uint16_t*)A, (const uint16_t*)W,
+                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(argmax_blocks_k, dim3((M + 3) / 4), dim3(256), 0, s, M, P, pv, pi, out);
+    return hipGetLastError();
 }
 
 bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu) {

@@ -7,7 +7,13 @@
 namespace tlt {
 
 enum { F32 = 0, BF16 = 1 };
-enum { OUT_T = 0, OUT_F32 = 1, OUT_ADD_F32 = 2, OUT_ATOMIC_ADD_F32 = 3 /* internal: split-K partial sums */ };
+enum {
+    OUT_T = 0,
+    OUT_F32 = 1,
+    OUT_ADD_F32 = 2,
+    OUT_ATOMIC_ADD_F32 = 3, /* internal: split-K partial sums */
+    OUT_ROWMAX = 4          /* internal: per-row (max, argmax) of every 128-column block instead of C */
+};
 
 // Rows of a layer forward, laid out [B][n].  Row (b, i) is active when i < n_valid[b] (all rows
 // when n_valid is null).  Its rotary position is seq_len[b] + pos_base + (pos_off ? pos_off[b*n+i]
@@ -40,6 +46,14 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
 // fused gate/up projection of the SwiGLU MLP (bf16 MFMA path only): act = silu(A Wg^T) * (A Wu^T)
 bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu);
 hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act);
+
+// argmax over each row of A W^T without writing the product (the LM head when only the most likely
+// token is wanted): the GEMM's epilogue leaves the best (value, column) of every 128-column block,
+// a second kernel picks the best block; lowest column on ties, as row_argmax on the stored product.
+// Call only when gemm_argmax_supported(); ws holds gemm_argmax_workspace_bytes(M, N) bytes.
+bool gemm_argmax_supported(int dtype, int M, int N, int K, const void* A, const void* W);
+size_t gemm_argmax_workspace_bytes(int M, int N);
+hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const void* W, void* ws, int32_t* out);
 
 // ---- elementwise.hip
 hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x);

@@ -65,3 +65,50 @@ def test_gemm_bf16_7b_layer_shape_sampled_rows():
     want = A[rows].double().numpy() @ W.double().numpy().T
     got = out[rows].double().cpu().numpy()
     assert np.abs(got - want).max() <= 2e-3 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("M,N,K,ties", [(1536, 8192, 256, False), (300, 1024, 192, False), (1000, 4096, 320, True),
+                                        (129, 512, 3584, False), (1536, 152064, 256, False)])
+def test_fused_row_argmax_equals_argmax_of_the_stored_product(M, N, K, ties):
+    """tlt_gemm_argmax (the LM head when only the most likely token is wanted) against the argmax of
+    the product the plain kernel stores: same accumulation, so the result must be identical, ragged M
+    tail and exact ties (small-integer operands: many equal maxima, lowest column must win) included.
+    The product itself is checked against float64 on sampled rows: the oracle's argmax wherever its
+    top-two gap is above the bf16 bar."""
+    g = torch.Generator().manual_seed(M + N)
+    if ties:
+        A = torch.randint(-2, 3, (M, K), generator=g).float().bfloat16()
+        W = torch.randint(-1, 2, (N, K), generator=g).float().bfloat16()
+    else:
+        A = torch.randn((M, K), generator=g).bfloat16()
+        W = (torch.randn((N, K), generator=g) * 0.02).bfloat16()
+    Ad, Wd = A.cuda(), W.cuda()
+    C = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    tlt.gemm(tlt.TLT_BF16, 1, Ad, Wd, C)
+    ws = torch.zeros((M * (N // 128) * 2,), dtype=torch.float32, device="cuda")
+    out = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+    print(f"fused argmax M={M} N={N} K={K}", flush=True)
+    assert tlt.gemm_argmax(Ad, Wd, ws, out) == 0
+    torch.cuda.synchronize()
+    Cn = C.cpu().numpy()
+    np.testing.assert_array_equal(out.cpu().numpy(), Cn.argmax(axis=1))     # numpy: first maximum = lowest column
+    rows = [0, 1, M // 2, M - 1]
+    want = A[rows].double().numpy() @ W.double().numpy().T
+    for r, w in zip(rows, want):
+        srt = np.sort(w)
+        if ties:
+            assert Cn[r].argmax() == w.argmax()                                # small integers: the product is exact
+        elif srt[-1] - srt[-2] > 2 * 2e-2 * np.abs(w).max():
+            assert out[r].item() == w.argmax()
+
+
+def test_fused_row_argmax_refuses_shapes_it_does_not_cover():
+    A = torch.zeros((32, 256), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((512, 256), dtype=torch.bfloat16, device="cuda")
+    ws = torch.zeros((4096,), dtype=torch.float32, device="cuda")
+    out = torch.zeros((32,), dtype=torch.int32, device="cuda")
+    assert tlt.gemm_argmax(A, W, ws, out) == -5                                # M <= 64
+    A = torch.zeros((128, 256), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((128,), dtype=torch.int32, device="cuda")
+    assert tlt.gemm_argmax(A, W[:384], ws, out) == -5                          # N % 256
+    assert tlt.gemm_argmax(A, W, ws[:16], out) == -2                           # scratch too small
