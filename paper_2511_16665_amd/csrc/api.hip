@@ -23,7 +23,7 @@ struct ProfRec {
 };
 
 struct Plan {  // byte offsets into the workspace
-    size_t x, xn, qkv, att, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
+    size_t x, xn, qkv, att, oproj, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
         pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, total;
     size_t attn_ws_bytes;
     int max_rows, pool_cap, feat_rows;
@@ -53,6 +53,7 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.xn = take(R * 2 * h * esz);
     p.qkv = take(R * qkv_dim * esz);
     p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
+    p.oproj = take(R * h * esz);
     p.g = take(R * F * esz);
     p.u = take(R * F * esz);
     p.act = take(R * F * esz);
@@ -205,8 +206,12 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
                 attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl,
                           reuse_attn_plan));
     }
-    if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
+    // the output projection's product goes to a buffer of its own (in the model dtype) and joins the
+    // residual stream inside the norm kernel that follows: a plain store in the GEMM's epilogue instead of
+    // a read-modify-write of the fp32 stream by every tile
+    if ((rc = run_gemm(ctx, s, OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + 2 * e),
+            rmsnorm_add(s, dt, M, h, x, ws + p.oproj, w.mlp_norm, c.rms_eps, ws + p.xn));
     if (gemm_glu_supported(dt, M, F, h, ws + p.xn, w.wg, w.wu)) {
         TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 4.0 * M * F * h,
                 ((double)M * h + 2.0 * F * h + (double)M * F) * e, gemm_glu(s, M, F, h, ws + p.xn, w.wg, w.wu, ws + p.act));

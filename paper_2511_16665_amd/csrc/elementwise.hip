@@ -16,9 +16,12 @@ __global__ void embed_rows_k(int M, int h, int V, const int32_t* __restrict__ to
     for (int c = threadIdx.x; c < h; c += blockDim.x) x[(int64_t)r * h + c] = ok ? to_float(e[c]) : 0.f;
 }
 
+// `add` (optional, [rows][h] in T, no row_map then): the residual stream takes x[r] += add[r] first --
+// the output projection leaves its product there instead of read-modify-writing x itself.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_k(int h, const float* __restrict__ x, const T* __restrict__ gamma,
-                                                 float eps, T* __restrict__ out, const int32_t* __restrict__ row_map) {
+__global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
+                                                 float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
+                                                 const T* __restrict__ add) {
     __shared__ float red[4];
     int r = blockIdx.x;
     int64_t src = row_map ? row_map[r] : r;
@@ -27,10 +30,14 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, const float* __restrict_
         for (int c = threadIdx.x; c < h; c += 256) o[c] = from_float<T>(0.f);
         return;
     }
-    const float* xr = x + src * h;
+    float* xr = x + src * h;
     float ss = 0.f;
     for (int c = threadIdx.x; c < h; c += 256) {
         float v = xr[c];
+        if (add) {   // (each element is read, updated and later re-read by the same thread)
+            v += to_float(add[src * h + c]);
+            xr[c] = v;
+        }
         ss += v * v;
     }
     ss = wave_sum(ss);
@@ -44,8 +51,9 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, const float* __restrict_
 // Same, for h % 4 == 0 and h <= 4096: the row is read once with 16-byte loads and stays in registers
 // between the reduction and the scaling.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, const float* __restrict__ x, const T* __restrict__ gamma,
-                                                     float eps, T* __restrict__ out, const int32_t* __restrict__ row_map) {
+__global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
+                                                     float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
+                                                     const T* __restrict__ add) {
     __shared__ float red[4];
     const int r = blockIdx.x, h4 = h >> 2;
     const int64_t src = row_map ? row_map[r] : r;
@@ -53,11 +61,25 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, const float* __restr
     float4 v[4];
     float ss = 0.f;
     if (src >= 0) {
-        const float4* xr = (const float4*)(x + src * h);
+        float4* xr = (float4*)(x + src * h);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = threadIdx.x + k * 256;
             v[k] = c < h4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (add && c < h4) {
+                const T* a = add + src * h + 4 * c;
+                if constexpr (sizeof(T) == 2) {
+                    const uint2 pk = *(const uint2*)a;
+                    v[k].x += __uint_as_float(pk.x << 16);
+                    v[k].y += __uint_as_float(pk.x & 0xffff0000u);
+                    v[k].z += __uint_as_float(pk.y << 16);
+                    v[k].w += __uint_as_float(pk.y & 0xffff0000u);
+                } else {
+                    const float4 av = *(const float4*)a;
+                    v[k].x += av.x; v[k].y += av.y; v[k].z += av.z; v[k].w += av.w;
+                }
+                xr[c] = v[k];
+            }
             ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
         }
     }
@@ -224,15 +246,27 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
     return hipGetLastError();
 }
 
-hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
-                   const int32_t* row_map) {
+static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* x, const void* gamma, float eps, void* out,
+                                 const int32_t* row_map, const void* add) {
     if (M <= 0) return hipSuccess;
-    if (h % 4 == 0 && h <= 4096 && ((uintptr_t)x & 15) == 0) {
-        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_vec_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+    if (h % 4 == 0 && h <= 4096 && (((uintptr_t)x | (uintptr_t)add) & 15) == 0) {
+        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_vec_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
+                                             row_map, (const T*)add));
     } else {
-        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map));
+        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
+                                             row_map, (const T*)add));
     }
     return hipGetLastError();
+}
+
+hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
+                   const int32_t* row_map) {
+    return rmsnorm_launch(s, dtype, M, h, const_cast<float*>(x), gamma, eps, out, row_map, nullptr);   // x is only read
+}
+
+hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
+                       void* out) {
+    return rmsnorm_launch(s, dtype, M, h, x, gamma, eps, out, nullptr, add);
 }
 
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,

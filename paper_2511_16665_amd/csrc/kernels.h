@@ -60,6 +60,9 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 // out[r] = rmsnorm(x[row_map ? row_map[r] : r]) * gamma, stored in dtype.  Rows with row_map < 0 give zeros.
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map);
+// x[r] += add[r] (add [M][h] in dtype), then out[r] = rmsnorm(x[r]) * gamma.
+hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
+                       void* out);
 // (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation)
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
                          float theta, const void* bias);
