@@ -104,6 +104,14 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
     }
 }
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+template <typename T>
+union Piece {   // 16 bytes of T
+    u32x4_t v;
+    T e[16 / sizeof(T)];
+    __device__ Piece() {}
+};
+
 // One workgroup per row.  Angles are formed in double (positions reach 32K, where an fp32 product
 // pos * inv_freq already carries ~1e-3 rad of rounding), once per (row, pair index), then reused by
 // every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.  An
@@ -133,34 +141,54 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
     bool have = locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, slot, pr);
     T* kc = (T*)kv.k;
     T* vc = (T*)kv.v;
-    const int n_rot = (n_q_heads + kv.n_kv) * half;
-    for (int e = threadIdx.x; e < n_rot; e += 256) {
-        int hd = e / half, j = e - hd * half;
+    // 16-byte pieces: VEC consecutive pair indices j of one head per thread, both halves of each pair
+    constexpr int VEC = 16 / sizeof(T);
+    const int cph = half / VEC;   // pieces per half head
+    const int n_piece = (n_q_heads + kv.n_kv) * cph;
+    for (int e = threadIdx.x; e < n_piece; e += 256) {
+        const int hd = e / cph, j0 = (e - hd * cph) * VEC;
         T* p = row + (int64_t)hd * d;
-        float x1 = to_float(p[j]), x2 = to_float(p[j + half]);
+        Piece<T> lo, hi, blo, bhi;
+        lo.v = *(const u32x4_t*)(p + j0);
+        hi.v = *(const u32x4_t*)(p + half + j0);
         if (bias) {
-            x1 += to_float(bias[hd * d + j]);
-            x2 += to_float(bias[hd * d + j + half]);
+            blo.v = *(const u32x4_t*)(bias + hd * d + j0);
+            bhi.v = *(const u32x4_t*)(bias + hd * d + half + j0);
         }
-        float c = cs[j], sn = cs[half + j];
-        T y1 = from_float<T>(x1 * c - x2 * sn), y2 = from_float<T>(x2 * c + x1 * sn);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            float x1 = to_float(lo.e[k]), x2 = to_float(hi.e[k]);
+            if (bias) {
+                x1 += to_float(blo.e[k]);
+                x2 += to_float(bhi.e[k]);
+            }
+            const float c = cs[j0 + k], sn = cs[half + j0 + k];
+            lo.e[k] = from_float<T>(x1 * c - x2 * sn);
+            hi.e[k] = from_float<T>(x2 * c + x1 * sn);
+        }
         if (hd < n_q_heads) {
-            p[j] = y1;
-            p[j + half] = y2;
+            *(u32x4_t*)(p + j0) = lo.v;
+            *(u32x4_t*)(p + half + j0) = hi.v;
         } else if (have) {
-            int kh = hd - n_q_heads;
-            int64_t o = ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d;
-            kc[o + j] = y1;
-            kc[o + j + half] = y2;
+            const int kh = hd - n_q_heads;
+            const int64_t o = ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d;
+            *(u32x4_t*)(kc + o + j0) = lo.v;
+            *(u32x4_t*)(kc + o + half + j0) = hi.v;
         }
     }
     if (have) {
         const T* vsrc = row + (int64_t)(n_q_heads + kv.n_kv) * d;
         const T* vbias = bias ? bias + (int64_t)(n_q_heads + kv.n_kv) * d : nullptr;
-        for (int e = threadIdx.x; e < kv.n_kv * d; e += 256) {
-            int kh = e / d, j = e - kh * d;
-            vc[((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d + j] =
-                vbias ? from_float<T>(to_float(vsrc[e]) + to_float(vbias[e])) : vsrc[e];
+        for (int e = threadIdx.x; e < kv.n_kv * d / VEC; e += 256) {
+            const int kh = e * VEC / d, j0 = e * VEC - kh * d;
+            Piece<T> x, bb;
+            x.v = *(const u32x4_t*)(vsrc + e * VEC);
+            if (vbias) {
+                bb.v = *(const u32x4_t*)(vbias + e * VEC);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) x.e[k] = from_float<T>(to_float(x.e[k]) + to_float(bb.e[k]));
+            }
+            *(u32x4_t*)(vc + ((pr.page * kv.n_kv + kh) * kv.page_size + pr.row) * d + j0) = x.v;
         }
     }
 }
@@ -273,6 +301,9 @@ hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLay
                          float theta, const void* bias) {
     int M = rows.B * rows.n;
     if (M <= 0) return hipSuccess;
+    // the kernel moves 16-byte pieces: rows of qkv and of the cache are multiples of 16 bytes by the
+    // configuration check, the bases must be aligned as well
+    if ((((uintptr_t)qkv | (uintptr_t)bias | (uintptr_t)kv.k | (uintptr_t)kv.v) & 15) != 0) return hipErrorInvalidValue;
     size_t lds = sizeof(float) * kv.d;
     DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta,
                                          (const T*)bias));
