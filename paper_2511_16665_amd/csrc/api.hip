@@ -209,9 +209,15 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     // the output projection's product goes to a buffer of its own (in the model dtype) and joins the
     // residual stream inside the norm kernel that follows: a plain store in the GEMM's epilogue instead of
     // a read-modify-write of the fp32 stream by every tile
-    if ((rc = run_gemm(ctx, s, OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + 2 * e),
-            rmsnorm_add(s, dt, M, h, x, ws + p.oproj, w.mlp_norm, c.rms_eps, ws + p.xn));
+    // (with few rows the GEMM instead accumulates into x directly: that lets it split K over the chip)
+    if (M > 256) {
+        if ((rc = run_gemm(ctx, s, OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + 2 * e),
+                rmsnorm_add(s, dt, M, h, x, ws + p.oproj, w.mlp_norm, c.rms_eps, ws + p.xn));
+    } else {
+        if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
+    }
     if (gemm_glu_supported(dt, M, F, h, ws + p.xn, w.wg, w.wu)) {
         TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 4.0 * M * F * h,
                 ((double)M * h + 2.0 * F * h + (double)M * F) * e, gemm_glu(s, M, F, h, ws + p.xn, w.wg, w.wu, ws + p.act));
@@ -364,6 +370,18 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
     return TLT_OK;
 }
 
+// x = fc([embedding ; hidden]) of the drafter (2h -> h).  With few rows the product has far fewer tiles
+// than the chip has CUs while K = 2h is long, so x is cleared and the GEMM accumulates into it, which
+// lets it split K over many workgroups; with many rows it is a plain store.
+static int draft_fc(tlt_ctx* ctx, hipStream_t s, int M, const void* xin, float* x) {
+    const int h = ctx->cfg.hidden;
+    if (ctx->cfg.dtype == TLT_BF16 && M <= 256 && h % 4 == 0) {
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 4, zero_f32(s, (int64_t)M * h, x));
+        return run_gemm(ctx, s, OUT_ADD_F32, M, h, 2 * h, xin, ctx->draft.fc, x);
+    }
+    return run_gemm(ctx, s, OUT_F32, M, h, 2 * h, xin, ctx->draft.fc, x);
+}
+
 // Drafter catch-up shared by both expansion modes: entries for the newly committed positions, the
 // last one's output as feature row 0, committed length advanced.
 static int draft_extend_rows(tlt_ctx* ctx, hipStream_t s, int B, const int32_t* new_tokens, const int32_t* new_src,
@@ -382,7 +400,7 @@ static int draft_extend_rows(tlt_ctx* ctx, hipStream_t s, int B, const int32_t* 
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
             draft_input(s, dt, B, new_stride, h, V, new_tokens, new_src, n_new, hidden_n, (int64_t)B * hidden_n, hidden,
                         ctx->target.embed, ws + p.xn));
-    if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+    if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
     Rows rows;
     rows.B = B;
     rows.n = new_stride;
@@ -464,7 +482,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
                 draft_input(s, dt, B, topk, h, V, st.fr_token, st.fr_src, nullptr, FR, (int64_t)B * FR, feat,
                             ctx->target.embed, ws + p.xn));
-        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+        if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
         Rows rows;
         rows.B = B;
         rows.n = topk;
@@ -584,7 +602,7 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
                 draft_input(s, dt, B, lv.R, h, V, fr_token, fr_src, nullptr, FR, (int64_t)B * FR, feat, ctx->target.embed,
                             ws + p.xn));
-        if ((rc = run_gemm(ctx, s, OUT_F32, M, h, 2 * h, ws + p.xn, ctx->draft.fc, x))) return rc;
+        if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
         Rows rows;
         rows.B = B;
         rows.n = lv.R;

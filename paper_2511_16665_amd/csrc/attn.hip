@@ -190,24 +190,27 @@ __global__ __launch_bounds__(256) void attn_plan_k(const int32_t* __restrict__ s
     AttnItem* items = (AttnItem*)(nch + B);
     const int tid = threadIdx.x;
     if (tid < 66) s_hist[tid] = 0;
+    constexpr int slots = 512;   // workgroups the chip holds at once: two per CU (LDS), 256 CUs
     if (tid == 0) {
         int64_t total = 0;
         for (int b = 0; b < B; ++b) total += (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
-        constexpr int slots = 512;   // workgroups the chip holds at once: two per CU (LDS), 256 CUs
         int64_t c = (total * heads + slots - 1) / slots;
-        int T = (int)(c < 8 ? 8 : (c > 64 ? 64 : c));
-        // the chunks of all sequences together should fit the chip at once: rounding every sequence up to
-        // whole chunks adds up to B of them, so grow T until they do.  (A few dozen workgroups left over
-        // for a second round cost 0.85 ms per step at the 7B benchmark shape.)
-        for (; T < 64; ++T) {
-            int64_t items = 0;
-            for (int b = 0; b < B; ++b) {
-                const int tiles = (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
-                items += (tiles + T - 1) / T;
-            }
-            if (items * heads <= slots) break;
-        }
-        s_T = T;
+        s_total = (int)(c < 8 ? 8 : (c > 64 ? 64 : c));   // (smallest chunk size worth trying)
+        s_T = 64;
+    }
+    __syncthreads();
+    // the chunks of all sequences together should fit the chip at once: rounding every sequence up to
+    // whole chunks adds up to B of them, so take the smallest chunk size for which they do (one candidate
+    // per thread).  A few dozen workgroups left over for a second round cost 0.85 ms per step at the 7B
+    // benchmark shape.
+    if (tid < 64 && s_total + tid < 64) {
+        const int T = s_total + tid;
+        int64_t items = 0;
+        for (int b = 0; b < B; ++b) items += ((max(seq_len[b], 0) + n_region + kKT - 1) / kKT + T - 1) / T;
+        if (items * heads <= slots) atomicMin(&s_T, T);
+    }
+    __syncthreads();
+    if (tid == 0) {
         int acc = 0;
         for (int b = 0; b < B; ++b) {
             const int tiles = (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;

@@ -229,6 +229,12 @@ __global__ void add_i32_k(int n, int32_t* dst, const int32_t* a, int add_const) 
     if (i < n) dst[i] += (a ? a[i] : 0) + add_const;
 }
 
+__global__ void zero_f32_k(int64_t count, float4* __restrict__ dst) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 __global__ void copy_f32_k(int64_t count, const float4* __restrict__ src, float4* __restrict__ dst) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -339,6 +345,15 @@ hipError_t copy_f32(hipStream_t s, int64_t count, const float* src, float* dst) 
     int blocks = (int)((c4 + 255) / 256);
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(copy_f32_k, dim3(blocks), dim3(256), 0, s, c4, (const float4*)src, (float4*)dst);
+    return hipGetLastError();
+}
+
+hipError_t zero_f32(hipStream_t s, int64_t count, float* dst) {
+    if (count <= 0) return hipSuccess;
+    int64_t c4 = count / 4;  // callers pass multiples of 4 floats
+    int blocks = (int)((c4 + 255) / 256);
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(zero_f32_k, dim3(blocks), dim3(256), 0, s, c4, (float4*)dst);
     return hipGetLastError();
 }
 

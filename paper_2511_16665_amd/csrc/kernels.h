@@ -75,6 +75,7 @@ hipError_t draft_input(hipStream_t s, int dtype, int B, int n, int h, int V, con
                        const void* embed, void* xin);
 hipError_t add_i32(hipStream_t s, int n, int32_t* dst, const int32_t* a, int add_const);
 hipError_t copy_f32(hipStream_t s, int64_t count, const float* src, float* dst);
+hipError_t zero_f32(hipStream_t s, int64_t count, float* dst);   // a kernel, not a memset: safe to capture in a graph
 hipError_t scatter_rows(hipStream_t s, int R, int n, int h, const float* src, float* dst, int dst_seq_stride, int dst_base);
 hipError_t gather_last_rows(hipStream_t s, int B, int n, int h, const int32_t* n_valid, const float* src, float* dst,
                             int dst_seq_stride);
