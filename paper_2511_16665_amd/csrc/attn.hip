@@ -259,7 +259,8 @@ template <int TPW>
 __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
                                                    float* __restrict__ part_o, float* __restrict__ part_ml,
                                                    const AttnWork* __restrict__ work, int heads, int n_q_heads,
-                                                   int row_tiles, int tiles_per_group, int r_pad, float scale_log2) {
+                                                   int row_tiles, int tiles_per_group, int r_pad, float scale_log2,
+                                                   float lazy_raw) {
     extern __shared__ __align__(16) uint16_t lds[];
     const int rank = blockIdx.x / heads, hy = blockIdx.x - rank * heads;
     if (rank >= work->n_items) return;  // uniform
@@ -505,12 +506,22 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             for (int st = 0; st < 4; ++st)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) tmax = fmaxf(tmax, sc[st][v]);
-            tmax = group_max4(tmax);
-            const float m_new = fmaxf(m_run[t], tmax);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2);
+            // Lazy running maximum: softmax is invariant to the reference value, which only has to keep
+            // exp2 in range.  As long as no score of this tile exceeds the reference in use by more than
+            // 2^8 in the exponent (P <= 256: harmless in bf16 and in the fp32 sums), it stays, and the
+            // rescaling of the accumulators (33 multiplies per row tile), the exp of the correction and the
+            // cross-lane maximum are all skipped; the decision is taken per wave.
+            if (__builtin_amdgcn_ballot_w64(tmax > m_run[t] + lazy_raw) != 0) {
+                tmax = group_max4(tmax);
+                const float m_new = fmaxf(m_run[t], tmax);
+                const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2);
+                m_run[t] = m_new;
+                acc_l[t] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
+            }
             // the clamp keeps exp2(x*c - mc) = 0 for masked scores (-1e30) while no key has been visible yet
-            const float mc = fmaxf(m_new, -1e29f) * scale_log2;
-            m_run[t] = m_new;
+            const float mc = fmaxf(m_run[t], -1e29f) * scale_log2;
             uint32_t pk[4][2];
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
@@ -523,11 +534,6 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                 }
                 pk[st][0] = pack_bf16x2(pv[0], pv[1]);
                 pk[st][1] = pack_bf16x2(pv[2], pv[3]);
-            }
-            if (alpha != 1.0f) {
-                acc_l[t] *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) acc[t][dt] *= alpha;
             }
             pb[t][0] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
             pb[t][1] = u32x4_t{pk[2][0], pk[2][1], pk[3][0], pk[3][1]};
@@ -627,7 +633,8 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     if (!reuse_plan)
         hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work);
     hipLaunchKernelGGL(kern, dim3(p.max_items * p.heads), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
-                       part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2);
+                       part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2,
+                       8.0f / scale_log2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int R = rows.n * (n_q_heads / kv.n_kv);
