@@ -390,7 +390,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                         for (int jj = 0; jj < WTN / 2; ++jj) {
                             int col = ti.n0 + wn * (WTN / 2 * 32) + jj * 32 + l32;
                             const float g = acc[i][jj][v], u = acc[i][jj + WTN / 2][v];
-                            store_out<OUT>(C, (int64_t)row * N + col, g / (1.0f + __expf(-g)) * u);
+                            // (hardware reciprocal, 1 ulp: the result is rounded to bf16 anyway, and an IEEE division
+                            // per element costs the tile epilogue several microseconds)
+                            store_out<OUT>(C, (int64_t)row * N + col, g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
                         }
                     } else {
 #pragma unroll
