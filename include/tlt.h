@@ -211,6 +211,11 @@ int tlt_kv_commit(tlt_ctx *ctx, void *stream, int B, tlt_kv *kv, const int32_t *
  * out_mode 0: C stored in dtype; 1: C stored as fp32; 2: fp32 C += product. */
 int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const void *A, const void *W, void *C);
 
+/* act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 DEVICE operands and result: the fused gate/up projection of
+ * the decoder block's MLP (the two products never reach memory).  TLT_ENOTIMPL when the shape is not
+ * covered (N % 128, K % 64, misaligned operands). */
+int tlt_gemm_glu(void *stream, int M, int N, int K, const void *A, const void *Wg, const void *Wu, void *act);
+
 /* out[m] = argmax_n (A W^T)[m][n] (lowest n on ties) for bf16 DEVICE operands, without storing the
  * product: what tlt_verify_forward runs as its LM head when only out_argmax is asked for.  ws: DEVICE
  * scratch of at least M * (N/128) * 8 bytes.  TLT_ENOTIMPL when the shape is not covered (N % 256,

@@ -25,7 +25,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu",
 ]
 
 
@@ -93,6 +93,7 @@ def load() -> C.CDLL:
         [C.c_int] + [C.c_void_p] * 4
     lib.tlt_kv_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(KVC), C.c_void_p, C.c_void_p, C.c_int]
     lib.tlt_gemm.argtypes = [C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3
+    lib.tlt_gemm_glu.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 4
     lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
@@ -396,3 +397,9 @@ def gemm_argmax(A, W, ws, out):
     M, K = A.shape
     N = W.shape[0]
     return load().tlt_gemm_argmax(_stream(), M, N, K, _ptr(A), _ptr(W), _ptr(ws), ws.numel() * ws.element_size(), _ptr(out))
+
+
+def gemm_glu(A, Wg, Wu, act):
+    """act = silu(A Wg^T) * (A Wu^T) for bf16 device tensors A [M, K], Wg/Wu [N, K], act [M, N]; returns the code."""
+    M, K = A.shape
+    return load().tlt_gemm_glu(_stream(), M, Wg.shape[0], K, _ptr(A), _ptr(Wg), _ptr(Wu), _ptr(act))

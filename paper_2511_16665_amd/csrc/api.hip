@@ -679,6 +679,12 @@ int tlt_kv_commit(tlt_ctx* ctx, void* stream, int B, tlt_kv* kv, const int32_t* 
     return TLT_OK;
 }
 
+int tlt_gemm_glu(void* stream, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
+    if (M < 1 || N < 1 || K < 1 || !A || !Wg || !Wu || !act) return TLT_EINVAL;
+    if (!gemm_glu_supported(TLT_BF16, M, N, K, A, Wg, Wu)) return TLT_ENOTIMPL;
+    return gemm_glu((hipStream_t)stream, M, N, K, A, Wg, Wu, act) == hipSuccess ? TLT_OK : TLT_EHIP;
+}
+
 int tlt_gemm_argmax(void* stream, int M, int N, int K, const void* A, const void* W, void* ws, size_t ws_bytes,
                     int32_t* out) {
     if (M < 1 || N < 1 || K < 1 || !A || !W || !ws || !out) return TLT_EINVAL;

@@ -112,3 +112,23 @@ def test_fused_row_argmax_refuses_shapes_it_does_not_cover():
     out = torch.zeros((128,), dtype=torch.int32, device="cuda")
     assert tlt.gemm_argmax(A, W[:384], ws, out) == -5                          # N % 256
     assert tlt.gemm_argmax(A, W, ws[:16], out) == -2                           # scratch too small
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1536, 18944, 256), (1000, 16512, 192), (129, 128, 640)])
+def test_fused_gate_up_projection_matches_float64(M, N, K):
+    """tlt_gemm_glu: silu(A Wg^T) * (A Wu^T) in one kernel (256-row weight tiles for the whole rounds of
+    the chip, 128-row tiles for the rest, ragged M tail), against float64 on sampled rows."""
+    g = torch.Generator().manual_seed(M + K)
+    A = torch.randn((M, K), generator=g).bfloat16()
+    Wg = (torch.randn((N, K), generator=g) * 0.1).bfloat16()
+    Wu = (torch.randn((N, K), generator=g) * 0.1).bfloat16()
+    act = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    print(f"fused gate/up M={M} N={N} K={K}", flush=True)
+    assert tlt.gemm_glu(A.cuda(), Wg.cuda(), Wu.cuda(), act) == 0
+    torch.cuda.synchronize()
+    rows = sorted({r for r in (0, 1, 127, 128, 255, 256, M // 2, M - 1) if r < M})
+    a = A[rows].double().numpy()
+    gate, up = a @ Wg.double().numpy().T, a @ Wu.double().numpy().T
+    want = gate / (1.0 + np.exp(-gate)) * up
+    got = act[rows].double().cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-2 * np.abs(want).max()
