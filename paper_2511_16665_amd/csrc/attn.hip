@@ -361,15 +361,18 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         for (int e = 0; e < 2; ++e) {
             const int blk = wave_u + 8 * e;                 // 4-key block of the tile
             const int key_t = blk * 4 + (lane >> 4);        // key slot inside the tile
-            const int lc = (lane & 15) ^ (key_t & 15);      // logical 16-byte chunk this lane fetches
+            // logical 16-byte chunk this lane fetches: K rows are swizzled by the key slot (the 16 keys of
+            // a QK^T fragment read then hit 16 distinct chunks), V rows by twice the key slot (a
+            // transposing V read takes two neighbouring chunks of each of 8 keys: they stay distinct)
+            const int lck = (lane & 15) ^ (key_t & 15), lcv = (lane & 15) ^ ((2 * key_t) & 15);
             int key = t0 + key_t;
             key = key < k_end ? key : k_end - 1;            // tail slots re-read the last key (masked later)
             const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
-            const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (key & 15)) * kD + lc * 8;
+            const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (key & 15)) * kD;
             if (pg >= 0) {
                 const uint32_t dst = lds_base + (uint32_t)(stage * kStageElems + blk * 512) * 2u;
-                dma_global_to_lds_16(kpool + off, dst);
-                dma_global_to_lds_16(vpool + off, dst + kKT * kD * 2u);
+                dma_global_to_lds_16(kpool + off + lck * 8, dst);
+                dma_global_to_lds_16(vpool + off + lcv * 8, dst + kKT * kD * 2u);
             }
         }
     };
@@ -411,7 +414,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                         const int dt = dq * 4 + d4;
                         const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
                         const int lcv = 2 * dt + ((l16 & 3) >> 1);
-                        const uint16_t* vp = vt + key_t * kD + ((lcv ^ (key_t & 15)) * 8) + (l16 & 1) * 4;
+                        const uint16_t* vp = vt + key_t * kD + ((lcv ^ ((2 * key_t) & 15)) * 8) + (l16 & 1) * 4;
                         vv[d4][sub] =
                             __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
                     }
