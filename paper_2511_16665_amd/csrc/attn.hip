@@ -310,9 +310,11 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 
     // ---- K/V tiles: a ring of kStages LDS stages, each [64 keys][128] for K then the same for V,
     // filled by direct global->LDS loads.  One DMA instruction moves 4 keys (1 KB): lane -> key
-    // lane/16 of the block, 16-byte slot lane%16, and it fetches logical chunk slot ^ (key & 15), so a
-    // row's chunks are XOR-swizzled by its key index and both the 16-byte K fragment reads of 16
-    // consecutive keys and the transposing V reads spread over the banks.
+    // lane/16 of the block, 16-byte slot lane%16, and it fetches logical chunk slot ^ swizzle(key), so a
+    // row's chunks are XOR-swizzled by its key index: by key & 15 for K (the 16-byte fragment reads of 16
+    // consecutive keys hit 16 distinct chunks) and by 2*key & 15 for V (a transposing read touches two
+    // neighbouring chunks of each of 8 keys; with key & 15 those collided pairwise: a third of the LDS
+    // cycles were bank conflicts).
     const uint16_t* kpool = (const uint16_t*)kv.k;
     const uint16_t* vpool = (const uint16_t*)kv.v;
     int32_t* page_ids = (int32_t*)(lds + kStages * kStageElems);
