@@ -170,11 +170,11 @@ static AttnPlan plan_attention(int B, int n, int G, int n_kv, int bound_total) {
     const int per_wave = (per_group + 7) / 8;
     p.tpw = per_wave <= 1 ? 1 : (per_wave <= 2 ? 2 : 3);
     p.heads = n_kv * p.row_groups;
-    // items <= sum_b ceil(tiles_b / T) <= total_tiles / T + B with T = clamp(ceil(total_tiles * heads / 512), 8, 64):
-    // the first term is at most 512 / heads unless T is capped at 64
+    // items <= sum_b ceil(tiles_b / T) <= total_tiles / T + B, and the planner picks T so that they fill
+    // whole rounds of 256 workgroups with T <= 64: items * heads <= 256 * ceil((total_tiles / 64 + B) * heads / 256)
     const int64_t tiles_bound = (int64_t)B * ((bound_total + kKT - 1) / kKT);
-    const int64_t a = (512 + p.heads - 1) / p.heads, c = (tiles_bound + 63) / 64;
-    p.max_items = B + (int)(a > c ? a : c);
+    const int64_t a = (256 + p.heads - 1) / p.heads, c = (tiles_bound + 63) / 64;
+    p.max_items = 2 * B + (int)(a + c);
     return p;
 }
 
@@ -190,24 +190,34 @@ __global__ __launch_bounds__(256) void attn_plan_k(const int32_t* __restrict__ s
     AttnItem* items = (AttnItem*)(nch + B);
     const int tid = threadIdx.x;
     if (tid < 66) s_hist[tid] = 0;
-    constexpr int slots = 512;   // workgroups the chip holds at once: two per CU (LDS), 256 CUs
-    if (tid == 0) {
-        int64_t total = 0;
-        for (int b = 0; b < B; ++b) total += (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
-        int64_t c = (total * heads + slots - 1) / slots;
-        s_total = (int)(c < 8 ? 8 : (c > 64 ? 64 : c));   // (smallest chunk size worth trying)
-        s_T = 64;
+    // A workgroup takes a whole CU (248 VGPRs per wave, 128 KB of LDS), so the work items run in rounds of
+    // 256.  Measured at the 7B benchmark shape (attention ms per step): one round of 256 items 4.02, two
+    // rounds 4.33, four 4.20, and 4.6-4.8 when the count falls between whole rounds (384, 768 items): the
+    // fewest whole rounds that the 64-tile cap on a chunk allows are the target.
+    __shared__ int s_count[65];   // items for every chunk size T = 8 .. 64 (one candidate per thread)
+    if (tid >= 8 && tid <= 64) {
+        int64_t items = 0;
+        for (int b = 0; b < B; ++b) items += ((max(seq_len[b], 0) + n_region + kKT - 1) / kKT + tid - 1) / tid;
+        s_count[tid] = (int)(items < 0x7fffffff / 64 ? items : 0x7fffffff / 64);
     }
     __syncthreads();
-    // the chunks of all sequences together should fit the chip at once: rounding every sequence up to
-    // whole chunks adds up to B of them, so take the smallest chunk size for which they do (one candidate
-    // per thread).  A few dozen workgroups left over for a second round cost 0.85 ms per step at the 7B
-    // benchmark shape.
-    if (tid < 64 && s_total + tid < 64) {
-        const int T = s_total + tid;
-        int64_t items = 0;
-        for (int b = 0; b < B; ++b) items += ((max(seq_len[b], 0) + n_region + kKT - 1) / kKT + T - 1) / T;
-        if (items * heads <= slots) atomicMin(&s_T, T);
+    if (tid == 0) {
+        // fewest rounds first; within a round count the smallest chunk size that fits (items closest to
+        // filling the rounds).  Ends at the latest when T = 64 fits, which some round count always allows.
+        int64_t total = 0;
+        for (int b = 0; b < B; ++b) total += (max(seq_len[b], 0) + n_region + kKT - 1) / kKT;
+        int64_t r = (total * heads + 256 * 64 - 1) / (256 * 64);
+        int T = 64;
+        for (r = r < 1 ? 1 : r;; ++r) {
+            bool found = false;
+            for (int t = 8; t <= 64 && !found; ++t)
+                if ((int64_t)s_count[t] * heads <= 256 * r) {
+                    T = t;
+                    found = true;
+                }
+            if (found) break;
+        }
+        s_T = T;
     }
     __syncthreads();
     if (tid == 0) {
