@@ -263,6 +263,10 @@ def main():
                                "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
                                "bytes_per_launch": round(attn_bytes_per_step / cfg.n_layers, 0),
+                               # at N*G = 336 query rows per cached key the kernel sits at the ridge: the same
+                               # launches against the MFMA roof (4*d*Hq*N flops per cached token and layer)
+                               "mfma_tflops": round(at["flops"] / (at["ms"] * 1e-3) / 1e12, 1) if at["ms"] > 0 else 0.0,
+                               "mfma_frac": round(at["flops"] / (at["ms"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4) if at["ms"] > 0 else 0.0,
                                "avg_launch_us": round(at["ms"] / max(at["launches"], 1) * 1e3, 2)},
         "per_class": per_class, "ms_per_step_profiled": round(ms_prof, 3), "setup_s": round(setup_s, 1),
     }

@@ -105,6 +105,29 @@ def test_sampling_accept_bit_exact(B, n, V, tau, k):
     ctx.close()
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+def test_sampling_accept_root_only_tree_is_a_plain_draw(mode):
+    """N = 1 (no speculation): both sampling rules reduce to one inverse-CDF draw from the target."""
+    B, n, V, tau = 5, 1, 1031, 0.8
+    cfg, ctx = _ctx(V, B, n)
+    logits = synthetic_logits((B, n, V), seed=3)
+    q = np.full((B, n, V), 1.0 / V, dtype=np.float32)
+    token = np.zeros((B, n), dtype=np.int32)
+    parent = np.full((B, n), -1, dtype=np.int32)
+    u_acc, u_fin = uniforms_u32((B, n), 1), uniforms_u32((B,), 2)
+    u_fin[0], u_fin[1] = 0, 2**32 - 1
+    if mode == 1:
+        want = oa.accept_sample(token, parent, logits, q, u_acc, u_fin, tau, 1)
+    else:
+        want = oa.accept_target_only(token, parent, logits, u_acc, u_fin, tau, 1)
+    got = _run_accept(ctx, B, n, 1, mode, _tree_dev(token, parent), logits=_dev(logits), draft_q=_dev(q),
+                      u_accept=_dev(u_acc), u_final=_dev(u_fin), temperature=tau)
+    for g, w in zip(got, want):
+        np.testing.assert_array_equal(g, w)
+    assert (got[0] == 0).all() and (got[3] == 1).all()
+    ctx.close()
+
+
 @pytest.mark.parametrize("B,n,V,tau,k", [(256, 4, 16, 1.0, 2), (16, 21, 1000, 0.9, 4), (4, 64, 152064, 0.9, 3), (8, 64, 97, 0.7, 63)])
 def test_target_only_sampling_accept_bit_exact(B, n, V, tau, k):
     """Deterministic top-k trees of a noisy copy of the target (the trees the target-only rule is

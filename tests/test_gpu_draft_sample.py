@@ -41,7 +41,9 @@ def _dev_u32(a):
 
 @pytest.mark.parametrize("cfg,dtype,K,D,N,tau,tol", [(MID7, "bf16", 10, 8, 64, 0.9, 2e-2), (MID7, "bf16", 8, 6, 48, 1.0, 2e-2),
                                                    (MID7, "bf16", 1, 4, 5, 0.9, 2e-2), (TINY, "fp32", 3, 4, 12, 0.9, 1e-4),
-                                                   (TINY, "fp32", 2, 2, 4, 0.5, 1e-4)])
+                                                   (TINY, "fp32", 2, 2, 4, 0.5, 1e-4),
+                                                   (TINY, "fp32", 4, 1, 5, 0.9, 1e-4),      # depth 1: a star, no drafter pass
+                                                   (TINY, "fp32", 3, 3, 1, 0.9, 1e-4)])     # one node: the root alone
 def test_draft_sample_matches_oracle(cfg, dtype, K, D, N, tau, tol):
     cfg = dataclasses.replace(cfg, n_layers=1)
     B = 3
@@ -50,7 +52,7 @@ def test_draft_sample_matches_oracle(cfg, dtype, K, D, N, tau, tol):
     hidden_n, stride = 5, 4
     tw_dev, dw_dev, tw, dw = make_models(cfg, 5, dtype, std=0.05)
     cap = int(ctxs.max()) + 160
-    e, _, dtable = make_engine(cfg, dtype, tw_dev, dw_dev, B, N, D, K, cap, seed=3, seq_len=ctxs)
+    e, _, dtable = make_engine(cfg, dtype, tw_dev, dw_dev, B, max(N, stride), D, K, cap, seed=3, seq_len=ctxs)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     dk, dv = fill_kv_pool(1, e.dkv.k_pool.shape[1], cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 6, dtype=tdt)
     e.dkv.k_pool.copy_(dk)
@@ -62,7 +64,8 @@ def test_draft_sample_matches_oracle(cfg, dtype, K, D, N, tau, tol):
     parent, rank, depth = osd.static_template(K, D, N)
     n = len(parent)
     u = _u32(rng, B, n)
-    u[0, 1:3] = [0, 2**32 - 1][: max(0, min(2, n - 1))]          # the extreme uniforms
+    if n > 1:
+        u[0, 1:3] = [0, 2**32 - 1][: min(2, n - 1)]              # the extreme uniforms
     tree = e.tree(n)
     q = torch.full((B, n, cfg.vocab), -1.0, dtype=torch.float32, device="cuda")
     dev = lambda a: torch.from_numpy(a).cuda()
