@@ -23,7 +23,7 @@ struct ProfRec {
 };
 
 struct Plan {  // byte offsets into the workspace
-    size_t x, xn, qkv, att, oproj, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
+    size_t x, xn, qkv, qkv32, att, oproj, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
         pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, total;
     size_t attn_ws_bytes;
     int max_rows, pool_cap, feat_rows;
@@ -52,6 +52,7 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.x = take(R * h * 4);
     p.xn = take(R * 2 * h * esz);
     p.qkv = take(R * qkv_dim * esz);
+    p.qkv32 = take(std::min<size_t>(R, 64) * qkv_dim * 4);   // fp32 q/k/v of a forward over few rows (split-K)
     p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
     p.oproj = take(R * h * esz);
     p.g = take(R * F * esz);
@@ -194,8 +195,20 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     float* x = (float*)(ws + p.x);
     int rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr));
-    if ((rc = run_gemm(ctx, s, OUT_T, M, qkv_dim, h, ws + p.xn, w.wqkv, ws + p.qkv))) return rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2, rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv));
+    if (dt == TLT_BF16 && M <= 64 && qkv_dim % 128 == 0) {
+        // a handful of rows: the projection has too few tiles for the chip unless it splits K, which needs
+        // an fp32 target to accumulate into; the rotary kernel reads that and leaves q in the model dtype.
+        // (From about a hundred rows on the partial sums' traffic eats the gain: measured equal at M = 256.)
+        float* q32 = (float*)(ws + p.qkv32);
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * 4, zero_f32(s, (int64_t)M * qkv_dim, q32));
+        if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, qkv_dim, h, ws + p.xn, w.wqkv, q32))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * (4 + e),
+                rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv, q32));
+    } else {
+        if ((rc = run_gemm(ctx, s, OUT_T, M, qkv_dim, h, ws + p.xn, w.wqkv, ws + p.qkv))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2,
+                rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv));
+    }
     {
         // algorithmic traffic: one pass over the cached K and V of every sequence (bounded by the
         // host-known length) plus q in / out; flops: 4 * d per (query row, head, key)

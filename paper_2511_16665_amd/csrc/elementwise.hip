@@ -118,7 +118,8 @@ union Piece {   // 16 bytes of T
 // optional projection bias is added first (to q, k and v).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T* __restrict__ qkv, int n_q_heads,
-                                                       float theta, const T* __restrict__ bias) {
+                                                       float theta, const T* __restrict__ bias,
+                                                       const float* __restrict__ src32) {
     extern __shared__ float cs[];  // [d/2] cos, [d/2] sin
     const int d = kv.d, half = d >> 1;
     int r = blockIdx.x;
@@ -137,6 +138,23 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
     __syncthreads();
     const int qkv_dim = (n_q_heads + 2 * kv.n_kv) * d;
     T* row = qkv + (int64_t)r * qkv_dim;
+    // src32 (optional): the projection's product still in fp32 (a split-K GEMM accumulated it there);
+    // q then goes to `qkv` in T for the attention kernel, exactly as when it is rotated in place
+    const float* row32 = src32 ? src32 + (int64_t)r * qkv_dim : nullptr;
+    auto load_piece = [&](int elem, Piece<T>& out) {   // VEC consecutive elements of the row, as T
+        if (row32) {
+#pragma unroll
+            for (int k = 0; k < 16 / (int)sizeof(T); k += 4) {
+                const float4 f = *(const float4*)(row32 + elem + k);
+                out.e[k] = from_float<T>(f.x);
+                out.e[k + 1] = from_float<T>(f.y);
+                out.e[k + 2] = from_float<T>(f.z);
+                out.e[k + 3] = from_float<T>(f.w);
+            }
+        } else {
+            out.v = *(const u32x4_t*)(row + elem);
+        }
+    };
     PageRef pr;
     bool have = locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, slot, pr);
     T* kc = (T*)kv.k;
@@ -149,8 +167,9 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
         const int hd = e / cph, j0 = (e - hd * cph) * VEC;
         T* p = row + (int64_t)hd * d;
         Piece<T> lo, hi, blo, bhi;
-        lo.v = *(const u32x4_t*)(p + j0);
-        hi.v = *(const u32x4_t*)(p + half + j0);
+        load_piece(hd * d + j0, lo);
+        hi.v = lo.v;   // (initialised for the compiler; overwritten)
+        load_piece(hd * d + half + j0, hi);
         if (bias) {
             blo.v = *(const u32x4_t*)(bias + hd * d + j0);
             bhi.v = *(const u32x4_t*)(bias + hd * d + half + j0);
@@ -177,12 +196,12 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
         }
     }
     if (have) {
-        const T* vsrc = row + (int64_t)(n_q_heads + kv.n_kv) * d;
+        const int v0 = (n_q_heads + kv.n_kv) * d;
         const T* vbias = bias ? bias + (int64_t)(n_q_heads + kv.n_kv) * d : nullptr;
         for (int e = threadIdx.x; e < kv.n_kv * d / VEC; e += 256) {
             const int kh = e * VEC / d, j0 = e * VEC - kh * d;
             Piece<T> x, bb;
-            x.v = *(const u32x4_t*)(vsrc + e * VEC);
+            load_piece(v0 + e * VEC, x);
             if (vbias) {
                 bb.v = *(const u32x4_t*)(vbias + e * VEC);
 #pragma unroll
@@ -304,15 +323,16 @@ hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const v
 }
 
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta, const void* bias) {
+                         float theta, const void* bias, const float* src32) {
     int M = rows.B * rows.n;
     if (M <= 0) return hipSuccess;
     // the kernel moves 16-byte pieces: rows of qkv and of the cache are multiples of 16 bytes by the
     // configuration check, the bases must be aligned as well
-    if ((((uintptr_t)qkv | (uintptr_t)bias | (uintptr_t)kv.k | (uintptr_t)kv.v) & 15) != 0) return hipErrorInvalidValue;
+    if ((((uintptr_t)qkv | (uintptr_t)bias | (uintptr_t)kv.k | (uintptr_t)kv.v | (uintptr_t)src32) & 15) != 0)
+        return hipErrorInvalidValue;
     size_t lds = sizeof(float) * kv.d;
     DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta,
-                                         (const T*)bias));
+                                         (const T*)bias, src32));
     return hipGetLastError();
 }
 

@@ -576,16 +576,22 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
         // too few 256x256 tiles for the chip but a long K and an accumulating fp32 output: split K
         // over several workgroups per tile, which add their partial sums with fp32 atomics (the
         // order of those additions, and so the last bit of the result, is not fixed)
-        // one row of tiles (M <= 256) accumulating into fp32: the weights stream from HBM, so what counts
-        // is how many workgroups pull on them and how little partial-sum traffic the split costs.
-        // 256x128 tiles halve both the tile count needed per split and the bytes of every partial tile.
-        if (out_mode == OUT_ADD_F32 && M > 64 && M <= 256 && N % 128 == 0 && N / 128 < 256) {
-            const int nk = K / kBK, tiles = N / 128;
-            int ks = 256 / tiles;
-            if (ks > nk / 8) ks = nk / 8;
-            // (what is left after this is the atomic traffic of the partial tiles, ks * M * N * 4 bytes at
-            // 1.5-2 TB/s: deeper weight rings, 128x128 tiles with twice the workgroups -- all measured the same)
-            if (ks >= 2) return launch_pipe<2, 2, 4, 2, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
+        // few rows accumulating into fp32 (M <= 256 is one row of tiles: the drafter's projections, a
+        // verification forward over a handful of tree nodes; up to a few hundred rows the picture is the
+        // same): the weights stream from HBM, so what counts is how many workgroups pull on them and how
+        // little partial-sum traffic the split costs.  256x128 tiles halve both the tile count needed per
+        // split and the bytes of every partial tile.
+        if (out_mode == OUT_ADD_F32 && N % 128 == 0) {
+            const int nk = K / kBK, tiles = ((M + 255) / 256) * (N / 128);
+            if (tiles < 200) {
+                int ks = 256 / tiles;
+                if (ks > nk / 8) ks = nk / 8;
+                // (what is left after this is the atomic traffic of the partial tiles, ks * M * N * 4 bytes at
+                // 1.5-2 TB/s: deeper weight rings, 128x128 tiles with twice the workgroups -- all measured the same)
+                // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
+                // the deeper ring keeps more of it in flight (31.7 against 39.5 us on the down projection at M = 32)
+                if (ks >= 2) return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
+            }
         }
         if (out_mode == OUT_ADD_F32 && N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
             const int nk = K / kBK;

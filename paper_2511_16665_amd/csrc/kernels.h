@@ -63,9 +63,10 @@ hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const
 // x[r] += add[r] (add [M][h] in dtype), then out[r] = rmsnorm(x[r]) * gamma.
 hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
                        void* out);
-// (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation)
+// (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation; src32: optional
+// fp32 copy of the projection to read instead of qkv, which then only receives the rotated q)
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta, const void* bias);
+                         float theta, const void* bias, const float* src32 = nullptr);
 hipError_t swiglu(hipStream_t s, int dtype, int64_t count, const void* g, const void* u, void* out);
 // Rows [B][n]: xin[r] = [embed[tok[r]] ; hidden[src row]] in dtype (2h wide).  The hidden row is
 // b*src_seq_stride + src[r] when src_seq_stride > 0, else src[r].  Rows with tok < 0, src < 0,
