@@ -195,6 +195,12 @@ def main():
     ap.add_argument("--verify", type=int, default=48)
     ap.add_argument("--ctx-median", type=int, default=4096)
     ap.add_argument("--ctx-cap", type=int, default=16384)
+    ap.add_argument("--ctx-lo", type=int, default=0,
+                    help="contexts uniform in [ctx-lo, ctx-cap] instead of lognormal (the long-tail phase's few long sequences)")
+    ap.add_argument("--mode", default="greedy", choices=["greedy", "sampled", "target-only"],
+                    help="greedy (the headline workload); sampled = static-template drafting + rejection-sampling "
+                         "acceptance; target-only = the drafter's top-k tree + target-only sampling acceptance")
+    ap.add_argument("--temperature", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", dest="sweep", action="store_false")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
@@ -209,13 +215,26 @@ def main():
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 
+    if args.mode != "greedy":
+        from paper_2511_16665_amd import binding as tlt
+        n_nodes = len(tlt.template_build(K, D, N)[0]) if args.mode == "sampled" else min(N, 1 + K + (D - 1) * K * K)
+        gen = torch.Generator(device="cuda").manual_seed(11)
+        u32 = lambda *shape: torch.randint(-2**31, 2**31 - 1, shape, generator=gen, device="cuda", dtype=torch.int32)
+
+    def one_step():
+        if args.mode == "greedy":
+            return e.step(K, D, N)
+        if args.mode == "sampled":
+            return e.step_sampled(K, D, N, args.temperature, u32(B, n_nodes), u32(B, n_nodes), u32(B))
+        return e.step(K, D, N, sample=(args.temperature, u32(B, n_nodes), u32(B)))
+
     for _ in range(args.warmup):
-        e.step(K, D, N)
+        one_step()
     torch.cuda.synchronize()
     emitted = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        al, _ = e.step(K, D, N)
+        al, _ = one_step()
         emitted += int(al.sum()) + B
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -225,7 +244,7 @@ def main():
     e.ctx.profile_begin(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e.step(K, D, N)
+        one_step()
     torch.cuda.synchronize()
     ms_prof = (time.perf_counter() - t0) / args.steps * 1e3
     prof = e.ctx.profile_read()
@@ -243,15 +262,21 @@ def main():
     per_class = {k: {"ms_per_step": round(v["ms"] / args.steps, 4), "launches_per_step": v["launches"] // args.steps}
                  for k, v in prof.items()}
 
-    default_workload = (args.model, B, D, K, N, args.ctx_median, args.ctx_cap) == ("7b", 32, 6, 8, 48, 4096, 16384)
+    default_workload = (args.model, B, D, K, N, args.ctx_median, args.ctx_cap, args.ctx_lo, args.mode) == \
+        ("7b", 32, 6, 8, 48, 4096, 16384, 0, "greedy")
+    ctx_desc = f"uniform in [{args.ctx_lo}, {args.ctx_cap}]" if args.ctx_lo else \
+        f"lognormal(median {args.ctx_median}, sigma 0.8, cap {args.ctx_cap})"
+    mode_desc = {"greedy": "greedy", "sampled": f"sampled on the static template at temperature {args.temperature} "
+                 "(rejection-sampling acceptance)", "target-only": f"top-k tree, target-only sampling acceptance at "
+                 f"temperature {args.temperature}"}[args.mode]
     result = {
         "metric": "accepted tokens/s per GPU in SD rollout step; verify latency vs tree size",
         "value": round(emitted / dt, 2), "unit": "accepted tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} random-init bf16, 1-layer drafter, batch {B}, contexts lognormal(median "
-                               f"{args.ctx_median}, sigma 0.8, cap {args.ctx_cap}) = {int(ctx.sum())} cached tokens, "
-                               f"16-token pages, tree depth {D} top-k {K} verify {N}, greedy",
+        "config": {"workload": f"{cfg.name} random-init bf16, 1-layer drafter, batch {B}, contexts {ctx_desc} = "
+                               f"{int(ctx.sum())} cached tokens, 16-token pages, tree depth {D} top-k {K} verify {N}, "
+                               f"{mode_desc}",
                    "accepted_per_step": round(emitted / args.steps, 2), "drafter": "random-init (accept length ~0)"},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_k (GEMMs of the verification forward; one launch here = one library GEMM = one or two kernel launches)",
                      "achieved": round(gemm_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -275,7 +300,7 @@ def main():
     }
     if args.sweep:
         result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.mode == "greedy":
         result["cpu_baseline"] = cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args)
     if args.pmc_copy_mib > 0:
         src = torch.ones(args.pmc_copy_mib << 18, dtype=torch.float32, device="cuda")
