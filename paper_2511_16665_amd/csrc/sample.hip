@@ -490,6 +490,7 @@ __device__ __forceinline__ unsigned long long q_weight(float q) {
 // elements per lane: 16-byte accesses when the row allows), so a wave's weight total is the total of
 // a contiguous range and the threshold search goes wave -> 256-element step -> lane -> element.
 constexpr int kDrawThreads = 1024, kDrawWaves = kDrawThreads / 64;
+constexpr int kDrawMaxSteps = 64;   // step totals kept per wave: covers vocabularies up to 16 * 64 * 256 = 262144
 
 template <bool VEC4>
 __device__ __forceinline__ void load4(const float* __restrict__ p, int idx, int V, float (&x)[4], float fill) {
@@ -513,6 +514,7 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
                                                                int32_t* __restrict__ token, float* __restrict__ q_out) {
     __shared__ float sf[kDrawWaves];
     __shared__ unsigned long long wsum[kDrawWaves];
+    __shared__ unsigned long long step_sum[kDrawWaves][kDrawMaxSteps];   // totals of each wave's 256-element steps
     __shared__ int pick_s;
     __shared__ int removed[16];   // a node has at most 16 children (the largest topK)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -536,30 +538,65 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
     }
     const float inv = 1.0f / block_sum_f<kDrawWaves>(part, sf);
 
-    // q, and each wave's integer weight total over its own range
+    // q, each wave's integer weight total over its own range, and the totals of its 256-element steps
     const int Vw = (V + kDrawWaves * 256 - 1) / (kDrawWaves * 256) * 256;
     const int w0 = wave * Vw, w1 = min(V, w0 + Vw);
+    const int n_steps = Vw / 256;
+    const bool fast = n_steps <= kDrawMaxSteps;   // (else the search walks a wave's range step by step)
     unsigned long long acc = 0;
-    for (int i = w0 + lane * 4; i < w1; i += 256) {
+    for (int i0 = w0, k = 0; i0 < w1; i0 += 256, ++k) {
+        const int i = i0 + lane * 4;
         load4<VEC4>(l, i, V, x, -INFINITY);
         float qv[4];
+        unsigned long long mine = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             qv[e] = expf((x[e] - m) * inv_temperature) * inv;
-            if (i + e < V) acc += q_weight(qv[e]);
+            if (i + e < V) mine += q_weight(qv[e]);
         }
         if (VEC4) {
-            *(float4*)(q + i) = make_float4(qv[0], qv[1], qv[2], qv[3]);
+            if (i < V) *(float4*)(q + i) = make_float4(qv[0], qv[1], qv[2], qv[3]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (i + e < V) q[i + e] = qv[e];
         }
+        acc += mine;
+        if (fast) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+            if (lane == 0) step_sum[wave][k] = mine;
+        }
     }
+    if (fast)
+        for (int k = (w1 > w0 ? (w1 - w0 + 255) / 256 : 0) + lane; k < kDrawMaxSteps; k += 64) step_sum[wave][k] = 0;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
     if (lane == 0) wsum[wave] = acc;
     __syncthreads();   // totals published; the row is complete before any of it is read back
+
+    // weights of the 4 elements a lane holds in the step starting at i0 (tokens already drawn count zero)
+    auto step_weights = [&](int i0, int c, unsigned long long (&wt)[4]) {
+        const int i = i0 + lane * 4;
+        load4<VEC4>(q, i, V, x, 0.f);
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            bool gone = i + e >= V;
+            for (int k = 0; k < c; ++k) gone |= removed[k] == i + e;
+            wt[e] = gone ? 0ull : q_weight(x[e]);
+            mine += wt[e];
+        }
+        return mine;
+    };
+    auto wave_incl_scan = [&](unsigned long long v) {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long up = __shfl_up(v, o, 64);
+            if (lane >= o) v += up;
+        }
+        return v;
+    };
 
     for (int c = 0; c < n_child; ++c) {
         unsigned long long S = 0;
@@ -580,24 +617,19 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
         if (tid == 0) pick_s = V - 1;
         __syncthreads();
         if (wave == hit) {
-            for (int i0 = w0; i0 < w1; i0 += 256) {
-                const int i = i0 + lane * 4;
-                load4<VEC4>(q, i, V, x, 0.f);
-                unsigned long long wt[4], mine = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    bool gone = i + e >= V;
-                    for (int k = 0; k < c; ++k) gone |= removed[k] == i + e;
-                    wt[e] = gone ? 0ull : q_weight(x[e]);
-                    mine += wt[e];
-                }
-                // inclusive scan of the lanes' sums
-                unsigned long long incl = mine;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const unsigned long long up = __shfl_up(incl, o, 64);
-                    if (lane >= o) incl += up;
-                }
+            int i0 = w0;
+            if (fast) {   // the step: one step total per lane, scanned
+                const unsigned long long mine = lane < kDrawMaxSteps ? step_sum[wave][lane] : 0ull;
+                const unsigned long long incl = wave_incl_scan(mine);
+                const unsigned long long over = __builtin_amdgcn_ballot_w64(base + incl > thr);
+                const int k = over ? __builtin_ctzll(over) : 0;
+                base += __shfl(incl - mine, k, 64);
+                i0 = w0 + k * 256;
+            }
+            for (; i0 < w1; i0 += 256) {
+                unsigned long long wt[4];
+                const unsigned long long mine = step_weights(i0, c, wt);
+                const unsigned long long incl = wave_incl_scan(mine);
                 const unsigned long long step_total = __shfl(incl, 63, 64);
                 if (base + step_total > thr) {   // uniform over the wave: the pick is in this step
                     unsigned long long run = base + incl - mine;
@@ -606,7 +638,7 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
                         for (int e = 0; e < 4; ++e) {
                             run += wt[e];
                             if (run > thr) {
-                                pick_s = i + e;
+                                pick_s = i0 + lane * 4 + e;
                                 break;
                             }
                         }
@@ -621,7 +653,12 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
             const int pick = pick_s;
             bool gone = false;
             for (int k = 0; k < c; ++k) gone |= removed[k] == pick;
-            if (!gone) wsum[pick / Vw] -= q_weight(q[pick]);
+            if (!gone) {
+                const unsigned long long w = q_weight(q[pick]);
+                const int owner = pick / Vw;
+                wsum[owner] -= w;
+                if (fast) step_sum[owner][(pick - owner * Vw) / 256] -= w;
+            }
             token[(int64_t)b * n + first + c] = pick;
             removed[c] = pick;
         }
