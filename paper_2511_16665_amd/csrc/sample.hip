@@ -729,8 +729,9 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
     const int32_t* par = parent + (int64_t)b * n;
     int32_t* path = path_idx + (int64_t)b * stride;
     int32_t* out = out_tokens + (int64_t)b * stride;
-    unsigned long long* W = ws + (int64_t)b * 2 * V;
+    unsigned long long* W = ws + (int64_t)b * 3 * V;
     unsigned long long* Qw = W + V;
+    unsigned long long* R = Qw + V;   // the residual is built here and swapped with W when it has mass
     const double tau = (double)temperature;
     for (int j = tid; j < stride; j += kAcceptThreads) {
         path[j] = -1;
@@ -743,9 +744,11 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
     for (;;) {
         const float* l = logits + ((int64_t)b * n + cur) * V;
         const float* q = draft_q + ((int64_t)b * n + cur) * V;
-        double m = -INFINITY;
-        for (int j = tid; j < V; j += kAcceptThreads) m = fmax(m, (double)l[j] / tau);
-        m = block_max_d<kAcceptThreads / 64>(m, sd);
+        // max_j (l_j / tau) = (max_j l_j) / tau: a correctly rounded division by a positive number keeps
+        // the order, so the maximum is taken on the floats and divided once
+        float lmax = -INFINITY;
+        for (int j = tid; j < V; j += kAcceptThreads) lmax = fmaxf(lmax, l[j]);
+        const double m = block_max_d<kAcceptThreads / 64>((double)lmax, sd) / tau;
         unsigned long long s = 0, sq = 0;
         for (int j = tid; j < V; j += kAcceptThreads) {
             unsigned long long w = (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0);
@@ -775,25 +778,22 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
                 double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
                 double r = pj - qj;
                 if (r < 0.0) r = 0.0;
-                s2 += (unsigned long long)floor(r * 4294967296.0);
+                const unsigned long long rw = (unsigned long long)floor(r * 4294967296.0);
+                R[j] = rw;
+                s2 += rw;
             }
             s2 = block_sum_u64<kAcceptThreads / 64>(s2, su);
-            if (s2 > 0) {
-                for (int j = tid; j < V; j += kAcceptThreads) {
-                    double pj = u64_to_d(W[j]) / u64_to_d(S);
-                    double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
-                    double r = pj - qj;
-                    if (r < 0.0) r = 0.0;
-                    W[j] = (unsigned long long)floor(r * 4294967296.0);
-                }
+            if (s2 > 0) {   // the residual replaces the target weights (uniform: every thread swaps)
+                unsigned long long* tmp = W;
+                W = R;
+                R = tmp;
                 S = s2;
             }
+            // the draft loses the rejected token: an exact integer update of its total
+            const unsigned long long qt = Qw[t];
             __syncthreads();
             if (tid == 0) Qw[t] = 0;
-            __syncthreads();
-            unsigned long long sq2 = 0;
-            for (int j = tid; j < V; j += kAcceptThreads) sq2 += Qw[j];
-            SQ = block_sum_u64<kAcceptThreads / 64>(sq2, su);
+            SQ -= qt;
         }
         if (next < 0) break;
         if (tid == 0) out[a] = tok[next];
@@ -1107,7 +1107,7 @@ hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const i
     return hipGetLastError();
 }
 
-size_t accept_sample_workspace_bytes(int B, int V) { return (size_t)B * 2 * (size_t)V * sizeof(unsigned long long); }
+size_t accept_sample_workspace_bytes(int B, int V) { return (size_t)B * 3 * (size_t)V * sizeof(unsigned long long); }
 
 hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
                          const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
