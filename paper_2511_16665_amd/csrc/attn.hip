@@ -265,6 +265,13 @@ __global__ __launch_bounds__(256) void attn_plan_k(const int32_t* __restrict__ s
     }
 }
 
+__device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, uint32_t soff_bytes,
+                                           uint32_t lds_bytes) {
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :
+                 : "v"(voff_bytes), "s"(rsrc), "s"(soff_bytes), "s"(lds_bytes)
+                 : "memory", "m0");
+}
 template <int TPW>
 __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
                                                    float* __restrict__ part_o, float* __restrict__ part_ml,
@@ -367,25 +374,53 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int n_tiles = (k_end - k_begin + kKT - 1) / kKT;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)lds;
+    // Every DMA instruction of a wave covers 4 consecutive keys of one page, so the page, the source
+    // address and the range check are wave-uniform: they live in scalar registers (a raw buffer
+    // descriptor per instruction: base = the block's first key, size = the block, or 0 for a page the
+    // block table does not back, which makes every lane out of range: nothing is fetched), and a lane
+    // contributes only its constant offset inside the block.
+    uint32_t ck[2], cv[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int key_t = (wave_u + 8 * e) * 4 + (lane >> 4);   // key slot inside the tile
+        // logical 16-byte chunk this lane fetches: K rows are swizzled by the key slot (the 16 keys of
+        // a QK^T fragment read then hit 16 distinct chunks), V rows by twice the key slot (a
+        // transposing V read takes two neighbouring chunks of each of 8 keys: they stay distinct)
+        ck[e] = (uint32_t)(((lane & 15) ^ (key_t & 15)) * 16);
+        cv[e] = (uint32_t)(((lane & 15) ^ ((2 * key_t) & 15)) * 16);
+    }
+    const uint32_t kq = (uint32_t)lane >> 4;
+    auto desc = [&](const uint16_t* base, uint32_t bytes) {
+        const uint64_t p = (uint64_t)(uintptr_t)base;
+        u32x4_t d;
+        d[0] = __builtin_amdgcn_readfirstlane((uint32_t)p);
+        d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32) & 0xffffu);
+        d[2] = __builtin_amdgcn_readfirstlane(bytes);
+        d[3] = 0x00020000u;
+        return d;
+    };
     auto issue_dma = [&](int tile, int stage) {
         const int t0 = k_begin + tile * kKT;
+        const int last = k_end - 1;
+        int kb[2], pgv[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int blk = wave_u + 8 * e;                 // 4-key block of the tile
-            const int key_t = blk * 4 + (lane >> 4);        // key slot inside the tile
-            // logical 16-byte chunk this lane fetches: K rows are swizzled by the key slot (the 16 keys of
-            // a QK^T fragment read then hit 16 distinct chunks), V rows by twice the key slot (a
-            // transposing V read takes two neighbouring chunks of each of 8 keys: they stay distinct)
-            const int lck = (lane & 15) ^ (key_t & 15), lcv = (lane & 15) ^ ((2 * key_t) & 15);
-            int key = t0 + key_t;
-            key = key < k_end ? key : k_end - 1;            // tail slots re-read the last key (masked later)
-            const int pg = page_ids[(key - k_begin) >> 4];  // page_size is 16 for this kernel
-            const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (key & 15)) * kD;
-            if (pg >= 0) {
-                const uint32_t dst = lds_base + (uint32_t)(stage * kStageElems + blk * 512) * 2u;
-                dma_global_to_lds_16(kpool + off + lck * 8, dst);
-                dma_global_to_lds_16(vpool + off + lcv * 8, dst + kKT * kD * 2u);
-            }
+            int k0 = t0 + (wave_u + 8 * e) * 4;             // first key of the 4-key block
+            k0 = k0 <= last ? k0 : (last & ~3);             // blocks past the end re-read the last key's block
+            kb[e] = k0;
+            pgv[e] = page_ids[(k0 - k_begin) >> 4];         // page_size is 16 for this kernel
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int blk = wave_u + 8 * e;
+            const int pg = __builtin_amdgcn_readfirstlane(pgv[e]);
+            const int lim = min(3, last - kb[e]);           // keys past the end re-read the last key (masked later)
+            const int64_t off = (((int64_t)(pg < 0 ? 0 : pg) * kv.n_kv + kh) * 16 + (kb[e] & 15)) * kD;
+            const uint32_t size = pg >= 0 ? 1024u : 0u;
+            const uint32_t row = min(kq, (uint32_t)lim) << 8;
+            const uint32_t dst = lds_base + (uint32_t)(stage * kStageElems + blk * 512) * 2u;
+            dma_buf_16(desc(kpool + off, size), row | ck[e], 0u, dst);
+            dma_buf_16(desc(vpool + off, size), row | cv[e], 0u, dst + kKT * kD * 2u);
         }
     };
 #pragma unroll
@@ -446,22 +481,36 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             }
         }
     };
-    // The two waves that share a SIMD (w and w + 4) run the loop one phase apart, so that one's softmax
-    // (VALU) overlaps the other's MFMA phases instead of both doing the same thing at the same time:
-    // the early waves 0..3 pass the tile barrier before S = QK^T, the late waves 4..7 pass it one
-    // phase earlier, before the PV product of the previous tile.  PV of tile it-1 therefore runs at the
-    // top of iteration it for everyone, and the stage of tile it-1 stays untouched until iteration it+1.
+    // The two waves that share a SIMD (w and w + 4) run the loop half a period apart, so that one's
+    // softmax (VALU) runs under the other's two matrix products instead of both doing the same thing
+    // at the same time.  Per tile a wave does [PV of the previous tile, S = QK^T] (matrix pipe) and then
+    // [softmax] (VALU), two halves of about equal length.  The early waves 0..3 meet the tile barrier at
+    // the top of the iteration, before the matrix half; the late waves 4..7 meet the same barrier
+    // between their two halves, after QK^T of the tile before.  After each release the early wave of a
+    // SIMD therefore multiplies while the late one exponentiates, and the other way round in the second
+    // half of the period (measured with cycle stamps: with the late waves' barrier at the top as well,
+    // one phase apart only, both multiplied at once and the late wave's softmax ran while the early
+    // one sat at the barrier, 5700 against 5200 clocks per tile).  A wave raises its issue priority for
+    // its matrix half: a late MFMA costs the pipe, a late exp only the wave that waits for it.
+    // Barrier number it guarantees tile it has landed (every wave waited for its own DMAs first) and
+    // that nobody reads stage (it - 2) % kStages any more, which is where the fetch issued after it
+    // (tile it + 2) lands: the early waves read V of tile it-2 before barrier it, the late ones in the
+    // iteration that ended with it.  Both kinds pass exactly n_tiles barriers.
     const bool late = wave_u >= 4;
-    auto tile_sync = [&](int it) {
+    auto tile_wait = [&](int it) {
         __builtin_amdgcn_s_waitcnt(0x0F70u | (4 * (kAhead - 1)));  // vmcnt: this tile's 4 DMAs per wave have landed
         __builtin_amdgcn_s_barrier();
+    };
+    auto tile_fetch = [&](int it) {
         const int nxt = it + kAhead;
         issue_dma(nxt < n_tiles ? nxt : n_tiles - 1, nxt % kStages);
     };
+    if (late) tile_wait(0);
     for (int it = 0; it < n_tiles; ++it) {
-        if (late) tile_sync(it);
+        if (!late) tile_wait(it);
+        tile_fetch(it);
+        __builtin_amdgcn_s_setprio(2);
         if (it > 0) pv_step(lds + ((it - 1) % kStages) * kStageElems + kKT * kD);
-        if (!late) tile_sync(it);
         const int t0 = k_begin + it * kKT;
         const uint16_t* kt = lds + (it % kStages) * kStageElems;
         // 1 for the tile(s) touching the tree region or the chunk's tail, else 0.  Used as the trip count
@@ -491,6 +540,8 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
         }
+        __builtin_amdgcn_s_setprio(0);
+        if (late && it + 1 < n_tiles) tile_wait(it + 1);
         // ---- per row tile: online softmax, P packed straight into the second product's B operand
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
