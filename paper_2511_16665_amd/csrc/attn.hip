@@ -439,11 +439,25 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         // four keys 4*g4 .. 4*g4+3 of a 16-key sub-tile for head dimension 16*dt + l16: the 16 lanes of
         // a group address a 4-key x 16-dim block (lane s -> key s/4, dims 4*(s%4) ..) and the
         // instruction transposes it.  Two such reads (sub-tiles 2*half, 2*half+1) form the 8 k-slots.
+        // Four batches (key half, dimension half) of 8 reads + 4*TPW MFMAs; a batch's reads are issued
+        // before the MFMAs of the batch in front of it.
+        typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+        typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+        s16x4_t vv[2][4][2];
+        auto read_v = [&](int half, int dq, s16x4_t (*v)[2]) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-            typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-            {   // denominator: the same product against a V^T row of ones (bf16 1.0 = 0x3f80)
+            for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int dt = dq * 4 + d4;
+                    const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
+                    const int lcv = 2 * dt + ((l16 & 3) >> 1);
+                    const uint16_t* vp = vt + key_t * kD + ((lcv ^ ((2 * key_t) & 15)) * 8) + (l16 & 1) * 4;
+                    v[d4][sub] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
+                }
+        };
+        auto mul_v = [&](int half, int dq, s16x4_t (*v)[2]) {
+            if (dq == 0) {   // denominator: the same product against a V^T row of ones (bf16 1.0 = 0x3f80)
                 const s16x8_t one8 = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
@@ -452,34 +466,31 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                                                                       acc_l[t], 0, 0, 0);
             }
 #pragma unroll
-            for (int dq = 0; dq < 2; ++dq) {
-                s16x4_t vv[4][2];
+            for (int d4 = 0; d4 < 4; ++d4) {
+                const int dt = dq * 4 + d4;
+                s16x8_t v8 = {v[d4][0][0], v[d4][0][1], v[d4][0][2], v[d4][0][3],
+                              v[d4][1][0], v[d4][1][1], v[d4][1][2], v[d4][1][3]};
+                bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
 #pragma unroll
-                for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-                    for (int sub = 0; sub < 2; ++sub) {
-                        const int dt = dq * 4 + d4;
-                        const int key_t = half * 32 + sub * 16 + 4 * g4 + (l16 >> 2);
-                        const int lcv = 2 * dt + ((l16 & 3) >> 1);
-                        const uint16_t* vp = vt + key_t * kD + ((lcv ^ ((2 * key_t) & 15)) * 8) + (l16 & 1) * 4;
-                        vv[d4][sub] =
-                            __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)vp);
-                    }
-#pragma unroll
-                for (int d4 = 0; d4 < 4; ++d4) {
-                    const int dt = dq * 4 + d4;
-                    s16x8_t v8 = {vv[d4][0][0], vv[d4][0][1], vv[d4][0][2], vv[d4][0][3],
-                                  vv[d4][1][0], vv[d4][1][1], vv[d4][1][2], vv[d4][1][3]};
-                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
-#pragma unroll
-                    for (int t = 0; t < TPW; ++t)
-                        acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            a, __builtin_bit_cast(bf16x8_t, pb[t][half]), acc[t][dt], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // 8 transposing reads
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
+                for (int t = 0; t < TPW; ++t)
+                    acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8_t, pb[t][half]),
+                                                                        acc[t][dt], 0, 0, 0);
             }
-        }
+        };
+        read_v(0, 0, vv[0]);
+        read_v(0, 1, vv[1]);
+        mul_v(0, 0, vv[0]);
+        read_v(1, 0, vv[0]);
+        mul_v(0, 1, vv[1]);
+        read_v(1, 1, vv[1]);
+        mul_v(1, 0, vv[0]);
+        mul_v(1, 1, vv[1]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 5 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 9 * TPW, 0);
     };
     // The two waves that share a SIMD (w and w + 4) run the loop half a period apart, so that one's
     // softmax (VALU) runs under the other's two matrix products instead of both doing the same thing
@@ -522,24 +533,39 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         // LDS reads are issued in batches of 4 fragments ahead of the 4*TPW MFMAs that consume them, so
         // one LDS latency is exposed per batch instead of one per fragment.
         f32x4_t scs[TPW][4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            bf16x8_t kf[4];
+        bf16x8_t kf[2][4];
+        auto read_k = [&](int st, bf16x8_t* f) {
             const uint16_t* kp = kt + (st * 16 + l16) * kD;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                kf[ks] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
+                f[ks] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(kp + (((4 * ks + g4) ^ l16) * 8)));
+        };
+        auto mul_k = [&](int st, const bf16x8_t* f) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
-                    scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
+                    scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
                                                                          scs[t][st], 0, 0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);  // then their MFMAs
-        }
+        };
+        // the next 16 keys' fragments fly under each batch's MFMAs: order = 8 reads, then
+        // (12 MFMAs, 4 reads) twice, then the last two batches of MFMAs
+        read_k(0, kf[0]);
+        read_k(1, kf[1]);
+        mul_k(0, kf[0]);
+        read_k(2, kf[0]);
+        mul_k(1, kf[1]);
+        read_k(3, kf[1]);
+        mul_k(2, kf[0]);
+        mul_k(3, kf[1]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
         __builtin_amdgcn_s_setprio(0);
         if (late && it + 1 < n_tiles) tile_wait(it + 1);
         // ---- per row tile: online softmax, P packed straight into the second product's B operand
