@@ -87,7 +87,7 @@ template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU 
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
-                                                        int ksplit, int wg_per_xcd, int32_t* __restrict__ C2) {
+                                                        int ksplit, int wg_per_xcd, int32_t* __restrict__ C2, int kskew) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -134,8 +134,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         // (integer division runs on the vector ALU: pin the uniform results back into scalar registers)
         ti.m0 = __builtin_amdgcn_readfirstlane(tile_m * BM);
         ti.n0 = __builtin_amdgcn_readfirstlane(tile_n * BNO);
-        ti.kt0 = __builtin_amdgcn_readfirstlane(nk_all * split / ksplit);   // (nk_all * ksplit < 2^31 by the shape check)
-        ti.nt = __builtin_amdgcn_readfirstlane(nk_all * (split + 1) / ksplit) - ti.kt0;
+        // K tiles of split i: an even cut, or (kskew > 0) lengths that rise linearly from the mean - kskew
+        // to the mean + kskew, so that the splits of a one-round launch end at different times and the
+        // partial tiles of the early ones are added while the others still multiply
+        auto kbound = [&](int i) {   // (nk_all * ksplit < 2^31 by the shape check)
+            int k = nk_all * i / ksplit;
+            if (kskew > 0) k += kskew * (i * (i - 1) - i * (ksplit - 1)) / (ksplit - 1);
+            return k;
+        };
+        ti.kt0 = __builtin_amdgcn_readfirstlane(kbound(split));
+        ti.nt = __builtin_amdgcn_readfirstlane(kbound(split + 1)) - ti.kt0;
         return ti;
     };
     // raw buffer descriptors (four scalar words: base, base high bits, size in bytes, format) over a
@@ -475,7 +483,7 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
 
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false>
 static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C,
-                              const void* W2 = nullptr, int ksplit = 1, int ldc = 0) {
+                              const void* W2 = nullptr, int ksplit = 1, int ldc = 0, int kskew = 0) {
     // N counts the output columns this launch covers; ldc (default N) is the row stride of C
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     if (ldc == 0) ldc = N;
@@ -499,7 +507,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             attr_set = true;                                                                                          \
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
-                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr);                                           \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr, kskew);                                           \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
@@ -590,7 +598,13 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
                 // 1.5-2 TB/s: deeper weight rings, 128x128 tiles with twice the workgroups -- all measured the same)
                 // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
                 // the deeper ring keeps more of it in flight (31.7 against 39.5 us on the down projection at M = 32)
-                if (ks >= 2) return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
+                if (ks >= 2) {
+                    // uneven splits once the partial tiles weigh something (down projection at M = 256:
+                    // 60 -> 54 us; at M = 32 the even cut is better, 32 against 36 us)
+                    int skew = M >= 128 ? 8 : 0;
+                    if (skew > nk / ks / 4) skew = nk / ks / 4;
+                    return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N, K, A, W, C, nullptr, ks, 0, skew);
+                }
             }
         }
         if (out_mode == OUT_ADD_F32 && N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
@@ -603,7 +617,15 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
             // every split ends with a 256x256 tile of atomics: worth it for a long K only, or when M is
             // small and the alternative leaves most of the chip idle while the weights stream in
             const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
-            if (pays && tiles256 * ks >= 128) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks);
+            if (pays && tiles256 * ks >= 128) {
+                // all splits of a one-round launch would end together and add 64 MB of partial tiles in one
+                // burst with the matrix pipes idle: K is cut unevenly (lengths mean -+ 10 K tiles) so that the
+                // early splits add theirs under the others' products (down projection at M = 1536, 3 splits
+                // of 90 / 99 / 107 K tiles: 196 -> 187 us; mean -+ 16 and more lose it again)
+                int skew = 10;
+                if (skew > nk / ks / 4) skew = nk / ks / 4;
+                return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks, 0, skew);
+            }
         }
         return launch_tiled(s, out_mode, M, N, K, A, W, nullptr, C, false);
     }
@@ -661,7 +683,7 @@ hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const 
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(wg_per_xcd * 8), dim3(256), lds, s, M, P, K, (const uint16_t*)A, (const uint16_t*)W,
-                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi);
+                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(argmax_blocks_k, dim3((M + 3) / 4), dim3(256), 0, s, M, P, pv, pi, out);
