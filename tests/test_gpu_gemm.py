@@ -47,9 +47,28 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (1100, 3584, 2048),   # few 256x256 tiles, long K: split-K with atomic accumulation in mode 2, ragged M tail
     (1000, 16768, 128),   # 256x256 tiles for the whole rounds of the chip + 128x128 tiles for the remaining columns
     (200, 512, 1600),     # 25 K tiles split unevenly over 3 workgroups per tile... when the chip is under-filled
+    (1500, 3584, 256),    # 192x128 tiles (more than one round of 128-row tiles, one of 192-row tiles), ragged M tail
 ])
 def test_gemm_bf16(M, N, K, out_mode):
     _case(M, N, K, tlt.TLT_BF16, out_mode, 2)
+
+
+def test_gemm_bf16_split_k_with_uneven_cut_sampled_rows():
+    """Down-projection shape class (few 256x256 tiles, K long enough for three splits whose lengths differ
+    on purpose), accumulating into fp32 with a ragged M tail: sampled rows against float64."""
+    M, N, K = 1100, 3584, 9216
+    g = torch.Generator().manual_seed(5)
+    A = torch.randn((M, K), generator=g).bfloat16()
+    W = (torch.randn((N, K), generator=g) * 0.02).bfloat16()
+    C0 = torch.randn((M, N), generator=g)
+    out = C0.clone().cuda()
+    print(f"gemm split-K M={M} N={N} K={K}", flush=True)
+    tlt.gemm(tlt.TLT_BF16, 2, A.cuda(), W.cuda(), out)
+    torch.cuda.synchronize()
+    rows = [0, 1, 255, 256, 511, 512, 1023, 1024, 1099]
+    want = A[rows].double().numpy() @ W.double().numpy().T + C0[rows].double().numpy()
+    got = out[rows].double().cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-3 * np.abs(want).max()
 
 
 def test_gemm_bf16_7b_layer_shape_sampled_rows():
