@@ -90,6 +90,76 @@ def verify_latency_sweep(cfg, e, sizes, iters=3):
     return out
 
 
+def fixed_acceptance_steps(cfg, e, K, D, N, alpha, steps, warmup=1, seed=17):
+    """The same four calls with a stand-in for a TRAINED drafter.  A random-init drafter is almost
+    never right, so the headline steps accept nothing; here the verified tree is the static template
+    of (topK, Draft_Depth, Tokens_to_Verify) and its tokens are set (outside the timed region) so
+    that a node's first child carries the target's own greedy token with probability alpha and every
+    other node a random token: the accept length is geometric in alpha along the first-child chain.
+    The target's greedy token at a node needs the node's ancestors' tokens, so the labelling takes one
+    verification forward per tree level (untimed).  Timed per step (HIP events on the launch stream):
+    tlt_draft_expand (the real drafter at the same strategy: it consumes the tokens and hidden
+    states the step before accepted; its tree is discarded) and tlt_verify_forward + tlt_accept +
+    tlt_kv_commit on the labelled tree."""
+    import torch
+
+    from paper_2511_16665_amd import binding as tlt
+    B = e.B
+    pool = K + (D - 1) * K * K if D >= 1 else 0
+    t = e.tree(min(N, 1 + pool))                       # the drafter's own tree (discarded)
+    par, rank, dep = tlt.template_build(K, D, N)
+    n = len(par)
+    ts = tlt.Tree.empty(B, n)
+    ts.parent.copy_(torch.from_numpy(par).cuda().expand(B, n))
+    e.ctx.tree_finalize(B, ts)
+    hid, am = e._buf("hid", n), e._buf("am", n)
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    parent = ts.parent.long()
+    depth = torch.from_numpy(dep.astype(np.int64)).cuda().expand(B, n)
+    first_child = torch.from_numpy(rank == 0).cuda().expand(B, n)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    emitted, ms, accept_hist = 0, 0.0, []
+    for it in range(warmup + steps):
+        ev[0].record()
+        e.ctx.draft_expand(B, D, K, N, e.out_tokens, e.path_idx, e.n_out, e.pending_hidden, None, e.dkv, t)
+        ev[1].record()
+        e.dkv.seq_len_bound += e.pending_max_new
+        # ---- untimed: label the template level by level (the root is the token the last step ended with)
+        hit = first_child & (torch.rand((B, n), generator=gen, device="cuda") < alpha)
+        rnd = torch.randint(0, cfg.vocab, (B, n), generator=gen, device="cuda", dtype=torch.int32)
+        ts.token.copy_(rnd)
+        ts.token[:, 0] = t.token[:, 0]
+        for d in range(int(dep.max())):
+            e.ctx.verify_forward(B, ts, e.kv, out_logits=None, out_argmax=am, out_hidden=None)
+            level = depth == d + 1
+            from_parent = torch.gather(am, 1, parent.clamp(min=0)).to(torch.int32)
+            other = torch.where(rnd == from_parent, (rnd + 1) % cfg.vocab, rnd)   # never the greedy token by chance
+            ts.token.copy_(torch.where(level, torch.where(hit, from_parent, other), ts.token))
+        # ---- timed: verification, acceptance, commit
+        ev[2].record()
+        e.ctx.verify_forward(B, ts, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
+        e.ctx.accept(B, 0, 1.0, ts, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+        e.ctx.kv_commit(B, e.kv, e.accept_len, e.path_idx, e.stride)
+        ev[3].record()
+        torch.cuda.synchronize()
+        e.pending_hidden, e.have_pending = hid, True
+        al = e.accept_len.cpu().numpy()
+        inc = int(al.max()) + 1
+        e.kv.seq_len_bound += inc
+        e.pending_max_new = inc
+        if it >= warmup:
+            ms += ev[0].elapsed_time(ev[1]) + ev[2].elapsed_time(ev[3])
+            emitted += int(al.sum()) + B
+            accept_hist.append(float(al.mean()))
+    chain = int(dep[rank == 0].max()) if n > 1 else 0
+    return {"alpha": alpha, "steps": steps, "ms_per_step": round(ms / steps, 3),
+            "accepted_per_step": round(emitted / steps, 2), "mean_accept_length": round(float(np.mean(accept_hist)), 3),
+            "expected_accept_length": round(sum(alpha ** k for k in range(1, chain + 1)), 3),
+            "value": round(emitted / (ms * 1e-3), 2), "unit": "accepted tokens/s",
+            "note": "stand-in for a trained drafter: static-template tree whose first children are the target's greedy "
+                    "token with probability alpha (labelled untimed); timed: draft_expand + verify_forward + accept + kv_commit"}
+
+
 def _gather_rows(pool_layer, table_row, c, page_size):
     """First c cache rows of one sequence in one layer as float64 [c, Hkv, d]."""
     import torch
@@ -203,6 +273,9 @@ def main():
     ap.add_argument("--temperature", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", dest="sweep", action="store_false")
+    ap.add_argument("--alpha", type=float, default=0.8,
+                    help="greedy mode: also time a few steps with a stand-in for a trained drafter whose first "
+                         "children match the target with this probability (0 = skip)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="end with one plain device copy of this many MiB: the known-size kernel that hardware "
                          "counter readings (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by")
@@ -300,6 +373,8 @@ def main():
     }
     if args.sweep:
         result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
+    if args.alpha > 0 and args.mode == "greedy" and args.sweep:
+        result["fixed_acceptance"] = fixed_acceptance_steps(cfg, e, K, D, N, args.alpha, steps=5)
     if not args.no_cpu_baseline and args.mode == "greedy":
         result["cpu_baseline"] = cpu_baseline(cfg, tw, dw, ctx, table, dtable, e, args)
     if args.pmc_copy_mib > 0:
