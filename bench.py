@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
-def build_workload(args):
+def build_workload(args, shared=None):
     import torch
 
     from paper_2511_16665_amd import binding as tlt
@@ -49,8 +49,11 @@ def build_workload(args):
     dtable, dn_pages = random_block_table(caps, cfg.page_size, seed=2, extra_pages=8)
     dt = torch.bfloat16
     t0 = time.time()
-    tw = make_decoder_weights(cfg, 1234, device="cuda", dtype=dt)
-    dw = make_drafter_weights(cfg, 1234, device="cuda", dtype=dt)
+    if shared is None:
+        tw = make_decoder_weights(cfg, 1234, device="cuda", dtype=dt)
+        dw = make_drafter_weights(cfg, 1234, device="cuda", dtype=dt)
+    else:
+        tw, dw = shared
     kfill = fill_kv_pool(cfg.n_layers, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 3, "cuda", dt)
     dfill = fill_kv_pool(1, dn_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 4, "cuda", dt)
     kv = eng.alloc_kv(cfg, tlt.TLT_BF16, cfg.n_layers, table, n_pages, ctx, fill=kfill)
@@ -253,6 +256,63 @@ def recorded_traffic(key):
         return None
 
 
+def strategy_grid(args):
+    """The strategy sweep on the 7B shape (context fixed at 8192, greedy): for every batch size and
+    tree size the SD step with the trained-drafter stand-in of fixed_acceptance_steps (Draft_Depth =
+    min(8, N - 1), topK 8), and plain decoding for N = 1.  One JSON line with latency and accepted
+    tokens/s per cell: the grid the strategy selector's arms live on, and where speculative decoding
+    stops paying as the batch grows."""
+    import copy
+
+    import torch
+    shared, cells = None, []
+    for B in args.grid_batches:
+        a = copy.copy(args)
+        a.batch, a.verify, a.depth, a.topk = B, 64, 8, 8
+        a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = 8192, 8192, (max(2, -(-24 // B)) + 1) * len(args.grid_nodes), 2, True
+        cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a, shared)
+        shared = (tw, dw)
+        for N in args.grid_nodes:
+            if N == 1:
+                t = e.tree(1)
+                t.token.copy_(torch.randint(0, cfg.vocab, (B, 1), device="cuda", dtype=torch.int32))
+                t.parent.fill_(-1)
+                e.ctx.tree_finalize(B, t)
+                am = e._buf("am", 1)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                ms = 0.0
+                for it in range(4):
+                    ev[0].record()
+                    e.ctx.verify_forward(B, t, e.kv, out_logits=None, out_argmax=am, out_hidden=None)
+                    e.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx,
+                                 e.out_tokens, e.n_out)
+                    e.ctx.kv_commit(B, e.kv, e.accept_len, e.path_idx, e.stride)
+                    ev[1].record()
+                    torch.cuda.synchronize()
+                    e.kv.seq_len_bound += 1
+                    ms += ev[0].elapsed_time(ev[1]) if it > 0 else 0.0
+                cell = {"batch": B, "nodes": 1, "ms_per_step": round(ms / 3, 3), "accepted_per_step": float(B),
+                        "value": round(B / (ms / 3 * 1e-3), 1)}
+                # the drafter was not run: start its bookkeeping afresh for the cells that follow
+                g = torch.Generator(device="cuda").manual_seed(5)
+                e.set_pending(torch.randint(0, cfg.vocab, (B, 1), generator=g, device="cuda", dtype=torch.int32),
+                              torch.zeros((B, 1), dtype=torch.int32, device="cuda"),
+                              torch.ones((B,), dtype=torch.int32, device="cuda"),
+                              torch.randn((B, 1, cfg.hidden), generator=g, device="cuda", dtype=torch.float32), 1)
+            else:
+                # (enough sequence-steps per cell for a mean: 24 or more, each cell with draws of its own)
+                r = fixed_acceptance_steps(cfg, e, 8, min(8, N - 1), N, args.alpha, steps=max(2, -(-24 // B)),
+                                           seed=17 + 1000 * N + B)
+                cell = {"batch": B, "nodes": N, "ms_per_step": r["ms_per_step"], "accepted_per_step": r["accepted_per_step"],
+                        "expected_per_step": round(B * (1 + r["expected_accept_length"]), 2), "value": r["value"]}
+            cells.append(cell)
+            print(json.dumps(cell), file=sys.stderr, flush=True)
+        del e
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "strategy grid: accepted tokens/s per (batch, tree nodes)", "unit": "accepted tokens/s",
+                      "alpha": args.alpha, "context": 8192, "cells": cells}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -279,12 +339,18 @@ def main():
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="end with one plain device copy of this many MiB: the known-size kernel that hardware "
                          "counter readings (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by")
+    ap.add_argument("--grid", action="store_true",
+                    help="instead of the benchmark line: the strategy sweep (batch x tree nodes at context 8192)")
+    ap.add_argument("--grid-batches", type=int, nargs="+", default=[1, 4, 16, 64, 128])
+    ap.add_argument("--grid-nodes", type=int, nargs="+", default=[1, 8, 16, 32, 64])
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent and would "
                  "shard by sequence); run with --gpus 1")
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.grid:
+        return strategy_grid(args)
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 
