@@ -272,12 +272,16 @@ __device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, ui
                  : "v"(voff_bytes), "s"(rsrc), "s"(soff_bytes), "s"(lds_bytes)
                  : "memory", "m0");
 }
-template <int TPW>
-__global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
-                                                   float* __restrict__ part_o, float* __restrict__ part_ml,
-                                                   const AttnWork* __restrict__ work, int heads, int n_q_heads,
-                                                   int row_tiles, int tiles_per_group, int r_pad, float scale_log2,
-                                                   float lazy_raw) {
+// The workgroup's program, for a wave that owns NT row tiles (tiles wave, wave + 8, ...).  Waves of one
+// workgroup may run different instances (a wave whose share of the row tiles is smaller skips the
+// matrix and softmax work it has no rows for; NT = 0: it only fetches its part of the K/V tiles and
+// keeps the barriers): every instance passes the same barriers in the same order.
+template <int NT>
+__device__ __forceinline__ void attn_body(const Rows& rows, const KVLayer& kv, const uint16_t* __restrict__ qkv,
+                                          float* __restrict__ part_o, float* __restrict__ part_ml,
+                                          const AttnWork* __restrict__ work, int heads, int n_q_heads, int row_tiles,
+                                          int tiles_per_group, int r_pad, float scale_log2, float lazy_raw) {
+    constexpr int TPW = NT > 0 ? NT : 1;   // array extents (nothing is computed in them when NT = 0)
     extern __shared__ __align__(16) uint16_t lds[];
     const int rank = blockIdx.x / heads, hy = blockIdx.x - rank * heads;
     if (rank >= work->n_items) return;  // uniform
@@ -300,7 +304,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     int row_i[TPW];
     bool tile_on[TPW];
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
+    for (int t = 0; t < NT; ++t) {
         const int tile = rg * tiles_per_group + wave + 8 * t;
         tile_on[t] = (wave + 8 * t) < tiles_per_group && tile < row_tiles;
         const int r = tile * 16 + l16;
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     float m_run[TPW];
     f32x4_t acc_l[TPW];   // running softmax denominator, accumulated by the matrix pipe (PV product against a row of ones)
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
+    for (int t = 0; t < NT; ++t) {
         m_run[t] = kNegBig;
         acc_l[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -433,8 +437,9 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     // P of the tile whose PV product is still owed (packed bf16, the second product's B operand)
     u32x4_t pb[TPW][2];
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) pb[t][0] = pb[t][1] = u32x4_t{0u, 0u, 0u, 0u};
+    for (int t = 0; t < NT; ++t) pb[t][0] = pb[t][1] = u32x4_t{0u, 0u, 0u, 0u};
     auto pv_step = [&](const uint16_t* vt) {
+        if constexpr (NT == 0) return;
         // ---- O^T += V^T P^T.  V stays row-major in LDS; ds_read_b64_tr_b16 hands lane (l16, g4) the
         // four keys 4*g4 .. 4*g4+3 of a 16-key sub-tile for head dimension 16*dt + l16: the 16 lanes of
         // a group address a 4-key x 16-dim block (lane s -> key s/4, dims 4*(s%4) ..) and the
@@ -460,7 +465,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             if (dq == 0) {   // denominator: the same product against a V^T row of ones (bf16 1.0 = 0x3f80)
                 const s16x8_t one8 = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
 #pragma unroll
-                for (int t = 0; t < TPW; ++t)
+                for (int t = 0; t < NT; ++t)
                     acc_l[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, one8),
                                                                       __builtin_bit_cast(bf16x8_t, pb[t][half]),
                                                                       acc_l[t], 0, 0, 0);
@@ -472,7 +477,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                               v[d4][1][0], v[d4][1][1], v[d4][1][2], v[d4][1][3]};
                 bf16x8_t a = __builtin_bit_cast(bf16x8_t, v8);
 #pragma unroll
-                for (int t = 0; t < TPW; ++t)
+                for (int t = 0; t < NT; ++t)
                     acc[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8_t, pb[t][half]),
                                                                         acc[t][dt], 0, 0, 0);
             }
@@ -486,11 +491,11 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         mul_v(1, 0, vv[0]);
         mul_v(1, 1, vv[1]);
         __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 5 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 5 * NT, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * NT, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 9 * TPW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 9 * NT, 0);
     };
     // The two waves that share a SIMD (w and w + 4) run the loop half a period apart, so that one's
     // softmax (VALU) runs under the other's two matrix products instead of both doing the same thing
@@ -542,35 +547,37 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
         };
         auto mul_k = [&](int st, const bf16x8_t* f) {
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < NT; ++t) scs[t][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                for (int t = 0; t < TPW; ++t)
+                for (int t = 0; t < NT; ++t)
                     scs[t][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[ks], __builtin_bit_cast(bf16x8_t, qf[t][ks]),
                                                                          scs[t][st], 0, 0, 0);
         };
         // the next 16 keys' fragments fly under each batch's MFMAs: order = 8 reads, then
         // (12 MFMAs, 4 reads) twice, then the last two batches of MFMAs
-        read_k(0, kf[0]);
-        read_k(1, kf[1]);
-        mul_k(0, kf[0]);
-        read_k(2, kf[0]);
-        mul_k(1, kf[1]);
-        read_k(3, kf[1]);
-        mul_k(2, kf[0]);
-        mul_k(3, kf[1]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TPW, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
+        if constexpr (NT > 0) {
+            read_k(0, kf[0]);
+            read_k(1, kf[1]);
+            mul_k(0, kf[0]);
+            read_k(2, kf[0]);
+            mul_k(1, kf[1]);
+            read_k(3, kf[1]);
+            mul_k(2, kf[0]);
+            mul_k(3, kf[1]);
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * NT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * NT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 8 * NT, 0);
+        }
         __builtin_amdgcn_s_setprio(0);
         if (late && it + 1 < n_tiles) tile_wait(it + 1);
         // ---- per row tile: online softmax, P packed straight into the second product's B operand
 #pragma unroll
-        for (int t = 0; t < TPW; ++t) {
+        for (int t = 0; t < NT; ++t) {
             f32x4_t sc[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st) sc[st] = scs[t][st];
@@ -637,7 +644,7 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
     // ---- partial results: part_o [slot][n_kv][r_pad][128], part_ml [..][r_pad][2]
     const int64_t pbase = ((int64_t)item.slot * kv.n_kv + kh) * r_pad;
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
+    for (int t = 0; t < NT; ++t) {
         if (!tile_on[t]) continue;
         const int tile = rg * tiles_per_group + wave + 8 * t;
         const int r = tile * 16 + l16;
@@ -650,6 +657,27 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
             part_ml[(pbase + r) * 2 + 1] = l;
         }
     }
+}
+
+template <int TPW>
+__global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const uint16_t* __restrict__ qkv,
+                                                   float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                   const AttnWork* __restrict__ work, int heads, int n_q_heads,
+                                                   int row_tiles, int tiles_per_group, int r_pad, float scale_log2,
+                                                   float lazy_raw) {
+    // row tiles of this wave that exist (tile indices rise with t, so they are the first n_on)
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int rg = (int)(blockIdx.x % heads) / kv.n_kv;
+    int n_on = 0;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t)
+        n_on += ((wave + 8 * t) < tiles_per_group && rg * tiles_per_group + wave + 8 * t < row_tiles) ? 1 : 0;
+#define TLT_BODY(N) attn_body<N>(rows, kv, qkv, part_o, part_ml, work, heads, n_q_heads, row_tiles, tiles_per_group, r_pad, scale_log2, lazy_raw)
+    if (n_on >= TPW) TLT_BODY(TPW);
+    else if (TPW >= 2 && n_on == TPW - 1) TLT_BODY((TPW >= 2 ? TPW - 1 : 0));
+    else if (TPW >= 3 && n_on == TPW - 2) TLT_BODY((TPW >= 3 ? TPW - 2 : 0));
+    else TLT_BODY(0);
+#undef TLT_BODY
 }
 
 // One wave per (b, kv head, row), four rows per workgroup: merges the chunks' partial outputs
