@@ -48,9 +48,9 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
     for (int c = threadIdx.x; c < h; c += 256) o[c] = from_float<T>(xr[c] * inv * to_float(gamma[c]));
 }
 
-// Same, for h % 4 == 0 and h <= 4096: the row is read once with 16-byte loads and stays in registers
-// between the reduction and the scaling.
-template <typename T>
+// Same, for h % 4 == 0 and h <= 1024 * NK: the row is read once with 16-byte loads and stays in
+// registers (NK float4 per thread) between the reduction and the scaling.
+template <typename T, int NK>
 __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                      float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
                                                      const T* __restrict__ add) {
@@ -58,12 +58,12 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
     const int r = blockIdx.x, h4 = h >> 2;
     const int64_t src = row_map ? row_map[r] : r;
     T* o = out + (int64_t)r * h;
-    float4 v[4];
+    float4 v[NK];
     float ss = 0.f;
     if (src >= 0) {
         float4* xr = (float4*)(x + src * h);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < NK; ++k) {
             const int c = threadIdx.x + k * 256;
             v[k] = c < h4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
             if (add && c < h4) {
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
     const float tot = red[0] + red[1] + red[2] + red[3];
     const float inv = src >= 0 ? 1.0f / sqrtf(tot / (float)h + eps) : 0.f;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < NK; ++k) {
         const int c = threadIdx.x + k * 256;
         if (c >= h4) continue;
         const T* g = gamma + 4 * c;
@@ -303,7 +303,10 @@ static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* 
                                  const int32_t* row_map, const void* add) {
     if (M <= 0) return hipSuccess;
     if (h % 4 == 0 && h <= 4096 && (((uintptr_t)x | (uintptr_t)add) & 15) == 0) {
-        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_vec_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
+        DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 4>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
+                                             row_map, (const T*)add));
+    } else if (h % 4 == 0 && h <= 8192 && (((uintptr_t)x | (uintptr_t)add) & 15) == 0) {   // (the 32B and 70B widths)
+        DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 8>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
                                              row_map, (const T*)add));
     } else {
         DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
