@@ -153,7 +153,10 @@ def test_full_size_step_properties_and_sampled_parity():
     differ = int((am_fused != am_plain).sum().item())
     print(f"  fused LM-head argmax (1536 x 152064): {differ} rows differ from the second forward's; largest logit gap "
           f"{gap:.2e}, run-to-run noise of the logits {noise:.2e}", flush=True)
-    assert differ <= 16 and gap <= 4 * noise     # (noise is one pair's maximum; the pick compares another pair of runs)
+    # (noise is one pair's maximum and the pick compares another pair of runs; two runs can also agree to
+    # the last bit while a third does not, so the bar never falls below what two forwards that each
+    # meet the bf16 tolerance may differ by: 2 * TOL of the largest logit)
+    assert differ <= 16 and gap <= max(4 * noise, 2 * TOL * float(lg.abs().max()))
     st4 = sd.SeqState(small, cap, dec.round_to_bf16)
     for l in range(L4):
         st4.target[l].k[:c] = st.target[l].k[:c]
