@@ -21,6 +21,7 @@
 //
 // Generic path (fp32 mode, odd shapes): 64x64 LDS-tiled FMA kernel with full bounds checks.
 #include "dev_common.h"
+#include <cmath>
 #include "kernels.h"
 
 namespace tlt {
@@ -599,6 +600,15 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
             if (tiles < 200) {
                 int ks = 256 / tiles;
                 if (ks > nk / 8) ks = nk / 8;
+                // fewer splits when the partial tiles weigh more than the K steps they save: a workgroup
+                // alone on its CU takes ~0.6 us per K step, a split adds M*N*4 bytes of atomic traffic at
+                // ~1.75 TB/s; the sum nk*0.6/ks + ks*M*N*4/1.75e6 us is smallest at the square root of the ratio
+                // (qkv-sized product at M = 256: 37 us with 7 splits, 27 with 3-4; the down projection keeps its 9)
+                {
+                    const double per_split_us = (double)M * N * 4.0 / 1.75e6;
+                    const int best = (int)(sqrt(0.6 * nk / per_split_us) + 0.5);
+                    if (best < ks) ks = best < 1 ? 1 : best;
+                }
                 // (what is left after this is the atomic traffic of the partial tiles, ks * M * N * 4 bytes at
                 // 1.5-2 TB/s: deeper weight rings, 128x128 tiles with twice the workgroups -- all measured the same)
                 // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
