@@ -194,14 +194,17 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     const double e = (double)esz_of(ctx);
     float* x = (float*)(ws + p.x);
     int rc;
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr));
-    if (dt == TLT_BF16 && M <= 256 && qkv_dim % 128 == 0) {
+    const bool qkv_split = dt == TLT_BF16 && M <= 256 && qkv_dim % 128 == 0;
+    // (the fp32 q/k/v target of the split-K projection below is cleared by the norm kernel, row by row)
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e) + (qkv_split ? (double)M * qkv_dim * 4 : 0.0),
+            rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr, qkv_split ? (float*)(ws + p.qkv32) : nullptr,
+                    qkv_split ? qkv_dim : 0));
+    if (qkv_split) {
         // one row of tiles: the projection has too few tiles for the chip unless it splits K, which needs
         // an fp32 target to accumulate into; the rotary kernel reads that and leaves q in the model dtype.
         // (With the split count chosen against the partial sums' traffic this still pays at M = 256:
         // 27 + 4 us for the product and the clearing against 39 us for the plain bf16 product.)
         float* q32 = (float*)(ws + p.qkv32);
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * 4, zero_f32(s, (int64_t)M * qkv_dim, q32));
         if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, qkv_dim, h, ws + p.xn, w.wqkv, q32))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * (4 + e),
                 rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv, q32));

@@ -21,9 +21,11 @@ __global__ void embed_rows_k(int M, int h, int V, const int32_t* __restrict__ to
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                  float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                 const T* __restrict__ add) {
+                                                 const T* __restrict__ add, float* __restrict__ zero, int zero_n) {
     __shared__ float red[4];
     int r = blockIdx.x;
+    if (zero)
+        for (int c = threadIdx.x; c < zero_n; c += 256) zero[(int64_t)r * zero_n + c] = 0.f;
     int64_t src = row_map ? row_map[r] : r;
     T* o = out + (int64_t)r * h;
     if (src < 0) {
@@ -53,9 +55,12 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
 template <typename T, int NK>
 __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                      float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                     const T* __restrict__ add) {
+                                                     const T* __restrict__ add, float* __restrict__ zero, int zero_n) {
     __shared__ float red[4];
     const int r = blockIdx.x, h4 = h >> 2;
+    if (zero)   // row r of a second buffer cleared on the way (zero_n % 4 == 0, 16-byte aligned: the launcher checks)
+        for (int c = threadIdx.x; c < (zero_n >> 2); c += 256)
+            ((float4*)(zero + (int64_t)r * zero_n))[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int64_t src = row_map ? row_map[r] : r;
     T* o = out + (int64_t)r * h;
     float4 v[NK];
@@ -300,24 +305,25 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 }
 
 static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* x, const void* gamma, float eps, void* out,
-                                 const int32_t* row_map, const void* add) {
+                                 const int32_t* row_map, const void* add, float* zero = nullptr, int zero_n = 0) {
     if (M <= 0) return hipSuccess;
-    if (h % 4 == 0 && h <= 4096 && (((uintptr_t)x | (uintptr_t)add) & 15) == 0) {
+    const bool vec_ok = h % 4 == 0 && (((uintptr_t)x | (uintptr_t)add | (uintptr_t)zero) & 15) == 0 && zero_n % 4 == 0;
+    if (vec_ok && h <= 4096) {
         DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 4>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add));
-    } else if (h % 4 == 0 && h <= 8192 && (((uintptr_t)x | (uintptr_t)add) & 15) == 0) {   // (the 32B and 70B widths)
+                                             row_map, (const T*)add, zero, zero_n));
+    } else if (vec_ok && h <= 8192) {   // (the 32B and 70B widths)
         DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 8>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add));
+                                             row_map, (const T*)add, zero, zero_n));
     } else {
         DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add));
+                                             row_map, (const T*)add, zero, zero_n));
     }
     return hipGetLastError();
 }
 
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
-                   const int32_t* row_map) {
-    return rmsnorm_launch(s, dtype, M, h, const_cast<float*>(x), gamma, eps, out, row_map, nullptr);   // x is only read
+                   const int32_t* row_map, float* zero, int zero_n) {
+    return rmsnorm_launch(s, dtype, M, h, const_cast<float*>(x), gamma, eps, out, row_map, nullptr, zero, zero_n);   // x is only read
 }
 
 hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,

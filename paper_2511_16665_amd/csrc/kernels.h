@@ -58,8 +58,9 @@ hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const 
 // ---- elementwise.hip
 hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x);
 // out[r] = rmsnorm(x[row_map ? row_map[r] : r]) * gamma, stored in dtype.  Rows with row_map < 0 give zeros.
+// zero (optional): a second fp32 buffer [M][zero_n] cleared row by row in the same launch.
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
-                   const int32_t* row_map);
+                   const int32_t* row_map, float* zero = nullptr, int zero_n = 0);
 // x[r] += add[r] (add [M][h] in dtype), then out[r] = rmsnorm(x[r]) * gamma.
 hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
                        void* out);
