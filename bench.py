@@ -313,6 +313,38 @@ def strategy_grid(args):
                       "alpha": args.alpha, "context": 8192, "cells": cells}))
 
 
+def kv_commit_stress(args):
+    """tlt_kv_commit where it is not launch-bound: 128 sequences each keeping a 16-token path whose
+    nodes sit at every other provisional slot (so every kept row really moves), on the 7B cache layout
+    (28 layers x 4 kv heads x 256-byte rows).  One JSON line with the achieved HBM rate (bytes read
+    plus bytes written over the time of the call, the length update included)."""
+    import copy
+
+    import torch
+    a = copy.copy(args)
+    a.batch, a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = 128, 1024, 1024, 60, 2, False
+    cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a)
+    B, stride, calls = a.batch, 17, 20
+    al = torch.full((B,), stride - 1, dtype=torch.int32, device="cuda")
+    path = (torch.arange(stride, dtype=torch.int32, device="cuda") * 2).expand(B, stride).contiguous()
+    for _ in range(3):
+        e.ctx.kv_commit(B, e.kv, al, path, stride)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(calls):
+        e.ctx.kv_commit(B, e.kv, al, path, stride)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / calls
+    moved = B * (stride - 1) * cfg.kv_bytes_per_token(2) * 2
+    print(json.dumps({"metric": "tlt_kv_commit on a stress shape", "value": round(moved / ms / 1e6, 1), "unit": "GB/s",
+                      "peak": PEAK_HBM_GBS, "frac": round(moved / ms / 1e6 / PEAK_HBM_GBS, 4), "us_per_call": round(ms * 1e3, 2),
+                      "bytes_moved_per_call": moved,
+                      "config": {"workload": f"{cfg.name} cache layout, batch {B}, {stride - 1} rows moved per sequence, "
+                                             "layer and kv head (256-byte rows, sources at every other slot)"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -341,6 +373,8 @@ def main():
                          "counter readings (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by")
     ap.add_argument("--grid", action="store_true",
                     help="instead of the benchmark line: the strategy sweep (batch x tree nodes at context 8192)")
+    ap.add_argument("--kv-commit-stress", action="store_true",
+                    help="instead of the benchmark line: the HBM rate of tlt_kv_commit on a shape that is not launch-bound")
     ap.add_argument("--grid-batches", type=int, nargs="+", default=[1, 4, 16, 64, 128])
     ap.add_argument("--grid-nodes", type=int, nargs="+", default=[1, 8, 16, 32, 64])
     args = ap.parse_args()
@@ -351,6 +385,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if args.grid:
         return strategy_grid(args)
+    if args.kv_commit_stress:
+        return kv_commit_stress(args)
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 
