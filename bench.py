@@ -345,6 +345,52 @@ def kv_commit_stress(args):
                                              "layer and kv head (256-byte rows, sources at every other slot)"}}))
 
 
+def measured_ceilings(cfg, M):
+    """What this machine delivers to plain kernels, in the same run: a device-to-device copy (HBM read +
+    write) and the vendor library's bf16 GEMM (torch.matmul) on the verification forward's gate/up
+    and down shapes.  Context for the roofline fractions, which are quoted against the published peaks."""
+    import torch
+
+    def timed(fn, it):
+        fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(it):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / it * 1e-3
+
+    out = {}
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()   # 1 GiB
+    dst = torch.empty_like(src)
+    out["hbm_copy_GBs"] = round(2 * src.numel() * 4 / timed(lambda: dst.copy_(src), 5) / 1e9, 1)
+    del src, dst
+    try:
+        a = torch.randn((M, cfg.hidden), device="cuda").bfloat16()
+        af = torch.randn((M, cfg.mlp), device="cuda").bfloat16()
+        ws = [(torch.randn((2 * cfg.mlp, cfg.hidden), device="cuda") * 0.02).bfloat16() for _ in range(3)]
+        wd = [(torch.randn((cfg.hidden, cfg.mlp), device="cuda") * 0.02).bfloat16() for _ in range(3)]
+        i = [0]
+
+        def gate_up():
+            i[0] = (i[0] + 1) % 3
+            return a @ ws[i[0]].T
+
+        def down():
+            i[0] = (i[0] + 1) % 3
+            return af @ wd[i[0]].T
+
+        out["vendor_gemm_TFLOPs"] = {
+            "gate_up": round(4.0 * M * cfg.mlp * cfg.hidden / timed(gate_up, 6) / 1e12, 1),
+            "down": round(2.0 * M * cfg.mlp * cfg.hidden / timed(down, 6) / 1e12, 1)}
+    except Exception as ex:   # the library GEMM is context only
+        out["vendor_gemm_TFLOPs"] = None
+        out["vendor_gemm_error"] = str(ex)[:120]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -475,6 +521,8 @@ def main():
     }
     if args.sweep:
         result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
+    if args.sweep:
+        result["measured_ceilings"] = measured_ceilings(cfg, B * N)
     if args.alpha > 0 and args.mode == "greedy" and args.sweep:
         result["fixed_acceptance"] = fixed_acceptance_steps(cfg, e, K, D, N, args.alpha, steps=5)
     if not args.no_cpu_baseline and args.mode == "greedy":
