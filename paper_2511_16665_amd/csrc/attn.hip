@@ -99,7 +99,8 @@ __global__ __launch_bounds__(64) void attn_wave_per_row_k(Rows rows, KVLayer kv,
 // row r = i*G + g, cut into tiles of 16 rows dealt round-robin to the waves; a wave keeps its tiles'
 // Q fragments and fp32 output accumulators in registers and the whole workgroup streams the chunk's
 // K/V pages once through a 4-stage LDS ring in tiles of 64 keys, filled by direct global->LDS loads
-// issued three tiles ahead.
+// issued two tiles ahead.  A wave runs the instance of the program for the number of row tiles it owns
+// (waves of one workgroup share the barriers and the fetches, not the code).
 //
 // Both products run on v_mfma_f32_16x16x32_bf16 in the transposed orientation:
 //   S^T[key][row] = sum_d K[key][d] Q[row][d]      A = K rows from LDS, B = Q fragment
