@@ -385,6 +385,24 @@ def measured_ceilings(cfg, M):
         out["vendor_gemm_TFLOPs"] = {
             "gate_up": round(4.0 * M * cfg.mlp * cfg.hidden / timed(gate_up, 6) / 1e12, 1),
             "down": round(2.0 * M * cfg.mlp * cfg.hidden / timed(down, 6) / 1e12, 1)}
+        # this library's fused gate/up kernel on the same shape, once with these random operands and once
+        # with constant ones: the matrix pipes then toggle few bits and the chip keeps a higher clock under
+        # its power limit, which separates what the kernel's schedule sustains from what the power limit
+        # leaves of it on random data
+        from paper_2511_16665_amd import binding as tlt
+        act = torch.empty((M, cfg.mlp), dtype=torch.bfloat16, device="cuda")
+        halves = [(w[: cfg.mlp], w[cfg.mlp:]) for w in ws]
+
+        def own():
+            i[0] = (i[0] + 1) % 3
+            tlt.gemm_glu(a, halves[i[0]][0], halves[i[0]][1], act)
+
+        own_random = 4.0 * M * cfg.mlp * cfg.hidden / timed(own, 30) / 1e12
+        a.fill_(1.0)
+        for w in ws:
+            w.fill_(1.0)
+        out["own_gate_up_TFLOPs"] = {"random_operands": round(own_random, 1),
+                                     "constant_operands": round(4.0 * M * cfg.mlp * cfg.hidden / timed(own, 30) / 1e12, 1)}
     except Exception as ex:   # the library GEMM is context only
         out["vendor_gemm_TFLOPs"] = None
         out["vendor_gemm_error"] = str(ex)[:120]
