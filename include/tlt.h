@@ -126,13 +126,22 @@ int tlt_destroy(tlt_ctx *ctx);
  * order.  The root's token is root_tokens[b], or, when root_tokens is NULL, the last new token of
  * sequence b (new_tokens[b][n_new[b]-1]: the bonus token of the previous step).  Ties prefer the candidate created first / the lower token.
  * out_tree->n must equal min(n_verify, 1 + topk + (depth-1)*topk^2).
- * Provisional drafter entries use rows seq_len .. seq_len + (depth-1)*topk - 1 of draft_kv.
+ * Provisional drafter entries use rows seq_len .. seq_len + (depth-1)*topk - 1 of draft_kv; there may
+ * be at most 128 of them: (depth-1)*topk > 128 returns TLT_ESHAPE.
  * All pointers DEVICE except the structs themselves.  mode must be 0 (deterministic top-k); sampled
  * drafting has its own entry point, tlt_draft_sample. */
 int tlt_draft_expand(tlt_ctx *ctx, void *stream, int B, int depth, int topk, int n_verify, int mode,
                      const int32_t *new_tokens, const int32_t *new_src, const int32_t *n_new, int new_stride,
                      const float *hidden, int hidden_n, const int32_t *root_tokens, tlt_kv *draft_kv,
                      tlt_tree *out_tree);
+
+/* Read-out of the candidate pool the last tlt_draft_expand(B, depth, topk, ...) of this context left
+ * in the workspace (Section 5.1: every level's topk * topk candidates stay candidates for the final
+ * selection): DEVICE arrays [B][topk + (depth-1)*topk^2] in creation order (level, then the parent's
+ * rank in its frontier, then the child's rank): token, parent (pool index, -1 = child of the root),
+ * score (path log-probability).  For tests and inspection; enqueues device-to-device copies. */
+int tlt_draft_pool(tlt_ctx *ctx, void *stream, int B, int depth, int topk, int32_t *token, int32_t *parent,
+                   float *score);
 
 /* Static tree template of sampled drafting, HOST arrays of n_verify entries each (no GPU work).
  * The paper samples its rollouts (temperature 0.9, Section 6.1) and requires the output
@@ -226,6 +235,11 @@ int tlt_gemm_argmax(void *stream, int M, int N, int K, const void *A, const void
 /* Attention kernel choice for cross-checks: -1 automatic (default), 0 wave-per-row kernel,
  * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
 int tlt_set_attention_impl(tlt_ctx *ctx, int impl);
+
+/* Measurement switch: 1 = with more than 256 rows the attention output projection's product is rounded
+ * to the model dtype before it joins the fp32 residual stream (2 bytes per element less to write
+ * and read back per block); 0 (default) = it stays fp32, as the conventions at the top state. */
+int tlt_set_oproj_rounding(tlt_ctx *ctx, int round_to_model_dtype);
 
 /* Per-kernel-class timing with HIP events on the launch stream.  Classes: 0 GEMMs of the target's
  * verification forward, 1 its tree attention, 2 KV commit, 3 everything else, 4 the drafter's GEMMs,

@@ -32,6 +32,17 @@
  * from the target at every node, for any tree.  All integer: accept iff (U * total) >> 32 < weight(c)
  * (the inverse-CDF draw with c placed first), then total -= weight(c), weight(c) = 0; the final draw as above.
  *
+ * A child whose token lies outside the vocabulary is skipped by both sampling rules (it has probability
+ * zero under any distribution: never accepted, nothing else changes).
+ *
+ * Near-threshold flags.  Given identical weights every decision above is exact; computed from
+ * identical LOGITS, two platforms can still differ in the last bit of a double `exp`, i.e. by one
+ * unit in a weight W_j (and so by a few units in S or in a running sum).  The *_near variants below
+ * report, per sequence, whether any decision taken was within 8 units of 2^-32 of going the other
+ * way: |u q_c - p_c| < 8 * 2^-32 for an accept test of the p/q rule, |thr - W_c| <= 8 for one of the
+ * target-only rule, and a final draw whose threshold lies within 8 units of either end of the picked
+ * token's interval.  A parity test may tolerate a mismatch only in a flagged sequence.
+ *
  * Pins (tests/test_oracle_accept.py): brute force over all root-to-leaf paths (greedy); a
  * chi-square test of two generated tokens against p(x1) p(x2|x1) on a 16-token vocabulary over
  * 1e6 draws with a negative control; the closed form sum_v min(p_v, q_v) for the first accept;
@@ -41,6 +52,8 @@
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
+
+#define NEAR_UNITS 8 /* weight units (2^-32 of probability mass) a platform's exp may plausibly move a threshold by */
 
 static void target_weights(const float *logit, int V, double tau, uint64_t *W, uint64_t *S) {
     double m = -INFINITY;
@@ -97,10 +110,10 @@ void oracle_accept_greedy(int B, int n, int V, int stride, const int32_t *token,
 
 /* draft_q [B][n][V]: row i is the distribution node i's children were drawn from.
  * u_accept [B][n]: uniform used when node i is tested; u_final [B]: uniform of the final draw. */
-void oracle_accept_sample(int B, int n, int V, int stride, float temperature, const int32_t *token,
-                          const int32_t *parent, const float *logits, const float *draft_q,
-                          const uint32_t *u_accept, const uint32_t *u_final, int32_t *accept_len,
-                          int32_t *path_idx, int32_t *out_tokens, int32_t *n_out) {
+void oracle_accept_sample_near(int B, int n, int V, int stride, float temperature, const int32_t *token,
+                               const int32_t *parent, const float *logits, const float *draft_q,
+                               const uint32_t *u_accept, const uint32_t *u_final, int32_t *accept_len,
+                               int32_t *path_idx, int32_t *out_tokens, int32_t *n_out, int32_t *near) {
     uint64_t *W = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
     uint64_t *Qw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
     uint64_t *R = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
@@ -109,7 +122,7 @@ void oracle_accept_sample(int B, int n, int V, int stride, float temperature, co
         const int32_t *tok = token + (size_t)b * n, *par = parent + (size_t)b * n;
         int32_t *path = path_idx + (size_t)b * stride, *out = out_tokens + (size_t)b * stride;
         for (int j = 0; j < stride; ++j) { path[j] = -1; out[j] = -1; }
-        int cur = 0, a = 0;
+        int cur = 0, a = 0, nr = 0;
         path[0] = 0;
         uint64_t S, SQ;
         for (;;) { /* one iteration per node on the accepted path */
@@ -119,9 +132,11 @@ void oracle_accept_sample(int B, int n, int V, int stride, float temperature, co
             for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
                 if (par[c] != cur) continue;
                 int t = tok[c];
+                if (t < 0 || t >= V) continue;
                 double p = (double)W[t] / (double)S;
                 double q = SQ > 0 ? (double)Qw[t] / (double)SQ : 0.0;
                 double u = ((double)u_accept[(size_t)b * n + c] + 0.5) / 4294967296.0;
+                if (fabs(u * q - p) < NEAR_UNITS / 4294967296.0) nr = 1;
                 if (u * q < p) { next = c; break; }
                 /* rejected: residual target (kept only if it has mass: it has none exactly when
                    p <= q everywhere, i.e. p == q, a case the accept test above never rejects
@@ -156,28 +171,38 @@ void oracle_accept_sample(int B, int n, int V, int stride, float temperature, co
             run += W[j];
             if (run > thr) { pick = j; break; }
         }
+        if (run <= thr || run - thr <= NEAR_UNITS || thr - (run - W[pick]) < NEAR_UNITS) nr = 1;
         out[a] = pick;
         accept_len[b] = a;
         n_out[b] = a + 1;
+        if (near) near[b] = nr;
     }
     free(W);
     free(Qw);
     free(R);
 }
 
+void oracle_accept_sample(int B, int n, int V, int stride, float temperature, const int32_t *token,
+                          const int32_t *parent, const float *logits, const float *draft_q,
+                          const uint32_t *u_accept, const uint32_t *u_final, int32_t *accept_len,
+                          int32_t *path_idx, int32_t *out_tokens, int32_t *n_out) {
+    oracle_accept_sample_near(B, n, V, stride, temperature, token, parent, logits, draft_q, u_accept, u_final,
+                              accept_len, path_idx, out_tokens, n_out, NULL);
+}
+
 /* Target-only rule (see the header): u_accept [B][n] is the uniform used when node i is tested,
  * u_final [B] the uniform of the final draw. */
-void oracle_accept_target_only(int B, int n, int V, int stride, float temperature, const int32_t *token,
-                               const int32_t *parent, const float *logits, const uint32_t *u_accept,
-                               const uint32_t *u_final, int32_t *accept_len, int32_t *path_idx,
-                               int32_t *out_tokens, int32_t *n_out) {
+void oracle_accept_target_only_near(int B, int n, int V, int stride, float temperature, const int32_t *token,
+                                    const int32_t *parent, const float *logits, const uint32_t *u_accept,
+                                    const uint32_t *u_final, int32_t *accept_len, int32_t *path_idx,
+                                    int32_t *out_tokens, int32_t *n_out, int32_t *near) {
     uint64_t *W = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
     const double tau = (double)temperature;
     for (int b = 0; b < B; ++b) {
         const int32_t *tok = token + (size_t)b * n, *par = parent + (size_t)b * n;
         int32_t *path = path_idx + (size_t)b * stride, *out = out_tokens + (size_t)b * stride;
         for (int j = 0; j < stride; ++j) { path[j] = -1; out[j] = -1; }
-        int cur = 0, a = 0;
+        int cur = 0, a = 0, nr = 0;
         path[0] = 0;
         uint64_t S;
         for (;;) {
@@ -186,7 +211,9 @@ void oracle_accept_target_only(int B, int n, int V, int stride, float temperatur
             for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
                 if (par[c] != cur) continue;
                 int t = tok[c];
+                if (t < 0 || t >= V) continue;
                 uint64_t thr = (uint64_t)(((unsigned __int128)u_accept[(size_t)b * n + c] * (unsigned __int128)S) >> 32);
+                if ((thr < W[t] ? W[t] - thr : thr - W[t]) <= NEAR_UNITS && W[t] > 0) nr = 1;
                 if (thr < W[t]) { next = c; break; }
                 S -= W[t];
                 W[t] = 0;
@@ -202,9 +229,19 @@ void oracle_accept_target_only(int B, int n, int V, int stride, float temperatur
             run += W[j];
             if (run > thr) { pick = j; break; }
         }
+        if (run <= thr || run - thr <= NEAR_UNITS || thr - (run - W[pick]) < NEAR_UNITS) nr = 1;
         out[a] = pick;
         accept_len[b] = a;
         n_out[b] = a + 1;
+        if (near) near[b] = nr;
     }
     free(W);
+}
+
+void oracle_accept_target_only(int B, int n, int V, int stride, float temperature, const int32_t *token,
+                               const int32_t *parent, const float *logits, const uint32_t *u_accept,
+                               const uint32_t *u_final, int32_t *accept_len, int32_t *path_idx,
+                               int32_t *out_tokens, int32_t *n_out) {
+    oracle_accept_target_only_near(B, n, V, stride, temperature, token, parent, logits, u_accept, u_final, accept_len,
+                                   path_idx, out_tokens, n_out, NULL);
 }

@@ -57,7 +57,9 @@ def accept_greedy(token, parent, logits, stride):
     return al, path, out, n_out
 
 
-def accept_sample(token, parent, logits, draft_q, u_accept, u_final, temperature, stride):
+def accept_sample(token, parent, logits, draft_q, u_accept, u_final, temperature, stride, with_near=False):
+    """with_near: also return near [B] int32, 1 where some decision of the sequence was within 8 units of
+    2^-32 of going the other way (see accept.c): the only place a platform's last-bit `exp` can show."""
     token = np.ascontiguousarray(token, np.int32)
     parent = np.ascontiguousarray(parent, np.int32)
     logits = np.ascontiguousarray(logits, np.float32)
@@ -67,16 +69,19 @@ def accept_sample(token, parent, logits, draft_q, u_accept, u_final, temperature
     B, n, V = logits.shape
     assert draft_q.shape == logits.shape and u_accept.shape == (B, n) and u_final.shape == (B,)
     al, path, out, n_out = _outputs(B, stride)
-    _load().oracle_accept_sample(B, n, V, stride, ctypes.c_float(temperature), _p(token, ctypes.c_int32),
-                                 _p(parent, ctypes.c_int32), _p(logits, ctypes.c_float),
-                                 _p(draft_q, ctypes.c_float), _p(u_accept, ctypes.c_uint32),
-                                 _p(u_final, ctypes.c_uint32), _p(al, ctypes.c_int32),
-                                 _p(path, ctypes.c_int32), _p(out, ctypes.c_int32), _p(n_out, ctypes.c_int32))
-    return al, path, out, n_out
+    near = np.zeros(B, np.int32)
+    _load().oracle_accept_sample_near(B, n, V, stride, ctypes.c_float(temperature), _p(token, ctypes.c_int32),
+                                      _p(parent, ctypes.c_int32), _p(logits, ctypes.c_float),
+                                      _p(draft_q, ctypes.c_float), _p(u_accept, ctypes.c_uint32),
+                                      _p(u_final, ctypes.c_uint32), _p(al, ctypes.c_int32),
+                                      _p(path, ctypes.c_int32), _p(out, ctypes.c_int32), _p(n_out, ctypes.c_int32),
+                                      _p(near, ctypes.c_int32))
+    return (al, path, out, n_out, near) if with_near else (al, path, out, n_out)
 
 
-def accept_target_only(token, parent, logits, u_accept, u_final, temperature, stride):
-    """The rule for trees whose shape depends on the drafter's values (deterministic top-K trees)."""
+def accept_target_only(token, parent, logits, u_accept, u_final, temperature, stride, with_near=False):
+    """The rule for trees whose shape depends on the drafter's values (deterministic top-K trees).
+    with_near: as in accept_sample."""
     token = np.ascontiguousarray(token, np.int32)
     parent = np.ascontiguousarray(parent, np.int32)
     logits = np.ascontiguousarray(logits, np.float32)
@@ -85,12 +90,25 @@ def accept_target_only(token, parent, logits, u_accept, u_final, temperature, st
     B, n, V = logits.shape
     assert u_accept.shape == (B, n) and u_final.shape == (B,)
     al, path, out, n_out = _outputs(B, stride)
-    _load().oracle_accept_target_only(B, n, V, stride, ctypes.c_float(temperature), _p(token, ctypes.c_int32),
-                                      _p(parent, ctypes.c_int32), _p(logits, ctypes.c_float),
-                                      _p(u_accept, ctypes.c_uint32), _p(u_final, ctypes.c_uint32),
-                                      _p(al, ctypes.c_int32), _p(path, ctypes.c_int32), _p(out, ctypes.c_int32),
-                                      _p(n_out, ctypes.c_int32))
-    return al, path, out, n_out
+    near = np.zeros(B, np.int32)
+    _load().oracle_accept_target_only_near(B, n, V, stride, ctypes.c_float(temperature), _p(token, ctypes.c_int32),
+                                           _p(parent, ctypes.c_int32), _p(logits, ctypes.c_float),
+                                           _p(u_accept, ctypes.c_uint32), _p(u_final, ctypes.c_uint32),
+                                           _p(al, ctypes.c_int32), _p(path, ctypes.c_int32), _p(out, ctypes.c_int32),
+                                           _p(n_out, ctypes.c_int32), _p(near, ctypes.c_int32))
+    return (al, path, out, n_out, near) if with_near else (al, path, out, n_out)
+
+
+def assert_equal_unless_near(got, want, near, what=""):
+    """got/want: the four output arrays of an acceptance call.  Sequences whose oracle decisions were all
+    clear of their thresholds must agree exactly; a flagged sequence may differ and is reported."""
+    bad = []
+    for b in range(len(near)):
+        same = all(np.array_equal(np.asarray(g)[b], np.asarray(w)[b]) for g, w in zip(got, want))
+        if not same:
+            assert near[b], f"{what}: sequence {b} differs from the oracle although no decision was near a threshold"
+            bad.append(b)
+    return bad
 
 
 def draw_without_replacement(q, k, rng):

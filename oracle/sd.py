@@ -34,7 +34,9 @@ Pins (tests/test_oracle_sd.py): greedy SD output == cache-free autoregressive gr
 verification of a tree == cache-free causal forward of every root-to-node path; chain tree from an
 empty cache == dense causal forward; committed cache == keys/values of the dense forward of the
 emitted tokens; tree invariants and a brute-force re-derivation of frontier and selection on a
-toy Markov drafter; the pool size 2+3*4 = 14 of the paper's topK=2, depth=4 example.
+toy Markov drafter; the pool size 2+3*4 = 14 of the paper's topK=2, depth=4 example; the real
+drafter's expansion (`draft_expand`: provisional rows, positions, visibility) against a cache-free
+drafter forward over (committed entries ++ root-to-node path) for every candidate of the pool.
 The exact tree of the paper's figure (its tokens and probabilities are not in the text) and
 every accept length or speed-up the paper prints need trained weights: parity unpinned.
 """
@@ -98,29 +100,39 @@ def topk_desc(values, k):
 
 
 # ----------------------------------------------------------------------------- tree expansion / pruning
-def expand_tree(root_logp, level_fn: Callable[[int, List[int], List[Cand]], np.ndarray], K: int, D: int):
+def pick_best(where, values, k):
+    """Every choice of the tree building goes through a function of this signature: `where` names
+    the decision (("root",), ("children", level, frontier rank), ("frontier", level), ("keep",)),
+    `values` are the quantities it ranks and the result lists the k chosen indices, best first.
+    The method's own choice is the k largest (lower index on ties); tests that judge a tree built
+    in lower precision pass a function that replays that tree's choices instead and inspects
+    `values` to see how far from the best each one was."""
+    return topk_desc(values, k)
+
+
+def expand_tree(root_logp, level_fn: Callable[[int, List[int], List[Cand]], np.ndarray], K: int, D: int, pick=pick_best):
     """Candidate pool of Section 5.1's tree: level 0 = the K most likely tokens after the root;
     for each further level the K frontier nodes are run through the drafter (`level_fn(level,
     frontier_pool_indices, pool)` returns their [K, V] log-probabilities), each gives its K most
     likely children, and the K best of those K*K (by path score) form the next frontier.
     Pool order = creation order: level, then frontier rank, then child rank."""
     pool: List[Cand] = []
-    for t in topk_desc(root_logp, K):
+    for t in pick(("root",), root_logp, K):
         pool.append(Cand(t, float(root_logp[t]), -1, 1))
     frontier = list(range(len(pool)))
     for level in range(1, D):
         logp = level_fn(level, frontier, pool)
         base = len(pool)
         for fr, pi in enumerate(frontier):
-            for t in topk_desc(logp[fr], K):
+            for t in pick(("children", level, fr), logp[fr], K):
                 pool.append(Cand(t, pool[pi].score + float(logp[fr][t]), pi, level + 1))
-        frontier = [base + i for i in topk_desc([c.score for c in pool[base:]], K)]
+        frontier = [base + i for i in pick(("frontier", level), [c.score for c in pool[base:]], K)]
     return pool
 
 
-def prune_tree(pool: List[Cand], root_token: int, N: int) -> Tree:
+def prune_tree(pool: List[Cand], root_token: int, N: int, pick=pick_best) -> Tree:
     """Keep the N-1 pool candidates of highest path score (+ the root as node 0), in pool order."""
-    keep = sorted(topk_desc([c.score for c in pool], max(0, min(N - 1, len(pool)))))
+    keep = sorted(pick(("keep",), [c.score for c in pool], max(0, min(N - 1, len(pool)))))
     node_of = {pi: i + 1 for i, pi in enumerate(keep)}
     token, parent, depth, score = [root_token], [-1], [0], [0.0]
     for pi in keep:
@@ -165,7 +177,7 @@ def draft_extend(cfg, tw, dw, st: SeqState, new_tokens, new_hiddens):
     st.root_logp = dec.log_softmax(dec.lm_logits(cfg, tw, x[-1]))
 
 
-def draft_expand(cfg, tw, dw, st: SeqState, root_token: int, K: int, D: int, N: int):
+def draft_expand(cfg, tw, dw, st: SeqState, root_token: int, K: int, D: int, N: int, pick=pick_best):
     """Tree expansion with the real drafter, then pruning.  Returns (Tree, pool).
 
     A frontier node at depth s (its token is a candidate for position ctx+s) becomes drafter
@@ -197,8 +209,8 @@ def draft_expand(cfg, tw, dw, st: SeqState, root_token: int, K: int, D: int, N: 
             feats[pi] = x[r]
         return dec.log_softmax(dec.lm_logits(cfg, tw, x))
 
-    pool = expand_tree(st.root_logp, level_fn, K, D) if (D >= 1 and N > 1) else []
-    return prune_tree(pool, root_token, N), pool
+    pool = expand_tree(st.root_logp, level_fn, K, D, pick) if (D >= 1 and N > 1) else []
+    return prune_tree(pool, root_token, N, pick), pool
 
 
 # ----------------------------------------------------------------------------- target verification

@@ -25,7 +25,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding",
 ]
 
 
@@ -84,6 +84,7 @@ def load() -> C.CDLL:
     lib.tlt_draft_expand.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p, C.c_int,
                                                                                          C.c_void_p, C.POINTER(KVC),
                                                                                          C.POINTER(TreeC)]
+    lib.tlt_draft_pool.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3
     lib.tlt_template_build.argtypes = [C.c_int] * 3 + [C.POINTER(C.c_int32)] * 4
     lib.tlt_draft_sample.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 3 + \
         [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(KVC), C.c_void_p, C.POINTER(TreeC), C.c_void_p]
@@ -96,6 +97,7 @@ def load() -> C.CDLL:
     lib.tlt_gemm_glu.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 4
     lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
+    lib.tlt_set_oproj_rounding.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
@@ -241,6 +243,15 @@ class Context:
                                               _ptr(new_src), _ptr(n_new), new_stride, _ptr(hidden), hidden_n,
                                               _ptr(root_tokens), C.byref(kvc), tree_ref), "tlt_draft_expand")
 
+    def draft_pool(self, B, depth, topk):
+        """(token, parent, score) device tensors [B, topk + (depth-1)*topk^2] of the last expansion's pool."""
+        n = topk + (depth - 1) * topk * topk
+        token, parent = (torch.empty((B, n), dtype=torch.int32, device="cuda") for _ in range(2))
+        score = torch.empty((B, n), dtype=torch.float32, device="cuda")
+        self._check(self.lib.tlt_draft_pool(self.handle, _stream(), B, depth, topk, _ptr(token), _ptr(parent), _ptr(score)),
+                    "tlt_draft_pool")
+        return token, parent, score
+
     def draft_sample(self, B, depth, topk, n_verify, temperature, new_tokens, new_src, n_new, hidden, root_tokens,
                      draft_kv: KV, u_draw, out_tree: Tree, out_draft_q):
         new_stride = 0 if new_tokens is None else new_tokens.shape[1]
@@ -274,6 +285,9 @@ class Context:
 
     def set_attention_impl(self, impl: int):
         self._check(self.lib.tlt_set_attention_impl(self.handle, impl), "tlt_set_attention_impl")
+
+    def set_oproj_rounding(self, round_to_model_dtype: bool):
+        self._check(self.lib.tlt_set_oproj_rounding(self.handle, int(round_to_model_dtype)), "tlt_set_oproj_rounding")
 
     def profile_begin(self, enable=True):
         self._check(self.lib.tlt_profile_begin(self.handle, int(enable)), "tlt_profile_begin")

@@ -31,6 +31,8 @@ struct Plan {  // byte offsets into the workspace
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+constexpr int kMaxProvisionalRows = 128;   // rows of one expansion past the committed drafter entries (two mask words)
+
 bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_ctx, Plan& p) {
     if (B < 1 || n < 1 || n > TLT_MAX_TREE || D < 0 || D > TLT_MAX_DEPTH || K < 1 || K > TLT_MAX_TOPK || max_ctx < 1)
         return false;
@@ -54,7 +56,7 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.qkv = take(R * qkv_dim * esz);
     p.qkv32 = take(std::min<size_t>(R, 256) * qkv_dim * 4);   // fp32 q/k/v of a forward over few rows (split-K)
     p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
-    p.oproj = take(R * h * esz);
+    p.oproj = take(R * h * 4);
     p.g = take(R * F * esz);
     p.u = take(R * F * esz);
     p.act = take(R * F * esz);
@@ -107,6 +109,7 @@ struct tlt_ctx {
     Plan plan;
     int hip_error = 0;
     int attn_impl = -1;  // -1: pick by dtype/shape
+    bool oproj_f32 = true;   // the output projection's product reaches the residual stream unrounded
     bool in_draft = false;  // launches are accounted to the drafter's classes
     // profiling
     bool prof_on = false;
@@ -228,9 +231,12 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     // a read-modify-write of the fp32 stream by every tile
     // (with few rows the GEMM instead accumulates into x directly: that lets it split K over the chip)
     if (M > 256) {
-        if ((rc = run_gemm(ctx, s, OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + 2 * e),
-                rmsnorm_add(s, dt, M, h, x, ws + p.oproj, w.mlp_norm, c.rms_eps, ws + p.xn));
+        // (the product stays fp32 on its way into the fp32 residual stream unless the caller asked for
+        // the model dtype: rounding it would be the only rounding of a residual addend in the block)
+        const bool f32 = ctx->oproj_f32 || dt == TLT_F32;
+        if ((rc = run_gemm(ctx, s, f32 ? OUT_F32 : OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + (f32 ? 4 : e) + e),
+                rmsnorm_add(s, dt, M, h, x, ws + p.oproj, f32, w.mlp_norm, c.rms_eps, ws + p.xn));
     } else {
         if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
@@ -333,6 +339,12 @@ int tlt_destroy(tlt_ctx* ctx) {
 int tlt_set_attention_impl(tlt_ctx* ctx, int impl) {
     if (!ctx) return TLT_EINVAL;
     ctx->attn_impl = impl;
+    return TLT_OK;
+}
+
+int tlt_set_oproj_rounding(tlt_ctx* ctx, int round_to_model_dtype) {
+    if (!ctx) return TLT_EINVAL;
+    ctx->oproj_f32 = round_to_model_dtype == 0;
     return TLT_OK;
 }
 
@@ -443,6 +455,8 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         return TLT_EINVAL;
     if (B > ctx->max_batch || new_stride > std::max(ctx->max_n, ctx->max_topk)) return TLT_ESHAPE;
     if (do_expand && (depth > ctx->max_depth || topk > ctx->max_topk || n_verify > ctx->max_n)) return TLT_ESHAPE;
+    // a provisional drafter row is one bit of a 128-bit visibility mask
+    if (do_expand && (depth - 1) * topk > kMaxProvisionalRows) return TLT_ESHAPE;
     const int pool_n = do_expand ? topk + (depth - 1) * topk * topk : 0;
     if (do_expand && out_tree->n != std::min(n_verify, 1 + pool_n)) return TLT_EINVAL;
     const int prov_rows = do_expand ? (depth - 1) * topk : 0;
@@ -520,6 +534,24 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
             draft_prune(s, B, pool_n, out_tree->n, root_tokens, new_tokens, n_new, new_stride, st, out_tree->token, out_tree->parent, out_tree->depth,
                         out_tree->anc_mask, out_tree->score));
+    return TLT_OK;
+}
+
+int tlt_draft_pool(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int32_t* token, int32_t* parent, float* score) {
+    if (!ctx || !ctx->have_draft || B < 1 || depth < 1 || topk < 1 || !token || !parent || !score) return TLT_EINVAL;
+    if (B > ctx->max_batch || depth > ctx->max_depth || topk > ctx->max_topk) return TLT_ESHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    const Plan& p = ctx->plan;
+    const size_t n = (size_t)topk + (size_t)(depth - 1) * topk * topk, src_pitch = (size_t)p.pool_cap * 4;
+    const struct {
+        void* dst;
+        size_t off;
+    } parts[3] = {{token, p.pool_token}, {parent, p.pool_parent}, {score, p.pool_score}};
+    for (const auto& part : parts) {
+        hipError_t e = hipMemcpy2DAsync(part.dst, n * 4, ctx->ws + part.off, src_pitch, n * 4, (size_t)B,
+                                        hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail(ctx, e);
+    }
     return TLT_OK;
 }
 

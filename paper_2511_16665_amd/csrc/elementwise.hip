@@ -16,12 +16,12 @@ __global__ void embed_rows_k(int M, int h, int V, const int32_t* __restrict__ to
     for (int c = threadIdx.x; c < h; c += blockDim.x) x[(int64_t)r * h + c] = ok ? to_float(e[c]) : 0.f;
 }
 
-// `add` (optional, [rows][h] in T, no row_map then): the residual stream takes x[r] += add[r] first --
-// the output projection leaves its product there instead of read-modify-writing x itself.
-template <typename T>
+// `add` (optional, [rows][h] in TA = T or float, no row_map then): the residual stream takes x[r] += add[r]
+// first -- the output projection leaves its product there instead of read-modify-writing x itself.
+template <typename T, typename TA>
 __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                  float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                 const T* __restrict__ add, float* __restrict__ zero, int zero_n) {
+                                                 const TA* __restrict__ add, float* __restrict__ zero, int zero_n) {
     __shared__ float red[4];
     int r = blockIdx.x;
     if (zero)
@@ -52,10 +52,10 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
 
 // Same, for h % 4 == 0 and h <= 1024 * NK: the row is read once with 16-byte loads and stays in
 // registers (NK float4 per thread) between the reduction and the scaling.
-template <typename T, int NK>
+template <typename T, int NK, typename TA>
 __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                      float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                     const T* __restrict__ add, float* __restrict__ zero, int zero_n) {
+                                                     const TA* __restrict__ add, float* __restrict__ zero, int zero_n) {
     __shared__ float red[4];
     const int r = blockIdx.x, h4 = h >> 2;
     if (zero)   // row r of a second buffer cleared on the way (zero_n % 4 == 0, 16-byte aligned: the launcher checks)
@@ -72,8 +72,8 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
             const int c = threadIdx.x + k * 256;
             v[k] = c < h4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
             if (add && c < h4) {
-                const T* a = add + src * h + 4 * c;
-                if constexpr (sizeof(T) == 2) {
+                const TA* a = add + src * h + 4 * c;
+                if constexpr (sizeof(TA) == 2) {
                     const uint2 pk = *(const uint2*)a;
                     v[k].x += __uint_as_float(pk.x << 16);
                     v[k].y += __uint_as_float(pk.x & 0xffff0000u);
@@ -304,31 +304,39 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
     return hipGetLastError();
 }
 
-static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* x, const void* gamma, float eps, void* out,
-                                 const int32_t* row_map, const void* add, float* zero = nullptr, int zero_n = 0) {
-    if (M <= 0) return hipSuccess;
+template <typename T, typename TA>
+static void rmsnorm_launch_t(hipStream_t s, int M, int h, float* x, const void* gamma, float eps, void* out,
+                             const int32_t* row_map, const void* add, float* zero, int zero_n) {
     const bool vec_ok = h % 4 == 0 && (((uintptr_t)x | (uintptr_t)add | (uintptr_t)zero) & 15) == 0 && zero_n % 4 == 0;
-    if (vec_ok && h <= 4096) {
-        DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 4>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add, zero, zero_n));
-    } else if (vec_ok && h <= 8192) {   // (the 32B and 70B widths)
-        DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_vec_k<T, 8>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add, zero, zero_n));
-    } else {
-        DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_k<T>, dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out,
-                                             row_map, (const T*)add, zero, zero_n));
-    }
+    if (vec_ok && h <= 4096)
+        hipLaunchKernelGGL((rmsnorm_vec_k<T, 4, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
+                           (const TA*)add, zero, zero_n);
+    else if (vec_ok && h <= 8192)   // (the 32B and 70B widths)
+        hipLaunchKernelGGL((rmsnorm_vec_k<T, 8, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
+                           (const TA*)add, zero, zero_n);
+    else
+        hipLaunchKernelGGL((rmsnorm_k<T, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
+                           (const TA*)add, zero, zero_n);
+}
+
+static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* x, const void* gamma, float eps, void* out,
+                                 const int32_t* row_map, const void* add, bool add_f32 = false, float* zero = nullptr,
+                                 int zero_n = 0) {
+    if (M <= 0) return hipSuccess;
+    if (dtype == F32) rmsnorm_launch_t<float, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
+    else if (add_f32) rmsnorm_launch_t<bf16, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
+    else rmsnorm_launch_t<bf16, bf16>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
     return hipGetLastError();
 }
 
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map, float* zero, int zero_n) {
-    return rmsnorm_launch(s, dtype, M, h, const_cast<float*>(x), gamma, eps, out, row_map, nullptr, zero, zero_n);   // x is only read
+    return rmsnorm_launch(s, dtype, M, h, const_cast<float*>(x), gamma, eps, out, row_map, nullptr, false, zero, zero_n);   // x is only read
 }
 
-hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
-                       void* out) {
-    return rmsnorm_launch(s, dtype, M, h, x, gamma, eps, out, nullptr, add);
+hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, bool add_f32, const void* gamma,
+                       float eps, void* out) {
+    return rmsnorm_launch(s, dtype, M, h, x, gamma, eps, out, nullptr, add, add_f32);
 }
 
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,

@@ -61,9 +61,9 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 // zero (optional): a second fp32 buffer [M][zero_n] cleared row by row in the same launch.
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map, float* zero = nullptr, int zero_n = 0);
-// x[r] += add[r] (add [M][h] in dtype), then out[r] = rmsnorm(x[r]) * gamma.
-hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, const void* gamma, float eps,
-                       void* out);
+// x[r] += add[r] (add [M][h] in dtype, or in fp32 when add_f32), then out[r] = rmsnorm(x[r]) * gamma.
+hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, bool add_f32, const void* gamma,
+                       float eps, void* out);
 // (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation; src32: optional
 // fp32 copy of the projection to read instead of qkv, which then only receives the rotated q)
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,

@@ -46,3 +46,30 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="not found"):
         binding.load()
+
+
+def test_draft_expand_rejects_more_provisional_rows_than_a_mask_holds():
+    """(depth-1)*topk provisional drafter rows are one bit each of a 128-bit visibility mask: a
+    depth/topk pair inside the published per-argument limits (16 each) but beyond 128 rows must
+    be refused on the host, before anything is enqueued (no GPU is touched here)."""
+    lib = binding.load()
+    cfg = binding.ModelCfgC(1, 256, 4, 2, 64, 768, 1024, 1e-6, 1e6, 0, 16)
+    fake = 0x10000      # never dereferenced: validation returns first
+    layers = (binding.LayerWeightsC * 1)()
+    for k, _ in binding.LayerWeightsC._fields_:
+        setattr(layers[0], k, fake)
+    tw = binding.WeightsC(fake, fake, fake, layers, None)
+    dw = binding.WeightsC(fake, fake, fake, layers, fake)
+    nbytes = lib.tlt_workspace_bytes(ctypes.byref(cfg), 2, 64, 16, 16, 4096)
+    assert nbytes > 0
+    h = ctypes.c_void_p()
+    assert lib.tlt_create(ctypes.byref(h), ctypes.byref(cfg), ctypes.byref(tw), ctypes.byref(dw), 2, 64, 16, 16, 4096,
+                          ctypes.c_void_p(fake), nbytes) == 0
+    kv = binding.KVC(fake, fake, 1024, fake, fake, 300, 100)
+    tree = binding.TreeC(fake, fake, fake, fake, fake, 64)
+    call = lambda depth, topk: lib.tlt_draft_expand(h, None, 2, depth, topk, 64, 0, None, None, None, 0, None, 0,
+                                                    ctypes.c_void_p(fake), ctypes.byref(kv), ctypes.byref(tree))
+    assert call(10, 16) == -2            # 144 rows
+    assert call(16, 16) == -2
+    assert call(9, 17) == -2             # topk beyond the context's limit
+    assert lib.tlt_destroy(h) == 0

@@ -11,7 +11,7 @@ from oracle import sd
 from paper_2511_16665_amd import binding as tlt
 from synth import MID, fill_kv_pool
 
-from gpu_util import dense_cache, make_engine, make_models
+from gpu_util import check_draft_tree_against_forced_oracle, dense_cache, make_engine, make_models
 
 pytestmark = pytest.mark.gpu
 
@@ -40,6 +40,7 @@ def test_draft_expand_bf16_matches_oracle(K, D, N, impl):
     print(f"draft_expand bf16 K={K} D={D} N={N} impl={impl}", flush=True)
     dev = lambda a: torch.from_numpy(a).cuda()
     e.ctx.draft_expand(B, D, K, N, dev(new_tok), dev(new_src), dev(n_new), dev(hidden), None, e.dkv, tree)
+    pool_dev = e.ctx.draft_pool(B, D, K)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(e.dkv.seq_len.cpu().numpy(), ctxs + n_new)
     g_tok, g_par, g_dep, g_sc = (x.cpu().numpy() for x in (tree.token, tree.parent, tree.depth, tree.score))
@@ -53,25 +54,18 @@ def test_draft_expand_bf16_matches_oracle(K, D, N, impl):
         st.draft_len = c
         toks = [int(t) for t in new_tok[b, : n_new[b]]]
         sd.draft_extend(cfg, tw, dw, st, toks, hidden[b][new_src[b, : n_new[b]]].astype(np.float64))
-        want, pool = sd.draft_expand(cfg, tw, dw, st, toks[-1], K, D, N)
         # structural invariants hold whatever the rounding did
         assert g_tok[b, 0] == toks[-1] and g_par[b, 0] == -1 and g_dep[b, 0] == 0
         for i in range(1, N):
             p = g_par[b, i]
             assert 0 <= p < i and g_dep[b, i] == g_dep[b, p] + 1 and g_sc[b, i] <= g_sc[b, p] + 1e-6
             assert g_mask[b, i] == (g_mask[b, p] | np.uint64(1 << i))
-        # the K root children are the drafter's K most likely tokens: compare their log-probs
-        lvl1 = [i for i in range(N) if g_dep[b, i] == 1]
-        o_lvl1 = [i for i in range(want.n) if want.depth[i] == 1]
-        top = np.sort(st.root_logp)[::-1]
-        if top[K - 1] - top[K] > 2e-2:
-            assert sorted(g_tok[b, lvl1]) == sorted(int(t) for t in want.token[o_lvl1])
-        # same tree whenever the oracle's path scores are separated by more than bf16 noise
-        scores = np.sort(np.array([cand.score for cand in pool]))
-        if np.array_equal(g_tok[b], want.token) and np.array_equal(g_par[b], want.parent):
-            n_same += 1
-            np.testing.assert_allclose(g_sc[b], want.score, atol=3e-2 * max(1.0, np.abs(want.score).max()))
-        else:
-            assert np.min(np.diff(scores)) < 2e-2, (b, "trees differ although all path scores are well separated")
+        # the GPU's choices replayed through the oracle's drafter: scores within tolerance, every choice
+        # optimal within twice the tolerance, tree = pruning of that pool, identical when no choice differs
+        g_pool = tuple(x[b].cpu().numpy() for x in pool_dev)
+        seen = check_draft_tree_against_forced_oracle(sd, cfg, tw, dw, st, toks[-1], K, D, N, g_pool,
+                                                      (g_tok[b], g_par[b], g_dep[b], g_sc[b]), 2e-2)
+        print(f"  sequence {b}: {seen}", flush=True)
+        n_same += int(seen["identical"])
     print("identical trees:", n_same, "of", B, flush=True)
     e.ctx.close()

@@ -234,3 +234,144 @@ def test_record_reward_arithmetic():
     assert a_bar == 3.5 and r == 28.0
     # no speculation: every accept length 0 -> one token per sequence per step
     assert sd.record_reward(2.0, [0] * 8, 8) == (1.0, 4.0)
+
+
+# ---------------------------------------------------------------- the real drafter's expansion, cache-free
+_plain_block_rows = dec.block_rows     # the unpatched routine (the mutation tests below swap sd's copy)
+
+
+def _pool_against_cache_free_drafter(K, D, N, seed=21):
+    """Every candidate of `sd.draft_expand`'s pool against a drafter run WITHOUT a cache (Section 4.1:
+    the drafter drafts autoregressively from its own output; Section 5.1: topK options per step):
+    the log-probability row behind a frontier node == one dense causal drafter pass over (committed
+    entries ++ the node's root-to-node path, each path entry built from its token and its parent's
+    output); its children == that row's K best tokens; every candidate's score == the sum of those
+    row entries along its path; each next frontier == the K best of the level.  Pins the provisional
+    rows' cache slots, rotary positions and visibility sets.  Returns the number of rows checked."""
+    cfg = MICRO
+    tw, dw = _models(cfg, seed, std=0.3)
+    prompt = [int(t) for t in prompts(1, 12, cfg.vocab, seed=9)[0]]
+    st = sd.SeqState(cfg, 96)
+    root = sd.prefill(cfg, tw, dw, st, prompt)
+    tree, pool = sd.draft_expand(cfg, tw, dw, st, root, K, D, N)
+    assert len(pool) == K + (D - 1) * K * K
+
+    _, hidden, _, _ = dec.dense_forward(cfg, tw, prompt[:-1])
+    x_committed = sd.drafter_input(cfg, tw, dw, prompt[1:], hidden)    # entry s = (token s+1, hidden s)
+    assert len(x_committed) == st.draft_len
+
+    def dense_drafter(x):
+        T = len(x)
+        pos = np.arange(T)
+        return _plain_block_rows(cfg, dw["layer"], x, pos, pos, pos[None, :] <= pos[:, None], dec.LayerCache(cfg, T))
+
+    def path_of(ci):
+        out = []
+        while ci >= 0:
+            out.append(ci)
+            ci = pool[ci].parent
+        return out[::-1]
+
+    rows = {}
+
+    def row_after(ci):   # log-probabilities of the token following candidate ci (-1: the root)
+        if ci not in rows:
+            x = x_committed
+            out = dense_drafter(x)
+            for node in ([] if ci < 0 else path_of(ci)):
+                x = np.concatenate([x, sd.drafter_input(cfg, tw, dw, [pool[node].token], out[-1:])])
+                out = dense_drafter(x)
+            rows[ci] = dec.log_softmax(dec.lm_logits(cfg, tw, out[-1]))
+        return rows[ci]
+
+    # level by level: children of each expanded node, their scores, the next frontier
+    frontier = [-1]
+    at = 0
+    for level in range(D):
+        level_cands = []
+        for parent_ci in frontier:
+            row = row_after(parent_ci)
+            best = sorted(range(cfg.vocab), key=lambda t: (-row[t], t))[:K]
+            for t in best:
+                c = pool[at]
+                assert (c.token, c.parent, c.depth) == (t, parent_ci, level + 1), (at, c)
+                want = (0.0 if parent_ci < 0 else pool[parent_ci].score) + row[t]
+                assert abs(c.score - want) < 1e-9, (at, c.score, want)
+                level_cands.append(at)
+                at += 1
+        frontier = sorted(level_cands, key=lambda ci: (-pool[ci].score, ci))[:K]
+    assert at == len(pool)
+    # the kept nodes: the N-1 best of the pool
+    keep = sorted(sorted(range(len(pool)), key=lambda ci: (-pool[ci].score, ci))[: N - 1])
+    assert [int(t) for t in tree.token[1:]] == [pool[ci].token for ci in keep]
+    return len(rows)
+
+
+@pytest.mark.parametrize("K,D,N", [(3, 4, 12), (2, 5, 9), (4, 3, 40)])
+def test_draft_expand_pool_equals_cache_free_drafter_forward_of_every_path(K, D, N):
+    assert _pool_against_cache_free_drafter(K, D, N) >= 1 + (D - 1) * K - K
+
+
+@pytest.mark.parametrize("mutation", ["position", "sibling_visible", "ancestors_hidden", "slot"])
+def test_the_cache_free_pin_catches_planted_mistakes_in_the_provisional_rows(mutation, monkeypatch):
+    """The pin above must fail when the oracle's provisional drafter rows are wrong: a rotary position
+    off by one, siblings of a level seeing each other, a node not seeing its ancestors, two nodes
+    sharing a cache row.  The mistake is planted in the oracle (CPU), in the routine draft_expand calls."""
+    in_expand = {"on": False}
+    real_expand = sd.draft_expand
+
+    def block_rows(cfg, lw, x, pos, slots, visible, cache, store=dec.identity):
+        if in_expand["on"]:
+            base = int(np.min(slots))
+            if mutation == "position":
+                pos = pos + 1
+            elif mutation == "sibling_visible":
+                visible = visible.copy()
+                visible[:, slots] = True
+            elif mutation == "ancestors_hidden":
+                keep_self = np.zeros_like(visible)
+                keep_self[np.arange(len(slots)), slots] = True
+                visible = visible.copy()
+                visible[:, cache_len["n"]:] = False      # no provisional row but its own
+                visible |= keep_self
+            elif mutation == "slot":
+                slots = np.full_like(slots, base)
+        return _plain_block_rows(cfg, lw, x, pos, slots, visible, cache, store)
+
+    cache_len = {"n": 0}
+
+    def expand(cfg, tw, dw, st, *a, **k):
+        in_expand["on"] = True
+        cache_len["n"] = st.draft_len
+        try:
+            return real_expand(cfg, tw, dw, st, *a, **k)
+        finally:
+            in_expand["on"] = False
+
+    monkeypatch.setattr(sd.dec, "block_rows", block_rows)
+    monkeypatch.setattr(sd, "draft_expand", expand)
+    with pytest.raises(AssertionError):
+        _pool_against_cache_free_drafter(3, 4, 12)
+
+
+def test_forced_choices_replay_the_same_pool_and_report_the_ranked_values():
+    """`pick`: with the default every decision is the K best; a function that returns other indices is
+    followed (scores stay sums of the rows' entries) and sees the values it chose among."""
+    rng = np.random.default_rng(4)
+    table = dec.log_softmax(rng.normal(size=(9, 9)) * 2)
+    seen = []
+
+    def second_best_first(where, values, k):
+        seen.append((where, len(values)))
+        best = sd.topk_desc(values, k + 1)
+        return best[1:] if where[0] == "children" and len(values) > k else best[:k]
+
+    pool = sd.expand_tree(table[0], _markov_level_fn(table), 2, 3, pick=second_best_first)
+    assert [w for w, _ in seen] == [("root",), ("children", 1, 0), ("children", 1, 1), ("frontier", 1),
+                                    ("children", 2, 0), ("children", 2, 1), ("frontier", 2)]
+    for c in pool[2:]:
+        assert abs(c.score - (pool[c.parent].score + table[pool[c.parent].token][c.token])) < 1e-12
+    first = pool[0]
+    kids = [c.token for c in pool[2:4]]
+    order = sorted(range(9), key=lambda t: (-table[first.token][t], t))
+    assert kids == order[1:3]
