@@ -37,7 +37,8 @@ enum {
     TLT_ESHAPE = -2,   /* size exceeds what tlt_create was told, or workspace too small */
     TLT_ENOPAGES = -3, /* block table cannot hold seq_len_bound + new rows */
     TLT_EHIP = -4,     /* a HIP call failed (see tlt_last_hip_error) */
-    TLT_ENOTIMPL = -5
+    TLT_ENOTIMPL = -5,
+    TLT_ESYNC = -6     /* reported by tlt_device_status: workgroups of a kernel could not meet on the device */
 };
 
 enum { TLT_F32 = 0, TLT_BF16 = 1 };
@@ -73,7 +74,8 @@ typedef struct tlt_weights {
  * in the model dtype.  block_table: DEVICE [B][max_pages] page ids; slot s of sequence b lives in
  * page block_table[b][s / page_size] at row s % page_size.  seq_len: DEVICE [B] committed tokens.
  * seq_len_bound: HOST-known upper bound of max_b seq_len[b] (sizes the attention grid and is
- * checked against the block table; a bound that is too small drops the excess context rows). */
+ * checked against the block table).  A bound below some seq_len[b] is a caller error that only the
+ * device can see: the call's outputs are wrong and tlt_device_status reports TLT_ESHAPE. */
 typedef struct tlt_kv {
     void *k_pool, *v_pool;
     int64_t n_pages;
@@ -235,6 +237,15 @@ int tlt_gemm_argmax(void *stream, int M, int N, int K, const void *A, const void
 /* Attention kernel choice for cross-checks: -1 automatic (default), 0 wave-per-row kernel,
  * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
 int tlt_set_attention_impl(tlt_ctx *ctx, int impl);
+
+/* Conditions that only the device can see are recorded in a status word in the workspace and reported
+ * here: synchronises `stream`, writes the bits to *flags (HOST, may be NULL), clears them, and returns
+ * TLT_ESHAPE when a kernel found seq_len[b] above the caller's seq_len_bound (the attention then covered
+ * only part of that sequence's context: the outputs of that call are wrong), TLT_ESYNC when the
+ * workgroups of a sampling acceptance could not meet because the chip was busy with other streams'
+ * work (that call's outputs are undefined: repeat it), else TLT_OK. */
+enum { TLT_STATUS_CONTEXT_TRUNCATED = 1, TLT_STATUS_NO_RENDEZVOUS = 2 };
+int tlt_device_status(tlt_ctx *ctx, void *stream, uint32_t *flags);
 
 /* Measurement switch: 1 = with more than 256 rows the attention output projection's product is rounded
  * to the model dtype before it joins the fp32 residual stream (2 bytes per element less to write

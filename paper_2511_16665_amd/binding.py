@@ -18,14 +18,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtlt.so")
 
 TLT_F32, TLT_BF16 = 0, 1
-ERRORS = {0: "TLT_OK", -1: "TLT_EINVAL", -2: "TLT_ESHAPE", -3: "TLT_ENOPAGES", -4: "TLT_EHIP", -5: "TLT_ENOTIMPL"}
+ERRORS = {0: "TLT_OK", -1: "TLT_EINVAL", -2: "TLT_ESHAPE", -3: "TLT_ENOPAGES", -4: "TLT_EHIP", -5: "TLT_ENOTIMPL",
+          -6: "TLT_ESYNC"}
 
 EXPORTS = [
     "tlt_strerror", "tlt_last_hip_error", "tlt_workspace_bytes", "tlt_create", "tlt_destroy", "tlt_draft_expand",
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status",
 ]
 
 
@@ -98,6 +99,7 @@ def load() -> C.CDLL:
     lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_set_oproj_rounding.argtypes = [C.c_void_p, C.c_int]
+    lib.tlt_device_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
@@ -285,6 +287,15 @@ class Context:
 
     def set_attention_impl(self, impl: int):
         self._check(self.lib.tlt_set_attention_impl(self.handle, impl), "tlt_set_attention_impl")
+
+    def device_status(self, check=True):
+        """Synchronises the current stream and returns the device-side status bits (cleared by the call);
+        with check=True a raised bit becomes a TltError (TLT_ESHAPE / TLT_ESYNC)."""
+        flags = C.c_uint32()
+        rc = self.lib.tlt_device_status(self.handle, _stream(), C.byref(flags))
+        if check:
+            self._check(rc, "tlt_device_status")
+        return flags.value
 
     def set_oproj_rounding(self, round_to_model_dtype: bool):
         self._check(self.lib.tlt_set_oproj_rounding(self.handle, int(round_to_model_dtype)), "tlt_set_oproj_rounding")

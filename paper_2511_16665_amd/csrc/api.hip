@@ -24,7 +24,7 @@ struct ProfRec {
 
 struct Plan {  // byte offsets into the workspace
     size_t x, xn, qkv, qkv32, att, oproj, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
-        pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, total;
+        pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, status, total;
     size_t attn_ws_bytes;
     int max_rows, pool_cap, feat_rows;
 };
@@ -80,6 +80,7 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.attn_ws = take(p.attn_ws_bytes);
     p.accept_ws = take(accept_sample_workspace_bytes(B, c.vocab));
     p.topk_ws = take(row_topk_workspace_bytes(B * K, c.vocab, K));
+    p.status = take(256);   // device-side status word (see tlt_device_status)
     p.total = o;
     return true;
 }
@@ -111,6 +112,7 @@ struct tlt_ctx {
     int attn_impl = -1;  // -1: pick by dtype/shape
     bool oproj_f32 = true;   // the output projection's product reaches the residual stream unrounded
     bool in_draft = false;  // launches are accounted to the drafter's classes
+    bool status_ready = false;   // the status word in the (caller-owned, uninitialised) workspace has been cleared
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> events;
@@ -164,6 +166,17 @@ int run_gemm(tlt_ctx* ctx, hipStream_t s, int out_mode, int M, int N, int K, con
     const double out_b = out_mode == OUT_T ? e : (out_mode == OUT_F32 ? 4.0 : 8.0);
     TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 2.0 * M * N * K, ((double)M * K + (double)N * K) * e + (double)M * N * out_b,
             gemm(s, ctx->cfg.dtype, out_mode, M, N, K, A, W, C));
+    return TLT_OK;
+}
+
+unsigned int* status_word(tlt_ctx* ctx) { return (unsigned int*)(ctx->ws + ctx->plan.status); }
+
+// The status word is cleared by the first call that may raise it (the workspace arrives uninitialised).
+int ensure_status(tlt_ctx* ctx, hipStream_t s) {
+    if (ctx->status_ready) return TLT_OK;
+    hipError_t e = zero_f32(s, 64, (float*)status_word(ctx));
+    if (e != hipSuccess) return fail(ctx, e);
+    ctx->status_ready = true;
     return TLT_OK;
 }
 
@@ -224,7 +237,7 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
         const double flops = 4.0 * c.head_dim * c.n_q_heads * (double)rows.n * keys;
         TLT_RUN(ctx, s, ctx->in_draft ? CLS_ATTN_DRAFT : CLS_ATTN, flops, bytes,
                 attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl,
-                          reuse_attn_plan));
+                          reuse_attn_plan, ctx->status_ready ? status_word(ctx) : nullptr));
     }
     // the output projection's product goes to a buffer of its own (in the model dtype) and joins the
     // residual stream inside the norm kernel that follows: a plain store in the GEMM's epilogue instead of
@@ -276,6 +289,7 @@ const char* tlt_strerror(int code) {
         case TLT_ENOPAGES: return "block table too short for seq_len_bound + new rows";
         case TLT_EHIP: return "HIP call failed";
         case TLT_ENOTIMPL: return "not implemented";
+        case TLT_ESYNC: return "workgroups of a kernel could not meet on the device (chip busy with other work)";
         default: return "unknown error";
     }
 }
@@ -342,6 +356,23 @@ int tlt_set_attention_impl(tlt_ctx* ctx, int impl) {
     return TLT_OK;
 }
 
+int tlt_device_status(tlt_ctx* ctx, void* stream, uint32_t* flags) {
+    if (!ctx) return TLT_EINVAL;
+    if (flags) *flags = 0;
+    if (!ctx->status_ready) return TLT_OK;   // nothing that could raise it has run
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t host = 0;
+    hipError_t e = hipMemcpyAsync(&host, status_word(ctx), sizeof(host), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(ctx, e);
+    if (flags) *flags = host;
+    if (host != 0) {
+        e = zero_f32(s, 64, (float*)status_word(ctx));
+        if (e != hipSuccess) return fail(ctx, e);
+    }
+    return (host & TLT_STATUS_CONTEXT_TRUNCATED) ? TLT_ESHAPE : ((host & TLT_STATUS_NO_RENDEZVOUS) ? TLT_ESYNC : TLT_OK);
+}
+
 int tlt_set_oproj_rounding(tlt_ctx* ctx, int round_to_model_dtype) {
     if (!ctx) return TLT_EINVAL;
     ctx->oproj_f32 = round_to_model_dtype == 0;
@@ -362,6 +393,7 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
     int rc = check_kv(ctx, kv, tree->n);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_status(ctx, s))) return rc;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -469,6 +501,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         ~DraftFlag() { c->in_draft = false; }
     } draft_flag(ctx);
     hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_status(ctx, s))) return rc;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -587,6 +620,7 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         ~DraftFlag() { c->in_draft = false; }
     } draft_flag(ctx);
     hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_status(ctx, s))) return rc;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -697,9 +731,12 @@ int tlt_accept(tlt_ctx* ctx, void* stream, int B, int mode, float temperature, c
     }
     if (mode == 1) {
         if (!target_logits || !draft_q || !u_accept || !u_final || !(temperature > 0.f)) return TLT_EINVAL;
+        int rc = ensure_status(ctx, s);
+        if (rc) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, 0,
                 accept_sample(s, B, n, V, stride, temperature, tree->token, tree->parent, target_logits, draft_q, u_accept,
-                              u_final, accept_len, path_idx, out_tokens, n_out, ctx->ws + ctx->plan.accept_ws));
+                              u_final, accept_len, path_idx, out_tokens, n_out, ctx->ws + ctx->plan.accept_ws,
+                              status_word(ctx)));
         return TLT_OK;
     }
     if (mode == 2) {

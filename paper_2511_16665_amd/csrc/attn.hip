@@ -184,13 +184,19 @@ static size_t attn_work_bytes(int B, int max_items) {
 }
 
 __global__ __launch_bounds__(256) void attn_plan_k(const int32_t* __restrict__ seq_len, int B, int n_region, int heads,
-                                                   int max_items, AttnWork* __restrict__ work) {
+                                                   int max_items, AttnWork* __restrict__ work, int len_bound,
+                                                   unsigned int* __restrict__ status) {
     __shared__ int s_T, s_total, s_hist[66], s_pos[66];
     int* slot0 = (int*)(work + 1);
     int* nch = slot0 + B;
     AttnItem* items = (AttnItem*)(nch + B);
     const int tid = threadIdx.x;
     if (tid < 66) s_hist[tid] = 0;
+    // the grid and the item list were sized from the caller's length bound: a longer sequence would lose
+    // part of its context, which only the device can see
+    if (status)
+        for (int b = tid; b < B; b += 256)
+            if (seq_len[b] > len_bound) atomicOr(status, 1u);
     // A workgroup takes a whole CU (248 VGPRs per wave, 128 KB of LDS), so the work items run in rounds of
     // 256.  Measured at the 7B benchmark shape (attention ms per step): one round of 256 items 4.02, two
     // rounds 4.33, four 4.20, and 4.6-4.8 when the count falls between whole rounds (384, 768 items): the
@@ -738,7 +744,7 @@ size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, in
 template <int TPW>
 static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
                                    int n_q_heads, const AttnPlan& p, AttnWork* work, float* part_o, float* part_ml,
-                                   bool reuse_plan) {
+                                   bool reuse_plan, unsigned int* status) {
     const size_t lds = (size_t)kStages * kStageElems * sizeof(uint16_t) + (kMaxChunk / 16 + 2) * sizeof(int32_t) +
                        (size_t)kMaxRows * 2 * sizeof(uint64_t);
     if (rows.n > kMaxRows) return hipErrorInvalidValue;
@@ -752,7 +758,8 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     const int tiles_per_group = (p.row_tiles + p.row_groups - 1) / p.row_groups;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)kD);
     if (!reuse_plan)
-        hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work);
+        hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work,
+                           kv.seq_len_bound, status);
     hipLaunchKernelGGL(kern, dim3(p.max_items * p.heads), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
                        part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2,
                        8.0f / scale_log2);
@@ -765,7 +772,7 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
 }
 
 hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan) {
+                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan, unsigned int* status) {
     if (rows.B * rows.n <= 0) return hipSuccess;
     if (kv.d % 64 != 0 || kv.d > 256) return hipErrorInvalidValue;
     const int G = n_q_heads / kv.n_kv;
@@ -777,9 +784,9 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
             float* part_o = (float*)((char*)ws + attn_work_bytes(rows.B, p.max_items));
             float* part_ml = part_o + (size_t)p.max_items * kv.n_kv * p.r_pad * kD;
             switch (p.tpw) {
-                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
-                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
-                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan);
+                case 1: return launch_attn_mfma<1>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan, status);
+                case 2: return launch_attn_mfma<2>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan, status);
+                default: return launch_attn_mfma<3>(s, rows, kv, qkv, out, n_q_heads, p, work, part_o, part_ml, reuse_plan, status);
             }
         }
         if (impl == 1) return hipErrorInvalidValue;  // explicitly requested but the workspace cannot hold it

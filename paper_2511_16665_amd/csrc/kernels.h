@@ -85,8 +85,11 @@ hipError_t iota_scaled(hipStream_t s, int n, int32_t* out, int scale);
 
 // ---- attn.hip
 size_t attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int d, int max_ctx);
+// status (optional): device word whose bit 0 is raised when some seq_len[b] exceeds kv.seq_len_bound (the MFMA
+// kernel's work list is sized from that bound, so such a sequence would lose context rows).
 hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, const void* qkv, void* out,
-                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan = false);
+                     int n_q_heads, void* ws, size_t ws_bytes, int impl, bool reuse_plan = false,
+                     unsigned int* status = nullptr);
 
 // ---- sample.hip
 hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
@@ -142,11 +145,15 @@ hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, T
 hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const int32_t* token, const int32_t* parent,
                          const float* logits, const int32_t* argmax, int32_t* accept_len, int32_t* path_idx,
                          int32_t* out_tokens, int32_t* n_out);
+// ws: accept_sample_workspace_bytes(B, V) bytes of scratch (16-byte aligned; contents need not be preserved or
+// cleared between calls).  status: device word; bit 1 is raised if the workgroups of a sequence could not meet
+// (see the kernel) and the sequence's outputs are then undefined.  n <= TLT_ACCEPT_MAX_NODES.
+#define TLT_ACCEPT_MAX_NODES 64
 size_t accept_sample_workspace_bytes(int B, int V);
 hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
                          const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
                          const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
-                         int32_t* n_out, void* ws);
+                         int32_t* n_out, void* ws, unsigned int* status);
 hipError_t accept_target_only(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
                               const int32_t* parent, const float* logits, const uint32_t* u_accept, const uint32_t* u_final,
                               int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens, int32_t* n_out);

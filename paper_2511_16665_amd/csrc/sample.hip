@@ -702,15 +702,69 @@ __global__ void accept_greedy_k(int B, int n, int stride, const int32_t* __restr
     n_out[b] = a + 1;
 }
 
-// Recursive rejection sampling, one workgroup per sequence.  Integer weights W (target) and Qw
-// (draft) live in the workspace: [B][2][V] u64.  Every sum over the vocabulary is an exact integer
-// sum, every other operation a single IEEE double operation, so the decisions do not depend on the
-// reduction order.
+// Recursive rejection sampling.  Integer weights W (target), Qw (draft) and the residual R live in
+// the scratch buffer ([B][3][V] u64, followed by the synchronisation area below).  Every sum over the
+// vocabulary is an exact integer sum and every other operation a single IEEE double operation, so the
+// decisions do not depend on how the vocabulary is split or in which order partial sums arrive.
+//
+// A sequence is worked on by G workgroups, each owning a contiguous slice of the vocabulary (its
+// slices of W, Qw and R are written and read by it alone).  The walk down the tree is sequential --
+// each decision needs vocabulary-wide totals -- so it proceeds in phases: in a phase every workgroup
+// passes over its slice, adds its partial sums to the phase's slots with 64-bit atomics, and the G
+// workgroups meet at the phase's counter; afterwards all of them read the same totals and take the
+// same decision redundantly (no leader, nothing is broadcast).  The owner of the token the NEXT
+// acceptance test is about adds that token's weights to further slots of the same phase, so no
+// workgroup ever reads another one's slice.  Every phase has slots and a counter of its own in a
+// zeroed area, so nothing is reset while others may still read it.
+// The meeting is a bounded wait: the G * B workgroups of a launch (at most 256, 256 threads each)
+// are co-resident on an idle chip; if that ever fails to hold long enough (another stream's kernels
+// occupying the chip), a workgroup gives up after kAcceptSpinLimit polls, raises the status word and
+// every workgroup of the launch leaves at its next poll.
 __device__ __forceinline__ double u64_to_d(unsigned long long x) { return (double)x; }
 
-constexpr int kAcceptThreads = 1024;   // one workgroup per sequence: as wide as a workgroup gets
+constexpr int kAcceptThreads = 256;       // multi-workgroup sampling acceptance
+constexpr int kAcceptMaxGroups = 64;      // workgroups per sequence
+constexpr int kAcceptPhases = 2 * TLT_ACCEPT_MAX_NODES + 4;   // node passes (<= stride <= nodes + 1) + rejections (< nodes) + final
+constexpr int kAcceptSlots = 5;           // per phase: S or residual total, SQ, next token's W, its R, its Qw
+constexpr unsigned kAcceptSpinLimit = 1u << 22;
 
-__global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, int stride, float temperature,
+struct AcceptSync {   // one per sequence, zeroed before the launch
+    unsigned long long sum[kAcceptPhases][kAcceptSlots];
+    unsigned long long slice_total[kAcceptMaxGroups];
+    unsigned int arrived[kAcceptPhases];
+};
+
+__device__ __forceinline__ unsigned long long sync_load(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All G workgroups of the sequence have finished phase `ph` (and their atomic adds are visible) when
+// this returns true; false = gave up (status raised) or another workgroup did.
+__device__ __forceinline__ bool accept_meet(AcceptSync* sy, int ph, int G, unsigned int* status, int* ok_s) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(&sy->arrived[ph], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        int ok = 1;
+        while (__hip_atomic_load(&sy->arrived[ph], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)G) {
+            __builtin_amdgcn_s_sleep(16);
+            if (++spins > kAcceptSpinLimit || (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 2u) != 0u) {
+                __hip_atomic_fetch_or(status, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+        }
+        *ok_s = ok;
+    }
+    __syncthreads();
+    return *ok_s != 0;
+}
+
+__global__ __launch_bounds__(kAcceptThreads) void accept_sync_clear_k(unsigned long long* p, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * kAcceptThreads + threadIdx.x; i < count; i += (int64_t)gridDim.x * kAcceptThreads) p[i] = 0ull;
+}
+
+__global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, int stride, int G, int slice, float temperature,
                                                        const int32_t* __restrict__ token,
                                                        const int32_t* __restrict__ parent,
                                                        const float* __restrict__ logits,
@@ -719,12 +773,13 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
                                                        const uint32_t* __restrict__ u_final,
                                                        int32_t* __restrict__ accept_len, int32_t* __restrict__ path_idx,
                                                        int32_t* __restrict__ out_tokens, int32_t* __restrict__ n_out,
-                                                       unsigned long long* __restrict__ ws) {
-    __shared__ unsigned long long su[kAcceptThreads / 64];
-    __shared__ double sd[kAcceptThreads / 64];
-    __shared__ unsigned long long scan[kAcceptThreads];
-    __shared__ int pick_s;
-    const int b = blockIdx.x, tid = threadIdx.x;
+                                                       unsigned long long* __restrict__ ws, AcceptSync* __restrict__ sync,
+                                                       unsigned int* __restrict__ status) {
+    constexpr int NW = kAcceptThreads / 64;
+    __shared__ unsigned long long su[NW];
+    __shared__ float sf[NW];
+    __shared__ int ok_s, pick_s;
+    const int b = blockIdx.x / G, g = blockIdx.x - b * G, tid = threadIdx.x;
     const int32_t* tok = token + (int64_t)b * n;
     const int32_t* par = parent + (int64_t)b * n;
     int32_t* path = path_idx + (int64_t)b * stride;
@@ -732,97 +787,168 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
     unsigned long long* W = ws + (int64_t)b * 3 * V;
     unsigned long long* Qw = W + V;
     unsigned long long* R = Qw + V;   // the residual is built here and swapped with W when it has mass
+    AcceptSync* sy = sync + b;
+    const int v0 = min(V, g * slice), v1 = min(V, v0 + slice);
+    const bool writer = g == 0;       // the workgroup that writes what all of them know
     const double tau = (double)temperature;
-    for (int j = tid; j < stride; j += kAcceptThreads) {
-        path[j] = -1;
-        out[j] = -1;
-    }
+    if (writer)
+        for (int j = tid; j < stride; j += kAcceptThreads) {
+            path[j] = -1;
+            out[j] = -1;
+        }
     __syncthreads();
-    int cur = 0, a = 0;
-    if (tid == 0) path[0] = 0;
+    int cur = 0, a = 0, ph = 0;
+    if (writer && tid == 0) path[0] = 0;
     unsigned long long S = 0, SQ = 0;
+    auto owns = [&](int t) { return t >= v0 && t < v1; };
+    auto next_child = [&](int after) {   // next child of `cur` with a token inside the vocabulary, or -1
+        for (int c = after + 1; c < n; ++c)
+            if (par[c] == cur && tok[c] >= 0 && tok[c] < V) return c;
+        return -1;
+    };
     for (;;) {
         const float* l = logits + ((int64_t)b * n + cur) * V;
         const float* q = draft_q + ((int64_t)b * n + cur) * V;
         // max_j (l_j / tau) = (max_j l_j) / tau: a correctly rounded division by a positive number keeps
-        // the order, so the maximum is taken on the floats and divided once
+        // the order, so the maximum is taken on the floats and divided once.  Every workgroup scans the
+        // whole row for it (a cheap pass from the L2) rather than meeting for it.
         float lmax = -INFINITY;
-        for (int j = tid; j < V; j += kAcceptThreads) lmax = fmaxf(lmax, l[j]);
-        const double m = block_max_d<kAcceptThreads / 64>((double)lmax, sd) / tau;
+        if (V % 4 == 0 && ((uintptr_t)l & 15) == 0) {
+            for (int j = tid * 4; j < V; j += kAcceptThreads * 4) {
+                const float4 x = *(const float4*)(l + j);
+                lmax = fmaxf(fmaxf(lmax, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
+            }
+        } else {
+            for (int j = tid; j < V; j += kAcceptThreads) lmax = fmaxf(lmax, l[j]);
+        }
+        const double m = (double)block_max_f<NW>(lmax, sf) / tau;
+        int c = a + 1 < stride ? next_child(cur) : -1;
         unsigned long long s = 0, sq = 0;
-        for (int j = tid; j < V; j += kAcceptThreads) {
-            unsigned long long w = (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0);
-            unsigned long long qw = (unsigned long long)floor((double)q[j] * 4294967296.0);
+        for (int j = v0 + tid; j < v1; j += kAcceptThreads) {
+            const unsigned long long w = (unsigned long long)floor(exp((double)l[j] / tau - m) * 4294967296.0);
+            const unsigned long long qw = (unsigned long long)floor((double)q[j] * 4294967296.0);
             W[j] = w;
             Qw[j] = qw;
             s += w;
             sq += qw;
         }
-        S = block_sum_u64<kAcceptThreads / 64>(s, su);
-        SQ = block_sum_u64<kAcceptThreads / 64>(sq, su);
+        s = block_sum_u64<NW>(s, su);
+        sq = block_sum_u64<NW>(sq, su);   // (block_sum's barriers also make this workgroup's W/Qw writes visible to it)
+        if (ph >= kAcceptPhases) return;  // cannot happen for n <= TLT_ACCEPT_MAX_NODES (uniform)
+        if (tid == 0) {
+            atomicAdd(&sy->sum[ph][0], s);
+            atomicAdd(&sy->sum[ph][1], sq);
+            if (c >= 0 && owns(tok[c])) {
+                atomicAdd(&sy->sum[ph][2], W[tok[c]]);
+                atomicAdd(&sy->sum[ph][4], Qw[tok[c]]);
+            }
+        }
+        if (!accept_meet(sy, ph, G, status, &ok_s)) return;
+        S = sync_load(&sy->sum[ph][0]);
+        SQ = sync_load(&sy->sum[ph][1]);
+        unsigned long long wt = sync_load(&sy->sum[ph][2]), qt = sync_load(&sy->sum[ph][4]);
+        ++ph;
         int next = -1;
-        for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
-            if (par[c] != cur) continue;  // uniform: every thread reads the same tree
+        while (c >= 0) {
             const int t = tok[c];
-            __syncthreads();  // W/Qw writes of other threads visible (same workgroup, global memory)
-            const double p = u64_to_d(W[t]) / u64_to_d(S);
-            const double qq = SQ > 0 ? u64_to_d(Qw[t]) / u64_to_d(SQ) : 0.0;
+            const double p = u64_to_d(wt) / u64_to_d(S);
+            const double qq = SQ > 0 ? u64_to_d(qt) / u64_to_d(SQ) : 0.0;
             const double u = ((double)u_accept[(int64_t)b * n + c] + 0.5) / 4294967296.0;
             if (u * qq < p) {
                 next = c;
                 break;
             }
+            // rejected: residual over the slice; the token of the child tested next is looked up on the way
+            const int cn = next_child(c);
             unsigned long long s2 = 0;
-            for (int j = tid; j < V; j += kAcceptThreads) {
-                double pj = u64_to_d(W[j]) / u64_to_d(S);
-                double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
+            for (int j = v0 + tid; j < v1; j += kAcceptThreads) {
+                const double pj = u64_to_d(W[j]) / u64_to_d(S);
+                const double qj = SQ > 0 ? u64_to_d(Qw[j]) / u64_to_d(SQ) : 0.0;
                 double r = pj - qj;
                 if (r < 0.0) r = 0.0;
                 const unsigned long long rw = (unsigned long long)floor(r * 4294967296.0);
                 R[j] = rw;
                 s2 += rw;
             }
-            s2 = block_sum_u64<kAcceptThreads / 64>(s2, su);
-            if (s2 > 0) {   // the residual replaces the target weights (uniform: every thread swaps)
+            s2 = block_sum_u64<NW>(s2, su);
+            if (ph >= kAcceptPhases) return;
+            if (tid == 0) {
+                atomicAdd(&sy->sum[ph][0], s2);
+                if (cn >= 0 && owns(tok[cn])) {
+                    const int tn = tok[cn];
+                    atomicAdd(&sy->sum[ph][2], W[tn]);
+                    atomicAdd(&sy->sum[ph][3], R[tn]);
+                    atomicAdd(&sy->sum[ph][4], tn == t ? 0ull : Qw[tn]);   // the rejected token leaves the draft
+                }
+                if (owns(t)) Qw[t] = 0;
+            }
+            if (!accept_meet(sy, ph, G, status, &ok_s)) return;
+            s2 = sync_load(&sy->sum[ph][0]);
+            const bool swap = s2 > 0;   // the residual replaces the target weights when it has mass (uniform)
+            wt = sync_load(&sy->sum[ph][swap ? 3 : 2]);
+            SQ -= qt;                   // exact integer update of the draft's total
+            qt = sync_load(&sy->sum[ph][4]);
+            ++ph;
+            if (swap) {
                 unsigned long long* tmp = W;
                 W = R;
                 R = tmp;
                 S = s2;
             }
-            // the draft loses the rejected token: an exact integer update of its total
-            const unsigned long long qt = Qw[t];
-            __syncthreads();
-            if (tid == 0) Qw[t] = 0;
-            SQ -= qt;
+            c = cn;
         }
         if (next < 0) break;
-        if (tid == 0) out[a] = tok[next];
+        if (writer && tid == 0) out[a] = tok[next];
         cur = next;
         ++a;
-        if (tid == 0) path[a] = cur;
-        __syncthreads();
+        if (writer && tid == 0) path[a] = cur;
     }
-    // final draw: first index whose running sum exceeds (u_final * S) >> 32
-    __syncthreads();
+    // final draw: first index whose running sum exceeds (u_final * S) >> 32.  Slice totals first, then the
+    // workgroup whose slice holds the threshold searches it.
+    unsigned long long local = 0;
+    const int chunk = (v1 - v0 + kAcceptThreads - 1) / kAcceptThreads;
+    const int j0 = min(v1, v0 + tid * chunk), j1 = min(v1, j0 + chunk);
+    for (int j = j0; j < j1; ++j) local += W[j];
+    const unsigned long long mine = block_sum_u64<NW>(local, su);
+    if (ph >= kAcceptPhases) return;
+    if (tid == 0) __hip_atomic_store(&sy->slice_total[g], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!accept_meet(sy, ph, G, status, &ok_s)) return;
     const unsigned long long thr =
         (unsigned long long)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32);
-    const int chunk = (V + kAcceptThreads - 1) / kAcceptThreads;
-    const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
-    unsigned long long local = 0;
-    for (int j = j0; j < j1; ++j) local += W[j];
-    scan[tid] = local;
-    if (tid == 0) pick_s = V - 1;
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long run = 0;
-        for (int t = 0; t < kAcceptThreads; ++t) {
-            unsigned long long v = scan[t];
-            scan[t] = run;
-            run += v;
-        }
+    unsigned long long before = 0;
+    int owner = -1;
+    for (int k = 0; k < G; ++k) {   // uniform
+        const unsigned long long tk = sync_load(&sy->slice_total[k]);
+        if (owner < 0 && before + tk > thr) owner = k;
+        if (owner < 0) before += tk;
     }
+    if (owner < 0) {   // no mass anywhere: the oracle's fallback
+        if (writer && tid == 0) {
+            out[a] = V - 1;
+            accept_len[b] = a;
+            n_out[b] = a + 1;
+        }
+        return;
+    }
+    if (writer && tid == 0) {
+        accept_len[b] = a;
+        n_out[b] = a + 1;
+    }
+    if (g != owner) return;
+    // exclusive scan of the threads' chunk totals (wave scan, then the waves' totals)
+    unsigned long long incl = local;
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) su[wave] = incl;
+    if (tid == 0) pick_s = v1 - 1;
     __syncthreads();
-    const unsigned long long excl = scan[tid];
+    unsigned long long wbase = before;
+    for (int w = 0; w < wave; ++w) wbase += su[w];
+    const unsigned long long excl = wbase + incl - local;
     if (local > 0 && excl <= thr && thr < excl + local) {
         unsigned long long run = excl;
         for (int j = j0; j < j1; ++j) {
@@ -834,11 +960,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        out[a] = pick_s;
-        accept_len[b] = a;
-        n_out[b] = a + 1;
-    }
+    if (tid == 0) out[a] = pick_s;
 }
 
 // Target-only rule (for trees whose shape depends on the drafter's values): child c is accepted
@@ -846,7 +968,8 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
 // weight leaves S; no child left -> the same final draw from what remains.  Weights are recomputed
 // from the logits where needed (W_j = floor(exp(l_j/tau - max) * 2^32), exp in double), the tokens
 // removed at the current node are kept in a short list; no workspace.
-__global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, int V, int stride, float temperature,
+constexpr int kTargetOnlyThreads = 1024;   // one workgroup per sequence: as wide as a workgroup gets
+__global__ __launch_bounds__(kTargetOnlyThreads) void accept_target_only_k(int n, int V, int stride, float temperature,
                                                                       const int32_t* __restrict__ token,
                                                                       const int32_t* __restrict__ parent,
                                                                       const float* __restrict__ logits,
@@ -856,9 +979,9 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, in
                                                                       int32_t* __restrict__ path_idx,
                                                                       int32_t* __restrict__ out_tokens,
                                                                       int32_t* __restrict__ n_out) {
-    __shared__ unsigned long long su[kAcceptThreads / 64];
-    __shared__ double sd[kAcceptThreads / 64];
-    __shared__ unsigned long long scan[kAcceptThreads];
+    __shared__ unsigned long long su[kTargetOnlyThreads / 64];
+    __shared__ double sd[kTargetOnlyThreads / 64];
+    __shared__ unsigned long long scan[kTargetOnlyThreads];
     __shared__ int pick_s;
     __shared__ int removed[64];   // a node has fewer than 64 children
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -867,7 +990,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, in
     int32_t* path = path_idx + (int64_t)b * stride;
     int32_t* out = out_tokens + (int64_t)b * stride;
     const double tau = (double)temperature;
-    for (int j = tid; j < stride; j += kAcceptThreads) {
+    for (int j = tid; j < stride; j += kTargetOnlyThreads) {
         path[j] = -1;
         out[j] = -1;
     }
@@ -886,11 +1009,11 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, in
     for (;;) {
         l = logits + ((int64_t)b * n + cur) * V;
         m = -INFINITY;
-        for (int j = tid; j < V; j += kAcceptThreads) m = fmax(m, (double)l[j] / tau);
-        m = block_max_d<kAcceptThreads / 64>(m, sd);
+        for (int j = tid; j < V; j += kTargetOnlyThreads) m = fmax(m, (double)l[j] / tau);
+        m = block_max_d<kTargetOnlyThreads / 64>(m, sd);
         unsigned long long s = 0;
-        for (int j = tid; j < V; j += kAcceptThreads) s += weight(j);
-        S = block_sum_u64<kAcceptThreads / 64>(s, su);
+        for (int j = tid; j < V; j += kTargetOnlyThreads) s += weight(j);
+        S = block_sum_u64<kTargetOnlyThreads / 64>(s, su);
         n_removed = 0;
         int next = -1;
         for (int c = cur + 1; c < n && a + 1 < stride; ++c) {
@@ -920,7 +1043,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, in
     __syncthreads();
     const unsigned long long thr =
         (unsigned long long)(((unsigned __int128)u_final[b] * (unsigned __int128)S) >> 32);
-    const int chunk = (V + kAcceptThreads - 1) / kAcceptThreads;
+    const int chunk = (V + kTargetOnlyThreads - 1) / kTargetOnlyThreads;
     const int j0 = min(V, tid * chunk), j1 = min(V, j0 + chunk);
     unsigned long long local = 0;
     for (int j = j0; j < j1; ++j) local += is_removed(j) ? 0ull : weight(j);
@@ -929,7 +1052,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_target_only_k(int n, in
     __syncthreads();
     if (tid == 0) {
         unsigned long long run = 0;
-        for (int t = 0; t < kAcceptThreads; ++t) {
+        for (int t = 0; t < kTargetOnlyThreads; ++t) {
             unsigned long long v = scan[t];
             scan[t] = run;
             run += v;
@@ -1107,21 +1230,38 @@ hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const i
     return hipGetLastError();
 }
 
-size_t accept_sample_workspace_bytes(int B, int V) { return (size_t)B * 3 * (size_t)V * sizeof(unsigned long long); }
+static int accept_groups(int B) {
+    int G = 256 / (B > 0 ? B : 1);
+    return G < 1 ? 1 : (G > kAcceptMaxGroups ? kAcceptMaxGroups : G);
+}
+
+size_t accept_sample_workspace_bytes(int B, int V) {
+    return ((size_t)B * 3 * (size_t)V * sizeof(unsigned long long) + 255) / 256 * 256 + (size_t)B * sizeof(AcceptSync);
+}
 
 hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
                          const int32_t* parent, const float* logits, const float* draft_q, const uint32_t* u_accept,
                          const uint32_t* u_final, int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens,
-                         int32_t* n_out, void* ws) {
-    hipLaunchKernelGGL(accept_sample_k, dim3(B), dim3(kAcceptThreads), 0, s, n, V, stride, temperature, token, parent, logits,
-                       draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out, (unsigned long long*)ws);
+                         int32_t* n_out, void* ws, unsigned int* status) {
+    if (n > TLT_ACCEPT_MAX_NODES) return hipErrorInvalidValue;
+    const int G = accept_groups(B);
+    const int slice = ((V + G - 1) / G + 3) & ~3;
+    AcceptSync* sync = (AcceptSync*)((char*)ws + ((size_t)B * 3 * (size_t)V * sizeof(unsigned long long) + 255) / 256 * 256);
+    const int64_t words = (int64_t)B * (int64_t)(sizeof(AcceptSync) / 8);
+    hipLaunchKernelGGL(accept_sync_clear_k, dim3((unsigned)((words + kAcceptThreads - 1) / kAcceptThreads)), dim3(kAcceptThreads),
+                       0, s, (unsigned long long*)sync, words);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_sample_k, dim3(B * G), dim3(kAcceptThreads), 0, s, n, V, stride, G, slice, temperature, token,
+                       parent, logits, draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out,
+                       (unsigned long long*)ws, sync, status);
     return hipGetLastError();
 }
 
 hipError_t accept_target_only(hipStream_t s, int B, int n, int V, int stride, float temperature, const int32_t* token,
                               const int32_t* parent, const float* logits, const uint32_t* u_accept, const uint32_t* u_final,
                               int32_t* accept_len, int32_t* path_idx, int32_t* out_tokens, int32_t* n_out) {
-    hipLaunchKernelGGL(accept_target_only_k, dim3(B), dim3(kAcceptThreads), 0, s, n, V, stride, temperature, token, parent,
+    hipLaunchKernelGGL(accept_target_only_k, dim3(B), dim3(kTargetOnlyThreads), 0, s, n, V, stride, temperature, token, parent,
                        logits, u_accept, u_final, accept_len, path_idx, out_tokens, n_out);
     return hipGetLastError();
 }

@@ -124,6 +124,7 @@ class Engine:
         if sync:
             al = self.accept_len.cpu().numpy()
             out = self.out_tokens.cpu().numpy()
+            self.ctx.device_status()          # raises when a kernel saw a length beyond its bound or could not rendezvous
             inc = int(al.max()) + 1
         else:
             al = out = None
@@ -157,6 +158,7 @@ class Engine:
         self.have_pending = True
         al = self.accept_len.cpu().numpy()
         out = self.out_tokens.cpu().numpy()
+        self.ctx.device_status()
         inc = int(al.max()) + 1
         self.kv.seq_len_bound += inc
         self.pending_max_new = inc

@@ -95,13 +95,17 @@ def test_sampling_accept_bit_exact(B, n, V, tau, k):
                     nxt += 1
     u_acc, u_fin = uniforms_u32((B, n), 11), uniforms_u32((B,), 12)
     stride = 6
-    want = oa.accept_sample(token, parent, logits, q, u_acc, u_fin, tau, stride)
+    *want, near = oa.accept_sample(token, parent, logits, q, u_acc, u_fin, tau, stride, with_near=True)
     assert want[0].max() >= 1
     print(f"sampling accept B={B} n={n} V={V}", flush=True)
     got = _run_accept(ctx, B, n, stride, 1, _tree_dev(token, parent), logits=_dev(logits), draft_q=_dev(q),
                       u_accept=_dev(u_acc), u_final=_dev(u_fin), temperature=tau)
-    for g, w in zip(got, want):
-        np.testing.assert_array_equal(g, w)
+    assert ctx.device_status() == 0
+    # bit for bit, except where the oracle itself says a decision sat within 8 units of 2^-32 of its
+    # threshold (a platform's last-bit `exp` can move a weight by one unit): those are reported
+    differ = oa.assert_equal_unless_near(got, want, near, "sampling accept")
+    print(f"  near-threshold sequences {int(near.sum())} of {B}, of which differing {len(differ)}", flush=True)
+    assert near.sum() <= max(1, B // 8)
     ctx.close()
 
 
@@ -154,12 +158,44 @@ def test_target_only_sampling_accept_bit_exact(B, n, V, tau, k):
                     nxt += 1
     u_acc, u_fin = uniforms_u32((B, n), 21), uniforms_u32((B,), 22)
     stride = 6
-    want = oa.accept_target_only(token, parent, logits, u_acc, u_fin, tau, stride)
+    *want, near = oa.accept_target_only(token, parent, logits, u_acc, u_fin, tau, stride, with_near=True)
     print(f"target-only accept B={B} n={n} V={V}: accept lengths up to {want[0].max()}", flush=True)
     got = _run_accept(ctx, B, n, stride, 2, _tree_dev(token, parent), logits=_dev(logits), u_accept=_dev(u_acc),
                       u_final=_dev(u_fin), temperature=tau)
+    differ = oa.assert_equal_unless_near(got, want, near, "target-only accept")
+    print(f"  near-threshold sequences {int(near.sum())} of {B}, of which differing {len(differ)}", flush=True)
+    assert near.sum() <= max(1, B // 8)
+    ctx.close()
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_sampling_accept_skips_children_whose_token_is_outside_the_vocabulary(mode):
+    """Caller-made trees may carry -1 or tokens >= V: both rules skip such a child (never accepted,
+    nothing else changes) instead of reading weights outside the row."""
+    B, n, V, tau, stride = 6, 9, 517, 0.9, 5
+    rng = np.random.default_rng(5)
+    cfg, ctx = _ctx(V, B, n)
+    logits = synthetic_logits((B, n, V), seed=4) * 2
+    q = np.exp(logits - logits.max(axis=-1, keepdims=True))
+    q = (q / q.sum(axis=-1, keepdims=True)).astype(np.float32)        # q = p: every in-range child is accepted
+    token = rng.integers(0, V, size=(B, n)).astype(np.int32)
+    parent = np.full((B, n), -1, dtype=np.int32)
+    parent[:, 1:] = (np.arange(1, n) - 1) // 2                         # binary tree
+    token[:, 1] = -1                                                   # the root's first child
+    token[:, 3] = V                                                    # node 1's first child
+    token[:, 5] = V + 1000
+    token[0, 2] = 2**31 - 1
+    u_acc, u_fin = uniforms_u32((B, n), 31), uniforms_u32((B,), 32)
+    if mode == 1:
+        want = oa.accept_sample(token, parent, logits, q, u_acc, u_fin, tau, stride)
+    else:
+        want = oa.accept_target_only(token, parent, logits, u_acc, u_fin, tau, stride)
+    got = _run_accept(ctx, B, n, stride, mode, _tree_dev(token, parent), logits=_dev(logits), draft_q=_dev(q),
+                      u_accept=_dev(u_acc), u_final=_dev(u_fin), temperature=tau)
     for g, w in zip(got, want):
         np.testing.assert_array_equal(g, w)
+    for b in range(B):
+        assert 1 not in got[1][b] and 3 not in got[1][b] and 5 not in got[1][b]
     ctx.close()
 
 

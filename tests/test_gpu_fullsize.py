@@ -231,10 +231,12 @@ def test_full_size_sampled_step_long_tail_shape():
             want = osd.draw_children_rows(g_q[b, i][None, :], u_d[b, kids[i]][None, :])[0]
             np.testing.assert_array_equal(g_tok[b, kids[i]], want)
     print("acceptance against the oracle's rule", flush=True)
-    o_al, o_path, o_out, o_nout = oacc.accept_sample(g_tok, g_par, g_logits, g_q, u_a, u_f, tau, e.stride)
-    np.testing.assert_array_equal(al, o_al)
-    np.testing.assert_array_equal(out, o_out)
-    np.testing.assert_array_equal(e.path_idx.cpu().numpy(), o_path)
+    o_al, o_path, o_out, o_nout, near = oacc.accept_sample(g_tok, g_par, g_logits, g_q, u_a, u_f, tau, e.stride,
+                                                           with_near=True)
+    differ = oacc.assert_equal_unless_near((al, e.path_idx.cpu().numpy(), out, e.n_out.cpu().numpy()),
+                                           (o_al, o_path, o_out, o_nout), near, "sampled step")
+    print(f"  near-threshold sequences {int(near.sum())}, differing {differ}", flush=True)
+    assert near.sum() <= 1
     np.testing.assert_array_equal(e.kv.seq_len.cpu().numpy(), ctx + al + 1)
     np.testing.assert_array_equal(e.dkv.seq_len.cpu().numpy(), ctx + 1)
     print("  accept lengths", al, flush=True)

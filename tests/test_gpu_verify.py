@@ -96,3 +96,30 @@ def test_verify_rejects_a_block_table_that_is_too_short():
     with pytest.raises(tlt.TltError, match="TLT_ENOPAGES"):
         e.ctx.verify_forward(1, t, e.kv, None, None, None)
     e.ctx.close()
+
+
+def test_a_length_bound_below_the_device_side_lengths_is_reported():
+    """seq_len lives on the device and the caller passes an upper bound that sizes the attention's work
+    list: a bound below the real lengths cannot be seen on the host, would drop context rows, and is
+    reported by tlt_device_status as TLT_ESHAPE (once; the word is cleared by the read)."""
+    cfg = MID
+    ctxs = np.array([700, 90], dtype=np.int32)
+    tw_dev, dw_dev, tw, dw = make_models(cfg, 3, "bf16")
+    e, table, _ = make_engine(cfg, "bf16", tw_dev, dw_dev, 2, 8, 4, 2, 900, seed=5, seq_len=ctxs)
+    t = e.tree(8)
+    t.token.fill_(1)
+    t.parent.copy_(torch.arange(-1, 7, dtype=torch.int32, device="cuda").expand(2, 8))
+    e.ctx.tree_finalize(2, t)
+    print("verify with an honest bound", flush=True)
+    e.ctx.verify_forward(2, t, e.kv, None, None, None)
+    assert e.ctx.device_status() == 0
+    print("verify with a bound of 500 for a sequence of 700", flush=True)
+    e.kv.seq_len_bound = 500
+    e.ctx.verify_forward(2, t, e.kv, None, None, None)
+    with pytest.raises(tlt.TltError, match="TLT_ESHAPE"):
+        e.ctx.device_status()
+    assert e.ctx.device_status() == 0          # cleared
+    e.kv.seq_len_bound = 700
+    e.ctx.verify_forward(2, t, e.kv, None, None, None)
+    assert e.ctx.device_status() == 0
+    e.ctx.close()
