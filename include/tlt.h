@@ -209,6 +209,21 @@ int tlt_accept(tlt_ctx *ctx, void *stream, int B, int mode, float temperature, c
                const uint32_t *u_accept, const uint32_t *u_final, int stride, int32_t *accept_len,
                int32_t *path_idx, int32_t *out_tokens, int32_t *n_out);
 
+/* tlt_accept's mode 1 for callers that cannot allocate device memory or provide a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no context; the integer
+ * weights and the rendezvous area live in a 16 MiB static device array inside the library (each GPU
+ * the library runs on holds it until the process ends).  Same arguments, outputs and arithmetic as
+ * tlt_accept(mode 1), plus `vocab` (no context to take it from).  Limit: B * vocab * 24 bytes plus
+ * 7 KB per sequence must fit in 16 MiB less 256 bytes (B = 4 at a vocabulary of 152064), else
+ * TLT_ESHAPE; tree->n <= 64.  status (DEVICE, may be NULL): word the caller has zeroed; bit 1
+ * (TLT_STATUS_NO_RENDEZVOUS) is raised as described at tlt_device_status.  Calls on one GPU share
+ * the array: calls that overlap in time (different streams) race; calls on one stream are ordered.
+ * Allocates nothing and calls no allocating routine. */
+int tlt_accept_sample_static(void *stream, int B, int vocab, float temperature, const tlt_tree *tree,
+                             const float *target_logits, const float *draft_q, const uint32_t *u_accept,
+                             const uint32_t *u_final, int stride, int32_t *accept_len, int32_t *path_idx,
+                             int32_t *out_tokens, int32_t *n_out, uint32_t *status);
+
 /* Keeps the accepted path: in every layer and kv head, row seq_len[b]+path_idx[b][j] moves to row
  * seq_len[b]+j for j <= accept_len[b]; then seq_len[b] += accept_len[b]+1 (the bonus token is not
  * cached: it is the next root).  kv->seq_len_bound is NOT updated (host field: the caller adds

@@ -26,7 +26,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status", "tlt_accept_sample_static",
 ]
 
 
@@ -93,6 +93,8 @@ def load() -> C.CDLL:
     lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 3
     lib.tlt_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 5 + \
         [C.c_int] + [C.c_void_p] * 4
+    lib.tlt_accept_sample_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 4 + \
+        [C.c_int] + [C.c_void_p] * 5
     lib.tlt_kv_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(KVC), C.c_void_p, C.c_void_p, C.c_int]
     lib.tlt_gemm.argtypes = [C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3
     lib.tlt_gemm_glu.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 4
@@ -308,6 +310,15 @@ class Context:
         self._check(self.lib.tlt_profile_read(self.handle, ms, n, fl, by), "tlt_profile_read")
         names = ("gemm", "attention", "kv_commit", "other", "gemm_draft", "attention_draft")
         return {k: {"ms": ms[i], "launches": n[i], "flops": fl[i], "bytes": by[i]} for i, k in enumerate(names)}
+
+
+def accept_sample_static(B, vocab, temperature, tree: Tree, target_logits, draft_q, u_accept, u_final, stride, accept_len,
+                         path_idx, out_tokens, n_out, status=None):
+    """tlt_accept_sample_static: sampling acceptance on the library's static scratch; returns the library's code."""
+    tc = tree.c()
+    return load().tlt_accept_sample_static(_stream(), B, vocab, temperature, C.byref(tc), _ptr(target_logits), _ptr(draft_q),
+                                           _ptr(u_accept), _ptr(u_final), stride, _ptr(accept_len), _ptr(path_idx),
+                                           _ptr(out_tokens), _ptr(n_out), _ptr(status))
 
 
 def template_build(topk: int, depth: int, n_verify: int):

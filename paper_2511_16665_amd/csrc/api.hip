@@ -749,6 +749,58 @@ int tlt_accept(tlt_ctx* ctx, void* stream, int B, int mode, float temperature, c
     return TLT_EINVAL;
 }
 
+// ---- sampling acceptance on the library's own static scratch (for callers that cannot allocate)
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (every GPU holds its own copy)
+
+// The array's name is a host-side stand-in, not a device address: the address is asked for once per
+// device, with that device current, and only that pointer is handed to kernels.
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+int tlt_accept_sample_static(void* stream, int B, int vocab, float temperature, const tlt_tree* tree,
+                             const float* target_logits, const float* draft_q, const uint32_t* u_accept,
+                             const uint32_t* u_final, int stride, int32_t* accept_len, int32_t* path_idx,
+                             int32_t* out_tokens, int32_t* n_out, uint32_t* status) {
+    if (B < 1 || vocab < 1 || !tree || !tree->token || !tree->parent || tree->n < 1 || tree->n > TLT_MAX_TREE || stride < 1 ||
+        !accept_len || !path_idx || !out_tokens || !n_out || !target_logits || !draft_q || !u_accept || !u_final ||
+        !(temperature > 0.f))
+        return TLT_EINVAL;
+    // weights and rendezvous area, then one status word of the library's own (used when the caller passes none)
+    const size_t need = accept_sample_workspace_bytes(B, vocab);
+    if (need + 256 > kStaticScratchBytes) return TLT_ESHAPE;
+    void* ptr = nullptr;
+    if (static_scratch(&ptr) != hipSuccess) return TLT_EHIP;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned int* st = status;
+    if (!st) {
+        st = (unsigned int*)((char*)ptr + kStaticScratchBytes - 256);
+        if (zero_f32(s, 64, (float*)st) != hipSuccess) return TLT_EHIP;
+    }
+    hipError_t e = accept_sample(s, B, tree->n, vocab, stride, temperature, tree->token, tree->parent, target_logits, draft_q,
+                                 u_accept, u_final, accept_len, path_idx, out_tokens, n_out, ptr, st);
+    return e == hipSuccess ? TLT_OK : TLT_EHIP;
+}
+
 int tlt_kv_commit(tlt_ctx* ctx, void* stream, int B, tlt_kv* kv, const int32_t* accept_len, const int32_t* path_idx,
                   int stride) {
     if (!ctx || B < 1 || !accept_len || !path_idx || stride < 1) return TLT_EINVAL;
