@@ -111,7 +111,7 @@ def check_draft_tree_against_forced_oracle(sd, cfg, tw, dw, st, root, K, D, N, g
     t_tok, t_par, t_dep, t_sc = (np.asarray(a) for a in g_tree)
     KK = K * K
     node_pool = match_tree_to_pool(p_tok, p_par, p_sc, t_tok, t_par, t_sc)
-    seen = {"choices": 0, "own": 0, "worst_slack": 0.0, "worst_score_err": 0.0}
+    seen = {"choices": 0, "own": 0, "worst_slack": -np.inf, "worst_score_err": 0.0}
     e_path = {-1: 0.0}          # pool index -> tolerance of its path score
     frontier = [-1]             # pool indices of the nodes whose children the next "children" calls rank
 
