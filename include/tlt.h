@@ -271,7 +271,8 @@ int tlt_set_oproj_rounding(tlt_ctx *ctx, int round_to_model_dtype);
  * verification forward, 1 its tree attention, 2 KV commit, 3 everything else, 4 the drafter's GEMMs,
  * 5 the drafter's attention.  tlt_profile_read synchronises the recorded events and returns, per
  * class, summed milliseconds, launches, algorithmic flops and algorithmic bytes since the last
- * tlt_profile_begin.  Arrays are HOST, TLT_PROFILE_CLASSES entries each. */
+ * tlt_profile_begin(ctx, 1).  enable: 1 = start afresh, 2 = resume (records kept), 0 = pause (records kept
+ * until the next read or fresh start).  Arrays are HOST, TLT_PROFILE_CLASSES entries each. */
 enum { TLT_PROFILE_CLASSES = 6 };
 int tlt_profile_begin(tlt_ctx *ctx, int enable);
 int tlt_profile_read(tlt_ctx *ctx, double *ms, int64_t *launches, double *flops, double *bytes);

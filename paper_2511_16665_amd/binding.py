@@ -303,6 +303,7 @@ class Context:
         self._check(self.lib.tlt_set_oproj_rounding(self.handle, int(round_to_model_dtype)), "tlt_set_oproj_rounding")
 
     def profile_begin(self, enable=True):
+        """enable: True/1 = start afresh, 2 = resume without dropping records, False/0 = pause."""
         self._check(self.lib.tlt_profile_begin(self.handle, int(enable)), "tlt_profile_begin")
 
     def profile_read(self):

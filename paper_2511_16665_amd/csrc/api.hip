@@ -840,7 +840,7 @@ int tlt_gemm(void* stream, int dtype, int out_mode, int M, int N, int K, const v
 int tlt_profile_begin(tlt_ctx* ctx, int enable) {
     if (!ctx) return TLT_EINVAL;
     ctx->prof_on = enable != 0;
-    ctx->recs.clear();
+    if (enable == 1) ctx->recs.clear();
     return TLT_OK;
 }
 
