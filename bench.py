@@ -447,6 +447,69 @@ def kv_commit_stress(args):
                                              "layer and kv head (256-byte rows, sources at every other slot)"}}))
 
 
+def attention_only(args):
+    """The tree-attention kernel on its own (tlt_attention) at a workload's shape: batch, contexts, page
+    tables and tree size as in the step, queries and cache N(0,1), chain-free random trees.  Two layers'
+    pools are used in turn so that no launch finds its keys and values in a cache from the launch before.
+    One JSON line: time per launch (HIP events on the launch stream), achieved HBM rate on the algorithmic
+    bytes (one pass over every sequence's cached keys and values) and the matrix rate of the same launches
+    (4 * d * Hq * n flops per cached token)."""
+    import torch
+
+    from paper_2511_16665_amd import binding as tlt
+    from synth import QWEN7B, QWEN32B, MID, fill_kv_pool, lognormal_contexts, random_block_table
+    cfg = {"7b": QWEN7B, "32b": QWEN32B, "mid": MID}[args.model]
+    B, n = args.batch, args.verify
+    if args.ctx_lo:
+        ctx = np.random.default_rng(0).integers(args.ctx_lo, args.ctx_cap + 1, size=B).astype(np.int32)
+    else:
+        ctx = lognormal_contexts(B, args.ctx_median, 0.8, args.ctx_cap, min(256, args.ctx_median), seed=0)
+    table, n_pages = random_block_table(ctx + n + 64, cfg.page_size, seed=1, extra_pages=8)
+    pools = [fill_kv_pool(1, n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim, 3 + l, "cuda", torch.bfloat16) for l in range(2)]
+    g = torch.Generator(device="cuda").manual_seed(5)
+    qkv = torch.randn((B, n, cfg.qkv_dim), generator=g, device="cuda").bfloat16()
+    rng = np.random.default_rng(1)
+    parent = np.full((B, n), -1, dtype=np.int64)
+    mask = np.zeros((B, n), dtype=np.uint64)
+    for b in range(B):
+        for i in range(n):
+            if i > 0:
+                parent[b, i] = rng.integers(max(0, i - 6), i)
+            mask[b, i] = (mask[b, parent[b, i]] if i > 0 else np.uint64(0)) | np.uint64(1 << i)
+    anc = torch.from_numpy(mask.view(np.int64)).cuda()
+    tbl = torch.from_numpy(table.astype(np.int32)).cuda()
+    sl = torch.from_numpy(ctx.astype(np.int32)).cuda()
+    kvs = [tlt.KV(k[0], v[0], tbl, sl, int(ctx.max())) for k, v in pools]
+    out = torch.zeros((B, n, cfg.q_dim), dtype=torch.bfloat16, device="cuda")
+    ws = tlt.attention_workspace(B, n, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, int(ctx.max()) + n + 64)
+
+    def launch(i):
+        rc = tlt.attention(tlt.TLT_BF16, cfg.n_q_heads, cfg.page_size, qkv, anc, kvs[i & 1], out, ws, args.attn_impl)
+        assert rc == 0, tlt.ERRORS.get(rc, rc)
+
+    for i in range(args.warmup + 1):
+        launch(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for i in range(args.steps):
+        launch(i)
+    ev[1].record()
+    torch.cuda.synchronize()
+    us = ev[0].elapsed_time(ev[1]) / args.steps * 1e3
+    tokens = float(ctx.sum() + B * n)
+    nbytes = tokens * 2 * cfg.n_kv_heads * cfg.head_dim * 2
+    flops = 4.0 * cfg.head_dim * cfg.n_q_heads * n * tokens
+    print(json.dumps({"metric": "tlt_attention (plan + main + combine kernels) per launch", "value": round(us, 2), "unit": "us",
+                      "higher_is_better": False,
+                      "roofline": {"bound": "hbm", "achieved": round(nbytes / us / 1e3, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4), "bytes_per_launch": nbytes,
+                                   "mfma_tflops": round(flops / us / 1e6, 1), "mfma_frac": round(flops / us / 1e6 / PEAK_BF16_TFLOPS, 4)},
+                      "config": {"workload": f"{cfg.name} attention shape ({cfg.n_q_heads} query / {cfg.n_kv_heads} kv heads, head "
+                                             f"dim {cfg.head_dim}), batch {B}, {int(ctx.sum())} cached tokens, {n} tree rows per "
+                                             f"sequence = {n * cfg.group} query rows per cached key"}}))
+
+
 def measured_ceilings(cfg, M):
     """What this machine delivers to plain kernels, in the same run: a device-to-device copy (HBM read +
     write) and the vendor library's bf16 GEMM (torch.matmul) on the verification forward's gate/up
@@ -549,6 +612,9 @@ def main():
                     help="instead of the benchmark line: the strategy sweep (batch x tree nodes at context 8192)")
     ap.add_argument("--kv-commit-stress", action="store_true",
                     help="instead of the benchmark line: the HBM rate of tlt_kv_commit on a shape that is not launch-bound")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="instead of the benchmark line: the tree-attention kernel alone at the workload's shape")
+    ap.add_argument("--attn-impl", type=int, default=-1)
     ap.add_argument("--grid-batches", type=int, nargs="+", default=[1, 4, 16, 64, 128])
     ap.add_argument("--grid-nodes", type=int, nargs="+", default=[1, 8, 16, 32, 64])
     args = ap.parse_args()
@@ -564,6 +630,8 @@ def main():
         return strategy_grid(args)
     if args.kv_commit_stress:
         return kv_commit_stress(args)
+    if args.attention_only:
+        return attention_only(args)
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 

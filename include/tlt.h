@@ -249,6 +249,18 @@ int tlt_gemm_glu(void *stream, int M, int N, int K, const void *A, const void *W
 int tlt_gemm_argmax(void *stream, int M, int N, int K, const void *A, const void *W, void *ws, size_t ws_bytes,
                     int32_t *out);
 
+/* The tree attention of one decoder block on its own (Section 2.2: every tree node attends to the
+ * committed context and to its ancestors-or-self).  qkv [B][n][(Hq+2Hkv)*d] in dtype holds the rotated
+ * queries (the key/value part is not read: the tree's keys and values must already sit in the cache at
+ * slots seq_len[b] + i); kv describes ONE layer's pools [n_pages][Hkv][page_size][d]; anc_mask [B][n];
+ * out [B][n][Hq*d] in dtype.  ws: DEVICE scratch of tlt_attention_workspace_bytes(...) bytes for the
+ * bound max_ctx >= kv->seq_len_bound + n.  impl as in tlt_set_attention_impl.  TLT_ESHAPE when the
+ * explicitly requested kernel does not cover the shape or the scratch is too small. */
+size_t tlt_attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int head_dim, int max_ctx);
+int tlt_attention(void *stream, int dtype, int B, int n, int n_q_heads, int n_kv_heads, int head_dim, int page_size,
+                  const void *qkv, const uint64_t *anc_mask, const tlt_kv *kv, void *out, void *ws, size_t ws_bytes,
+                  int impl);
+
 /* Attention kernel choice for cross-checks: -1 automatic (default), 0 wave-per-row kernel,
  * 1 MFMA split-KV kernel (bf16, head_dim 128 only; other shapes fall back to 0). */
 int tlt_set_attention_impl(tlt_ctx *ctx, int impl);

@@ -26,7 +26,7 @@ EXPORTS = [
     "tlt_tree_finalize", "tlt_verify_forward", "tlt_accept", "tlt_kv_commit", "tlt_gemm", "tlt_set_attention_impl",
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
-    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status", "tlt_accept_sample_static",
+    "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status", "tlt_accept_sample_static", "tlt_attention", "tlt_attention_workspace_bytes",
 ]
 
 
@@ -100,6 +100,10 @@ def load() -> C.CDLL:
     lib.tlt_gemm_glu.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 4
     lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
+    lib.tlt_attention_workspace_bytes.restype = C.c_size_t
+    lib.tlt_attention_workspace_bytes.argtypes = [C.c_int] * 6
+    lib.tlt_attention.argtypes = [C.c_void_p] + [C.c_int] * 7 + [C.c_void_p, C.c_void_p, C.POINTER(KVC), C.c_void_p, C.c_void_p,
+                                                               C.c_size_t, C.c_int]
     lib.tlt_set_oproj_rounding.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_device_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
     lib.tlt_profile_begin.argtypes = [C.c_void_p, C.c_int]
@@ -427,6 +431,23 @@ def gemm(dtype_code, out_mode, A, W, Cout):
     rc = load().tlt_gemm(_stream(), dtype_code, out_mode, M, N, K, _ptr(A), _ptr(W), _ptr(Cout))
     if rc:
         raise TltError(rc, "tlt_gemm")
+
+
+def attention_workspace(B, n, n_q_heads, n_kv_heads, head_dim, max_ctx) -> torch.Tensor:
+    nbytes = load().tlt_attention_workspace_bytes(B, n, n_q_heads, n_kv_heads, head_dim, max_ctx)
+    if nbytes == 0:
+        raise TltError(-1, "tlt_attention_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+
+def attention(dtype_code, n_q_heads, page_size, qkv, anc_mask, kv: KV, out, ws, impl=-1):
+    """tlt_attention on one layer's pools [n_pages, Hkv, page, d]; qkv [B, n, (Hq+2Hkv)*d]; returns the code."""
+    B, n = qkv.shape[0], qkv.shape[1]
+    n_kv, d = kv.k_pool.shape[-3], kv.k_pool.shape[-1]
+    kvc = KVC(_ptr(kv.k_pool), _ptr(kv.v_pool), kv.k_pool.shape[-4], _ptr(kv.block_table), _ptr(kv.seq_len),
+              kv.block_table.shape[1], int(kv.seq_len_bound))
+    return load().tlt_attention(_stream(), dtype_code, B, n, n_q_heads, n_kv, d, page_size, _ptr(qkv), _ptr(anc_mask),
+                                C.byref(kvc), _ptr(out), _ptr(ws), ws.numel(), impl)
 
 
 def gemm_argmax(A, W, ws, out):

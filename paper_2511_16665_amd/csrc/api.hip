@@ -817,6 +817,42 @@ int tlt_kv_commit(tlt_ctx* ctx, void* stream, int B, tlt_kv* kv, const int32_t* 
     return TLT_OK;
 }
 
+size_t tlt_attention_workspace_bytes(int B, int n, int n_q_heads, int n_kv_heads, int head_dim, int max_ctx) {
+    if (B < 1 || n < 1 || n > TLT_MAX_TREE || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || max_ctx < 1) return 0;
+    return attention_workspace_bytes(B, n, n_q_heads, n_kv_heads, head_dim, max_ctx);
+}
+
+int tlt_attention(void* stream, int dtype, int B, int n, int n_q_heads, int n_kv_heads, int head_dim, int page_size,
+                  const void* qkv, const uint64_t* anc_mask, const tlt_kv* kv, void* out, void* ws, size_t ws_bytes, int impl) {
+    if (B < 1 || n < 1 || n > TLT_MAX_TREE || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || head_dim < 64 ||
+        head_dim % 64 || head_dim > 256 || page_size < 1 || (dtype != TLT_F32 && dtype != TLT_BF16) || !qkv || !anc_mask || !out ||
+        !ws)
+        return TLT_EINVAL;
+    if (!kv || !kv->k_pool || !kv->v_pool || !kv->block_table || !kv->seq_len || kv->n_pages < 1 || kv->max_pages < 1 ||
+        kv->seq_len_bound < 0)
+        return TLT_EINVAL;
+    if ((int64_t)kv->seq_len_bound + n > (int64_t)kv->max_pages * page_size) return TLT_ENOPAGES;
+    Rows rows;
+    rows.B = B;
+    rows.n = n;
+    rows.mask = anc_mask;
+    rows.mask_words = 1;
+    rows.n_region = n;
+    KVLayer k;
+    k.k = kv->k_pool;
+    k.v = kv->v_pool;
+    k.n_pages = kv->n_pages;
+    k.block_table = kv->block_table;
+    k.seq_len = kv->seq_len;
+    k.max_pages = kv->max_pages;
+    k.page_size = page_size;
+    k.n_kv = n_kv_heads;
+    k.d = head_dim;
+    k.seq_len_bound = kv->seq_len_bound;
+    hipError_t e = attention((hipStream_t)stream, dtype, rows, k, qkv, out, n_q_heads, ws, ws_bytes, impl);
+    return e == hipSuccess ? TLT_OK : (e == hipErrorInvalidValue ? TLT_ESHAPE : TLT_EHIP);
+}
+
 int tlt_gemm_glu(void* stream, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
     if (M < 1 || N < 1 || K < 1 || !A || !Wg || !Wu || !act) return TLT_EINVAL;
     if (!gemm_glu_supported(TLT_BF16, M, N, K, A, Wg, Wu)) return TLT_ENOTIMPL;
