@@ -447,6 +447,179 @@ def kv_commit_stress(args):
                                              "layer and kv head (256-byte rows, sources at every other slot)"}}))
 
 
+class StandIn:
+    """One SD step at a time for the first Bk slots of an engine, with the stand-in for a trained drafter
+    (see fixed_acceptance_steps): the real drafter's expansion is run and timed, the verified tree is the
+    static template labelled so that a node's first child carries the target's greedy token with
+    probability alpha; plain decoding (one node) for comparison.  Times are HIP-event times of the timed
+    calls only."""
+
+    def __init__(self, cfg, e, alpha, seed=17):
+        import torch
+        self.cfg, self.e, self.alpha = cfg, e, alpha
+        self.gen = torch.Generator(device="cuda").manual_seed(seed)
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        self.templates = {}
+
+    def _template(self, K, D, N):
+        import torch
+
+        from paper_2511_16665_amd import binding as tlt
+        key = (K, D, N)
+        if key not in self.templates:
+            par, rank, dep = tlt.template_build(K, D, N)
+            n = len(par)
+            ts = tlt.Tree.empty(self.e.B, n)
+            ts.parent.copy_(torch.from_numpy(par).cuda().expand(self.e.B, n))
+            self.e.ctx.tree_finalize(self.e.B, ts)
+            self.templates[key] = (ts, torch.from_numpy(dep.astype(np.int64)).cuda().expand(self.e.B, n),
+                                   torch.from_numpy(rank == 0).cuda().expand(self.e.B, n), int(dep.max()))
+        return self.templates[key]
+
+    def reset_drafter(self, Bk):
+        """Fresh drafter bookkeeping for the first Bk slots (after steps that did not run the drafter)."""
+        import torch
+        e, cfg = self.e, self.cfg
+        e.set_pending(torch.randint(0, cfg.vocab, (e.B, 1), generator=self.gen, device="cuda", dtype=torch.int32),
+                      torch.zeros((e.B, 1), dtype=torch.int32, device="cuda"), torch.ones((e.B,), dtype=torch.int32, device="cuda"),
+                      torch.randn((e.B, 1, cfg.hidden), generator=self.gen, device="cuda", dtype=torch.float32), 1)
+
+    def plain_step(self, Bk):
+        """Plain decoding of the first Bk sequences: one node per sequence.  Returns (ms, accept_lens)."""
+        import torch
+        e = self.e
+        t = e.tree(1)
+        t.token.copy_(torch.randint(0, self.cfg.vocab, (e.B, 1), generator=self.gen, device="cuda", dtype=torch.int32))
+        t.parent.fill_(-1)
+        e.ctx.tree_finalize(e.B, t)
+        am = e._buf("am", 1)
+        self.ev[0].record()
+        e.ctx.verify_forward(Bk, t, e.kv, out_logits=None, out_argmax=am, out_hidden=None)
+        e.ctx.accept(Bk, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+        e.ctx.kv_commit(Bk, e.kv, e.accept_len, e.path_idx, e.stride)
+        self.ev[1].record()
+        torch.cuda.synchronize()
+        e.kv.seq_len_bound += 1
+        e.have_pending = False
+        return self.ev[0].elapsed_time(self.ev[1]), [0] * Bk
+
+    def sd_step(self, Bk, K, D, N):
+        """One SD step of strategy (Draft_Depth D, topK K, Tokens_to_Verify N) for the first Bk sequences.
+        Returns (ms of draft_expand + verify_forward + accept + kv_commit, accept_lens)."""
+        import torch
+        e, cfg = self.e, self.cfg
+        if not e.have_pending:
+            self.reset_drafter(Bk)
+        pool = K + (D - 1) * K * K if D >= 1 else 0
+        t = e.tree(min(N, 1 + pool))                       # the drafter's own tree (discarded)
+        ts, depth, first_child, levels = self._template(K, D, N)
+        n = ts.n
+        hid, am = e._buf("hid", n), e._buf("am", n)
+        parent = ts.parent.long()
+        self.ev[0].record()
+        e.ctx.draft_expand(Bk, D, K, N, e.out_tokens, e.path_idx, e.n_out, e.pending_hidden, None, e.dkv, t)
+        self.ev[1].record()
+        e.dkv.seq_len_bound += e.pending_max_new
+        hit = first_child & (torch.rand((e.B, n), generator=self.gen, device="cuda") < self.alpha)
+        rnd = torch.randint(0, cfg.vocab, (e.B, n), generator=self.gen, device="cuda", dtype=torch.int32)
+        ts.token.copy_(rnd)
+        ts.token[:, 0] = t.token[:, 0]
+        for d in range(levels):
+            e.ctx.verify_forward(Bk, ts, e.kv, out_logits=None, out_argmax=am, out_hidden=None)
+            level = depth == d + 1
+            from_parent = torch.gather(am, 1, parent.clamp(min=0)).to(torch.int32)
+            other = torch.where(rnd == from_parent, (rnd + 1) % cfg.vocab, rnd)
+            ts.token.copy_(torch.where(level, torch.where(hit, from_parent, other), ts.token))
+        self.ev[2].record()
+        e.ctx.verify_forward(Bk, ts, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
+        e.ctx.accept(Bk, 0, 1.0, ts, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+        e.ctx.kv_commit(Bk, e.kv, e.accept_len, e.path_idx, e.stride)
+        self.ev[3].record()
+        torch.cuda.synchronize()
+        e.pending_hidden, e.have_pending = hid, True
+        al = e.accept_len[:Bk].cpu().numpy()
+        inc = int(al.max()) + 1
+        e.kv.seq_len_bound += inc
+        e.pending_max_new = inc
+        return self.ev[0].elapsed_time(self.ev[1]) + self.ev[2].elapsed_time(self.ev[3]), [int(a) for a in al]
+
+
+def adaptive_rollout(args, model="7b", phases=(128, 64, 32, 16, 8, 4, 2, 1), steps_sd=24, steps_off=4, context=8192,
+                     strategies=None, thresholds=(1, 2, 8, 16), epsilon=0.1, window=8, sd_threshold=32, seed=3, trace=None):
+    """The adaptive engine's loop on measured steps (Algorithm 1 with the elastic rule of Section 5.1): the
+    running batch of one rollout shrinks phase by phase; every step the selector (tlt_mab_select) picks
+    a strategy for the current batch size or keeps speculation off (batch >= sd_threshold), the step is
+    run and timed, and its elapsed time and accept lengths are fed back (tlt_mab_record).  Per phase the
+    selector's throughput is compared with every fixed strategy and with plain decoding, each measured
+    in the same run on the same state.  `trace` (a list) receives one record per selector step:
+    (batch, u1, u2, choice, elapsed seconds, accept_lens)."""
+    import copy
+
+    import torch
+
+    from paper_2511_16665_amd import binding as tlt
+    if strategies is None:      # (Draft_Depth, topK, Tokens_to_Verify): two shapes per tree size
+        strategies = [(8, 8, 64), (4, 4, 64), (8, 8, 32), (4, 4, 32), (8, 8, 16), (4, 4, 16), (7, 8, 8), (3, 2, 8)]
+    a = copy.copy(args)
+    a.model, a.batch, a.verify, a.depth, a.topk = model, max(phases), 64, 8, 8
+    n_steps = sum(steps_off if B >= sd_threshold else steps_sd + 3 * len(strategies) + 3 for B in phases)
+    a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = context, context, n_steps, 2, True
+    cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a)
+    run = StandIn(cfg, e, args.alpha)
+    mab = tlt.Mab(strategies, list(thresholds), epsilon, window, sd_threshold)
+    rng = np.random.default_rng(seed)
+    out = []
+    for B in phases:
+        rec = {"batch": B}
+        if B >= sd_threshold:
+            ms = [run.plain_step(B)[0] for _ in range(steps_off)]
+            for _ in range(steps_off):
+                u1, u2 = int(rng.integers(2 ** 32)), int(rng.integers(2 ** 32))
+                assert mab.select(B, u1, u2) is None
+                if trace is not None:
+                    trace.append((B, u1, u2, None, 0.0, []))
+            rec.update({"speculation": "off", "ms_per_step": round(float(np.mean(ms[1:])), 3),
+                        "value": round(B / (np.mean(ms[1:]) * 1e-3), 1)})
+            out.append(rec)
+            print(json.dumps(rec), file=sys.stderr, flush=True)
+            continue
+        # baselines on the same state: plain decoding, then every fixed strategy
+        ms = [run.plain_step(B)[0] for _ in range(3)]
+        rec["no_sd"] = round(B / (np.mean(ms[1:]) * 1e-3), 1)
+        fixed = {}
+        for (D, K, N) in strategies:
+            r = [run.sd_step(B, K, D, N) for _ in range(3)]
+            fixed[f"D{D}K{K}N{N}"] = round(sum(sum(al) + B for _, al in r[1:]) / (sum(m for m, _ in r[1:]) * 1e-3), 1)
+        rec["fixed"] = fixed
+        rec["best_fixed"] = max(fixed, key=fixed.get)
+        # the selector
+        emitted, total_ms, chosen = 0, 0.0, {}
+        for _ in range(steps_sd):
+            u1, u2 = int(rng.integers(2 ** 32)), int(rng.integers(2 ** 32))
+            si = mab.select(B, u1, u2)
+            D, K, N = strategies[si]
+            ms_step, al = run.sd_step(B, K, D, N)
+            mab.record(si, ms_step * 1e-3, al, B)
+            if trace is not None:
+                trace.append((B, u1, u2, si, ms_step * 1e-3, al))
+            emitted += sum(al) + B
+            total_ms += ms_step
+            chosen[f"D{D}K{K}N{N}"] = chosen.get(f"D{D}K{K}N{N}", 0) + 1
+        rec.update({"speculation": "on", "adaptive": round(emitted / (total_ms * 1e-3), 1), "chosen": chosen,
+                    "adaptive_vs_best_fixed": round(emitted / (total_ms * 1e-3) / fixed[rec["best_fixed"]], 3),
+                    "adaptive_vs_no_sd": round(emitted / (total_ms * 1e-3) / rec["no_sd"], 3)})
+        out.append(rec)
+        print(json.dumps(rec), file=sys.stderr, flush=True)
+    mab.close()
+    e.ctx.close()
+    return {"metric": "adaptive rollout: accepted tokens/s per phase (selector vs fixed strategies vs plain decoding)",
+            "unit": "accepted tokens/s", "alpha": args.alpha, "context": context, "epsilon": epsilon, "window": window,
+            "sd_threshold": sd_threshold, "thresholds": list(thresholds), "strategies": [list(s) for s in strategies],
+            "steps_per_sd_phase": steps_sd, "phases": out,
+            "note": "drafter stand-in with fixed first-child acceptance (see fixed_acceptance_steps); the drafter's re-activation "
+                    "when speculation switches on (Engine.activate_drafter) is not part of the timed steps"}
+
+
 def attention_only(args):
     """The tree-attention kernel on its own (tlt_attention) at a workload's shape: batch, contexts, page
     tables and tree size as in the step, queries and cache N(0,1), chain-free random trees.  Two layers'
@@ -612,6 +785,9 @@ def main():
                     help="instead of the benchmark line: the strategy sweep (batch x tree nodes at context 8192)")
     ap.add_argument("--kv-commit-stress", action="store_true",
                     help="instead of the benchmark line: the HBM rate of tlt_kv_commit on a shape that is not launch-bound")
+    ap.add_argument("--adaptive", action="store_true",
+                    help="instead of the benchmark line: a rollout whose running batch shrinks from 128 to 1 with the strategy "
+                         "selector choosing the step's strategy from measured rewards")
     ap.add_argument("--attention-only", action="store_true",
                     help="instead of the benchmark line: the tree-attention kernel alone at the workload's shape")
     ap.add_argument("--attn-impl", type=int, default=-1)
@@ -632,6 +808,9 @@ def main():
         return kv_commit_stress(args)
     if args.attention_only:
         return attention_only(args)
+    if args.adaptive:
+        print(json.dumps(adaptive_rollout(args)))
+        return
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 
