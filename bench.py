@@ -545,7 +545,7 @@ class StandIn:
 
 
 def adaptive_rollout(args, model="7b", phases=(128, 64, 32, 16, 8, 4, 2, 1), steps_sd=24, steps_off=4, context=8192,
-                     strategies=None, thresholds=(1, 2, 8, 16), epsilon=0.1, window=8, sd_threshold=32, seed=3, trace=None):
+                     strategies=None, thresholds=(1, 2, 3, 8), epsilon=0.1, window=8, sd_threshold=32, seed=3, trace=None):
     """The adaptive engine's loop on measured steps (Algorithm 1 with the elastic rule of Section 5.1): the
     running batch of one rollout shrinks phase by phase; every step the selector (tlt_mab_select) picks
     a strategy for the current batch size or keeps speculation off (batch >= sd_threshold), the step is
@@ -562,7 +562,7 @@ def adaptive_rollout(args, model="7b", phases=(128, 64, 32, 16, 8, 4, 2, 1), ste
         strategies = [(8, 8, 64), (4, 4, 64), (8, 8, 32), (4, 4, 32), (8, 8, 16), (4, 4, 16), (7, 8, 8), (3, 2, 8)]
     a = copy.copy(args)
     a.model, a.batch, a.verify, a.depth, a.topk = model, max(phases), 64, 8, 8
-    n_steps = sum(steps_off if B >= sd_threshold else steps_sd + 3 * len(strategies) + 3 for B in phases)
+    n_steps = sum(steps_off if B >= sd_threshold else steps_sd + (max(3, -(-16 // B) + 1)) * len(strategies) + 3 for B in phases)
     a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = context, context, n_steps, 2, True
     cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a)
     run = StandIn(cfg, e, args.alpha)
@@ -587,8 +587,9 @@ def adaptive_rollout(args, model="7b", phases=(128, 64, 32, 16, 8, 4, 2, 1), ste
         ms = [run.plain_step(B)[0] for _ in range(3)]
         rec["no_sd"] = round(B / (np.mean(ms[1:]) * 1e-3), 1)
         fixed = {}
+        n_base = max(3, -(-16 // B) + 1)            # (few sequences: more steps for a mean accept length)
         for (D, K, N) in strategies:
-            r = [run.sd_step(B, K, D, N) for _ in range(3)]
+            r = [run.sd_step(B, K, D, N) for _ in range(n_base)]
             fixed[f"D{D}K{K}N{N}"] = round(sum(sum(al) + B for _, al in r[1:]) / (sum(m for m, _ in r[1:]) * 1e-3), 1)
         rec["fixed"] = fixed
         rec["best_fixed"] = max(fixed, key=fixed.get)

@@ -182,9 +182,13 @@ int tlt_tree_finalize(tlt_ctx *ctx, void *stream, int B, tlt_tree *tree);
  * seq_len[b] committed tokens and to its ancestors-or-self, with rotary position seq_len[b] +
  * depth[i]; its key/value are written to provisional slot seq_len[b] + i.  seq_len is unchanged.
  * Outputs (DEVICE, any may be NULL): out_logits [B][n][V] fp32; out_argmax [B][n] (lowest index on
- * ties); out_hidden [B][n][h] fp32 = last block's output before the final norm. */
+ * ties); out_lse [B][n][2] fp32 = (largest logit, log-sum-exp of the row), from which the target's
+ * log-probability of any token follows as logit - out_lse[..][1]; out_hidden [B][n][h] fp32 = last
+ * block's output before the final norm.  When only out_argmax is asked for, the logits are never
+ * written (the LM head's epilogue reduces them); out_lse without out_logits materialises them in the
+ * workspace. */
 int tlt_verify_forward(tlt_ctx *ctx, void *stream, int B, const tlt_tree *tree, tlt_kv *kv, float *out_logits,
-                       int32_t *out_argmax, float *out_hidden);
+                       int32_t *out_argmax, float *out_lse, float *out_hidden);
 
 /* Lossless acceptance (Section 2.2: keep the drafted prefix up to the first disagreement plus the
  * target's own token; Section 1 / Section 3 principle (a): output distributed exactly as the

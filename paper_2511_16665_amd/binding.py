@@ -90,7 +90,7 @@ def load() -> C.CDLL:
     lib.tlt_draft_sample.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 3 + \
         [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(KVC), C.c_void_p, C.POINTER(TreeC), C.c_void_p]
     lib.tlt_tree_finalize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC)]
-    lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 3
+    lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 4
     lib.tlt_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 5 + \
         [C.c_int] + [C.c_void_p] * 4
     lib.tlt_accept_sample_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 4 + \
@@ -274,10 +274,10 @@ class Context:
         tc = tree.c()
         self._check(self.lib.tlt_tree_finalize(self.handle, _stream(), B, C.byref(tc)), "tlt_tree_finalize")
 
-    def verify_forward(self, B, tree: Tree, kv: KV, out_logits=None, out_argmax=None, out_hidden=None):
+    def verify_forward(self, B, tree: Tree, kv: KV, out_logits=None, out_argmax=None, out_hidden=None, out_lse=None):
         tc, kvc = tree.c(), kv.c()
         self._check(self.lib.tlt_verify_forward(self.handle, _stream(), B, C.byref(tc), C.byref(kvc), _ptr(out_logits),
-                                                _ptr(out_argmax), _ptr(out_hidden)), "tlt_verify_forward")
+                                                _ptr(out_argmax), _ptr(out_lse), _ptr(out_hidden)), "tlt_verify_forward")
 
     def accept(self, B, mode, temperature, tree: Tree, target_logits, target_argmax, draft_q, u_accept, u_final, stride,
                accept_len, path_idx, out_tokens, n_out):

@@ -387,7 +387,7 @@ int tlt_tree_finalize(tlt_ctx* ctx, void* stream, int B, tlt_tree* tree) {
 }
 
 int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, tlt_kv* kv, float* out_logits,
-                       int32_t* out_argmax, float* out_hidden) {
+                       int32_t* out_argmax, float* out_lse, float* out_hidden) {
     if (!ctx || !tree_ok(tree) || B < 1) return TLT_EINVAL;
     if (B > ctx->max_batch || tree->n > ctx->max_n) return TLT_ESHAPE;
     int rc = check_kv(ctx, kv, tree->n);
@@ -414,11 +414,11 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
         if (rc) return rc;
     }
     if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));
-    if (out_logits || out_argmax) {
+    if (out_logits || out_argmax || out_lse) {
         float* logits = out_logits ? out_logits : (float*)(ws + p.logits);
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
                 rmsnorm(s, c.dtype, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
-        if (!out_logits && gemm_argmax_supported(c.dtype, M, V, h, ws + p.xn, ctx->target.lm_head)) {
+        if (!out_logits && !out_lse && gemm_argmax_supported(c.dtype, M, V, h, ws + p.xn, ctx->target.lm_head)) {
             // only the most likely tokens are wanted: the logits never leave the LM head's registers
             // (block partials go where the logits would have gone: M * V/128 * 8 bytes of M * V * 4)
             TLT_RUN(ctx, s, CLS_GEMM, 2.0 * M * V * h, ((double)M * h + (double)V * h) * e,
@@ -426,6 +426,7 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
         } else {
             if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
             if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
+            if (out_lse) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 8, row_lse(s, M, V, logits, out_lse));
         }
     }
     return TLT_OK;

@@ -93,6 +93,8 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
 
 // ---- sample.hip
 hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
+// out [M][2]: (max, log-sum-exp) of every row
+hipError_t row_lse(hipStream_t s, int M, int V, const float* logits, float* out);
 // per row: log-softmax statistics and the K best (token, log-prob) pairs, best first.
 size_t row_topk_workspace_bytes(int M, int V, int K);
 hipError_t row_topk_logp(hipStream_t s, int M, int V, int K, const float* logits, int32_t* tok, float* logp, void* ws);

@@ -117,6 +117,22 @@ __global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restri
     if (threadIdx.x == 0) out[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
 }
 
+// (max, log-sum-exp) of every logits row: out[2r] = max_j l_j, out[2r+1] = max + log(sum_j exp(l_j - max)).
+__global__ __launch_bounds__(256) void row_lse_k(int V, const float* __restrict__ logits, float* __restrict__ out) {
+    __shared__ float sf[4];
+    const float* row = logits + (int64_t)blockIdx.x * V;
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < V; j += 256) m = fmaxf(m, row[j]);
+    m = block_max_f<4>(m, sf);
+    float se = 0.f;
+    for (int j = threadIdx.x; j < V; j += 256) se += expf(row[j] - m);
+    se = block_sum_f<4>(se, sf);
+    if (threadIdx.x == 0) {
+        out[2 * (int64_t)blockIdx.x] = m;
+        out[2 * (int64_t)blockIdx.x + 1] = m + logf(se);
+    }
+}
+
 // Log-softmax statistics and the K best tokens of every logits row, in two kernels.
 // (1) One wave per (row, segment of kTopkSeg logits): the segment is read once into registers, then
 //     its max, its sum of exponentials and its K best entries in the (value desc, index asc) order
@@ -1142,6 +1158,12 @@ __global__ void seq_len_advance_k(int B, int32_t* seq_len, const int32_t* accept
 hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out) {
     if (M <= 0) return hipSuccess;
     hipLaunchKernelGGL(row_argmax_k, dim3(M), dim3(256), 0, s, V, logits, out);
+    return hipGetLastError();
+}
+
+hipError_t row_lse(hipStream_t s, int M, int V, const float* logits, float* out) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_lse_k, dim3(M), dim3(256), 0, s, V, logits, out);
     return hipGetLastError();
 }
 

@@ -62,7 +62,8 @@ def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std, impl):
     logits = torch.zeros((B, n, cfg.vocab), dtype=torch.float32, device="cuda")
     hidden = torch.zeros((B, n, cfg.hidden), dtype=torch.float32, device="cuda")
     argmax = torch.zeros((B, n), dtype=torch.int32, device="cuda")
-    e.ctx.verify_forward(B, t, e.kv, logits, argmax, hidden)
+    lse = torch.zeros((B, n, 2), dtype=torch.float32, device="cuda")
+    e.ctx.verify_forward(B, t, e.kv, logits, argmax, hidden, out_lse=lse)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(t.depth.cpu().numpy(), np.stack([tr.depth for tr in trees]))
     np.testing.assert_array_equal(e.kv.seq_len.cpu().numpy(), ctxs)           # verify does not commit
@@ -79,6 +80,12 @@ def test_verify_forward_matches_oracle(cfg, dtype, tol, n, ctxs, std, impl):
         st.ctx = c
         want_logits, want_hidden = sd.verify(cfg, tw, st, trees[b])
         assert rel_err(got_logits[b], want_logits) <= tol, ("logits", b)
+        # (largest logit, log-sum-exp) of every row against the plain definition on the oracle's logits
+        want_max = want_logits.max(axis=1)
+        want_lse = want_max + np.log(np.exp(want_logits - want_max[:, None]).sum(axis=1))
+        got_lse = lse[b].cpu().numpy().astype(np.float64)
+        scale = np.abs(want_logits).max()
+        assert np.abs(got_lse[:, 0] - want_max).max() <= tol * scale and np.abs(got_lse[:, 1] - want_lse).max() <= tol * scale, ("lse", b)
         assert rel_err(hidden[b].cpu().numpy(), want_hidden) <= tol, ("hidden", b)
         kn, vn = dense_cache(k_after, table, b, c + n, cfg.page_size), dense_cache(v_after, table, b, c + n, cfg.page_size)
         for l in range(cfg.n_layers):
