@@ -424,9 +424,9 @@ def kv_commit_stress(args):
 
     import torch
     a = copy.copy(args)
-    a.batch, a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = 128, 1024, 1024, 60, 2, False
+    a.batch, a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = 128, 1024, 1024, (60 if args.kv_rows <= 16 else 140), 2, False
     cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a)
-    B, stride, calls = a.batch, 17, 20
+    B, stride, calls = a.batch, args.kv_rows + 1, 20
     al = torch.full((B,), stride - 1, dtype=torch.int32, device="cuda")
     path = (torch.arange(stride, dtype=torch.int32, device="cuda") * 2).expand(B, stride).contiguous()
     for _ in range(3):
@@ -621,6 +621,93 @@ def adaptive_rollout(args, model="7b", phases=(128, 64, 32, 16, 8, 4, 2, 1), ste
                     "when speculation switches on (Engine.activate_drafter) is not part of the timed steps"}
 
 
+def graph_pool_report(args):
+    """The HIP-graph pool (Section 5.1, "Memory-Efficient CUDAGraph Capture") against naive capture on the 7B
+    shape at context 8192: the naive scheme captures one graph of the whole step per (batch size, strategy);
+    the pool captures per batch-size BUCKET, the drafter's and the target's halves separately, and strategies
+    with equal keys share a graph.  Reported: graphs captured, device memory they take (free-memory
+    difference around the captures), capture time, and the step's latency eager against replayed at small
+    batches (host time from launch to completion, where launch overhead would show)."""
+    import copy
+
+    import torch
+    batches = list(range(1, args.graph_max_batch + 1))
+    strategies = [(8, 8, 64), (4, 4, 64), (8, 8, 32), (4, 4, 16), (7, 8, 8), (3, 2, 8)]   # (Draft_Depth, topK, Tokens_to_Verify)
+    a = copy.copy(args)
+    a.batch, a.verify, a.depth, a.topk = max(batches), 64, 8, 8
+    a.ctx_lo, a.ctx_cap, a.steps, a.warmup, a.sweep = 8192, 8192, 400, 2, True
+    cfg, e, ctx, tw, dw, table, dtable, _ = build_workload(a)
+    e.step(8, 8, 64)                                     # creates the pending state graphs start from
+    for (D, K, N) in strategies:                         # every buffer a step touches exists before memory is compared
+        n = min(N, 1 + K + (D - 1) * K * K)
+        e.tree(n), e._buf("hid", n), e._buf("am", n)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+    def free():
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        return torch.cuda.mem_get_info()[0]
+
+    # --- the pool
+    pool = e.graph_pool()
+    f0, t0 = free(), time.perf_counter()
+    for B in batches:
+        for (D, K, N) in strategies:
+            pool.step(B, K, D, N)
+    torch.cuda.synchronize()
+    pool_s, pool_bytes = time.perf_counter() - t0, f0 - free()
+    n_draft, n_target = pool.n_graphs()
+    # --- naive: one whole-step graph per (batch size, strategy)
+    naive = {}
+    f0, t0 = free(), time.perf_counter()
+    for B in batches:
+        for (D, K, N) in strategies:
+            n = min(N, 1 + K + (D - 1) * K * K)
+            t, hid, am = e.tree(n), e._buf("hid", n), e._buf("am", n)
+            hid_prev = e.pending_hidden
+
+            def whole(B=B, D=D, K=K, N=N, t=t, hid=hid, am=am, hid_prev=hid_prev):
+                e.ctx.draft_expand(B, D, K, N, e.out_tokens, e.path_idx, e.n_out, hid_prev, None, e.dkv, t)
+                e.ctx.verify_forward(B, t, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
+                e.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+                e.ctx.kv_commit(B, e.kv, e.accept_len, e.path_idx, e.stride)
+            naive[(B, D, K, N)] = pool._capture(whole, also_keep=(hid_prev,))
+    naive_s, naive_bytes = time.perf_counter() - t0, f0 - free()
+    # --- latency at small batches: eager launches against one replay of the two pool graphs
+    lat = {}
+    for B in [b for b in (1, 2, 4) if b <= max(batches)]:
+        D, K, N = 7, 8, 8
+        for mode in ("eager", "replayed"):
+            ts = []
+            for it in range(6):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                if mode == "eager":
+                    n = min(N, 1 + K + (D - 1) * K * K)
+                    t, hid, am = e.tree(n), e._buf("hid", n), e._buf("am", n)
+                    e.ctx.draft_expand(B, D, K, N, e.out_tokens, e.path_idx, e.n_out, e.pending_hidden, None, e.dkv, t)
+                    e.dkv.seq_len_bound += e.pending_max_new
+                    e.ctx.verify_forward(B, t, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
+                    e.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+                    e.ctx.kv_commit(B, e.kv, e.accept_len, e.path_idx, e.stride)
+                    e.pending_hidden = hid
+                    e.kv.seq_len_bound += min(D, n - 1) + 1
+                    e.pending_max_new = min(D, n - 1) + 1
+                else:
+                    pool.step(B, K, D, N)
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - t0) * 1e3)
+            lat[f"batch {B} {mode}"] = round(float(np.median(ts[1:])), 3)
+    print(json.dumps({"metric": "HIP-graph pool against naive per-(batch, strategy) capture", "unit": "MiB of device memory",
+                      "batch_sizes": [batches[0], batches[-1]], "strategies": [list(x) for x in strategies],
+                      "pool": {"graphs": n_draft + n_target, "drafter_graphs": n_draft, "target_graphs": n_target,
+                               "MiB": round(pool_bytes / 2 ** 20, 1), "capture_s": round(pool_s, 2), "buckets": list(pool.buckets)},
+                      "naive": {"graphs": len(naive), "MiB": round(naive_bytes / 2 ** 20, 1), "capture_s": round(naive_s, 2)},
+                      "step_latency_ms_D7_K8_N8": lat,
+                      "config": {"workload": f"{cfg.name}, context 8192, every batch size 1..{batches[-1]} x {len(strategies)} strategies"}}))
+
+
 def attention_only(args):
     """The tree-attention kernel on its own (tlt_attention) at a workload's shape: batch, contexts, page
     tables and tree size as in the step, queries and cache N(0,1), chain-free random trees.  Two layers'
@@ -786,12 +873,17 @@ def main():
                     help="instead of the benchmark line: the strategy sweep (batch x tree nodes at context 8192)")
     ap.add_argument("--kv-commit-stress", action="store_true",
                     help="instead of the benchmark line: the HBM rate of tlt_kv_commit on a shape that is not launch-bound")
+    ap.add_argument("--graph-pool", action="store_true",
+                    help="instead of the benchmark line: graphs, memory and small-batch latency of the HIP-graph pool against "
+                         "naive per-(batch, strategy) capture")
+    ap.add_argument("--graph-max-batch", type=int, default=16)
     ap.add_argument("--adaptive", action="store_true",
                     help="instead of the benchmark line: a rollout whose running batch shrinks from 128 to 1 with the strategy "
                          "selector choosing the step's strategy from measured rewards")
     ap.add_argument("--attention-only", action="store_true",
                     help="instead of the benchmark line: the tree-attention kernel alone at the workload's shape")
     ap.add_argument("--attn-impl", type=int, default=-1)
+    ap.add_argument("--kv-rows", type=int, default=16, help="--kv-commit-stress: rows moved per sequence, layer and kv head (<= 64)")
     ap.add_argument("--grid-batches", type=int, nargs="+", default=[1, 4, 16, 64, 128])
     ap.add_argument("--grid-nodes", type=int, nargs="+", default=[1, 8, 16, 32, 64])
     args = ap.parse_args()
@@ -812,6 +904,8 @@ def main():
     if args.adaptive:
         print(json.dumps(adaptive_rollout(args)))
         return
+    if args.graph_pool:
+        return graph_pool_report(args)
     cfg, e, ctx, tw, dw, table, dtable, setup_s = build_workload(args)
     K, D, N, B = args.topk, args.depth, args.verify, args.batch
 
