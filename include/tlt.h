@@ -238,7 +238,9 @@ int tlt_kv_commit(tlt_ctx *ctx, void *stream, int B, tlt_kv *kv, const int32_t *
 /* ---- auxiliary entry points (unit tests, per-kernel measurement) ---- */
 
 /* C[M][N] (op)= A[M][K] . W[N][K]^T on DEVICE buffers of dtype (TLT_F32/TLT_BF16).
- * out_mode 0: C stored in dtype; 1: C stored as fp32; 2: fp32 C += product. */
+ * out_mode 0: C stored in dtype; 1: C stored as fp32; 2: fp32 C += product (products cut along K add their
+ * partial sums with atomics here, so the last bit can differ from run to run; the step itself keeps the
+ * partial products apart and sums them in a fixed order). */
 int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const void *A, const void *W, void *C);
 
 /* act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 DEVICE operands and result: the fused gate/up projection of

@@ -23,9 +23,9 @@ struct ProfRec {
 };
 
 struct Plan {  // byte offsets into the workspace
-    size_t x, xn, qkv, qkv32, att, oproj, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
+    size_t x, xn, qkv, parts, att, g, u, act, logits, argmax, feat, top_tok, top_logp, pool_token, pool_score, pool_parent,
         pool_depth, pool_mask, fr_token, fr_src, fr_pool, fr_mask, row_map, attn_ws, accept_ws, topk_ws, status, total;
-    size_t attn_ws_bytes;
+    size_t attn_ws_bytes, parts_bytes;
     int max_rows, pool_cap, feat_rows;
 };
 
@@ -54,9 +54,10 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.x = take(R * h * 4);
     p.xn = take(R * 2 * h * esz);
     p.qkv = take(R * qkv_dim * esz);
-    p.qkv32 = take(std::min<size_t>(R, 256) * qkv_dim * 4);   // fp32 q/k/v of a forward over few rows (split-K)
+    // fp32 partial products of the projections whose sum joins the fp32 residual stream (or feeds the rotary kernel)
+    p.parts_bytes = std::max(c.dtype == TLT_BF16 ? gemm_parts_max_bytes() : (size_t)0, R * std::max(h, qkv_dim) * 4);
+    p.parts = take(p.parts_bytes);
     p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
-    p.oproj = take(R * h * 4);
     p.g = take(R * F * esz);
     p.u = take(R * F * esz);
     p.act = take(R * F * esz);
@@ -111,6 +112,10 @@ struct tlt_ctx {
     int hip_error = 0;
     int attn_impl = -1;  // -1: pick by dtype/shape
     bool oproj_f32 = true;   // the output projection's product reaches the residual stream unrounded
+    // partial products in the workspace that the residual stream x has not absorbed yet: x (+)= their sum, formed
+    // by the next kernel that reads x (in the fixed order of the slices: the result is the same on every run)
+    int pending_parts = 0;
+    bool pending_assign = false;
     bool in_draft = false;  // launches are accounted to the drafter's classes
     bool status_ready = false;   // the status word in the (caller-owned, uninitialised) workspace has been cleared
     // profiling
@@ -180,6 +185,48 @@ int ensure_status(tlt_ctx* ctx, hipStream_t s) {
     return TLT_OK;
 }
 
+// A W^T as partial products in the workspace (see gemm_parts); returns their number through n_parts.
+int run_gemm_parts(tlt_ctx* ctx, hipStream_t s, int M, int N, int K, const void* A, const void* W, int* n_parts) {
+    const double e = (double)esz_of(ctx);
+    hipError_t err;
+    {
+        Scope sc(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 2.0 * M * N * K, ((double)M * K + (double)N * K) * e + (double)M * N * 4.0);
+        err = gemm_parts(s, ctx->cfg.dtype, M, N, K, A, W, (float*)(ctx->ws + ctx->plan.parts), ctx->plan.parts_bytes, n_parts);
+    }
+    if (err != hipSuccess) return fail(ctx, err);
+    return TLT_OK;
+}
+
+// x absorbs the partial products still pending (standalone: where no norm kernel follows that could do it).
+int fold_pending(tlt_ctx* ctx, hipStream_t s, int M) {
+    if (ctx->pending_parts == 0) return TLT_OK;
+    const int h = ctx->cfg.hidden;
+    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 4 * (2 + ctx->pending_parts),
+            add_parts(s, (int64_t)M * h, (float*)(ctx->ws + ctx->plan.x), (const float*)(ctx->ws + ctx->plan.parts), ctx->pending_parts,
+                      ctx->pending_assign));
+    ctx->pending_parts = 0;
+    ctx->pending_assign = false;
+    return TLT_OK;
+}
+
+// out = rmsnorm(x) * gamma over the M rows of the residual stream, x first absorbing what is pending.
+int norm_x(tlt_ctx* ctx, hipStream_t s, int M, const void* gamma, void* out) {
+    const tlt_model_cfg& c = ctx->cfg;
+    float* x = (float*)(ctx->ws + ctx->plan.x);
+    const double e = (double)esz_of(ctx);
+    if (ctx->pending_parts > 0) {
+        const int n = ctx->pending_parts;
+        const bool assign = ctx->pending_assign;
+        ctx->pending_parts = 0;
+        ctx->pending_assign = false;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * c.hidden * (8 + 4 * n + e),
+                rmsnorm_add(s, c.dtype, M, c.hidden, x, ctx->ws + ctx->plan.parts, true, gamma, c.rms_eps, out, n, assign));
+    } else {
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * c.hidden * (4 + e), rmsnorm(s, c.dtype, M, c.hidden, x, gamma, c.rms_eps, out, nullptr));
+    }
+    return TLT_OK;
+}
+
 KVLayer kv_layer(const tlt_ctx* ctx, const tlt_kv* kv, int layer) {
     const tlt_model_cfg& c = ctx->cfg;
     KVLayer k;
@@ -210,20 +257,15 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     const double e = (double)esz_of(ctx);
     float* x = (float*)(ws + p.x);
     int rc;
-    const bool qkv_split = dt == TLT_BF16 && M <= 256 && qkv_dim % 128 == 0;
-    // (the fp32 q/k/v target of the split-K projection below is cleared by the norm kernel, row by row)
-    TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e) + (qkv_split ? (double)M * qkv_dim * 4 : 0.0),
-            rmsnorm(s, dt, M, h, x, w.attn_norm, c.rms_eps, ws + p.xn, nullptr, qkv_split ? (float*)(ws + p.qkv32) : nullptr,
-                    qkv_split ? qkv_dim : 0));
-    if (qkv_split) {
-        // one row of tiles: the projection has too few tiles for the chip unless it splits K, which needs
-        // an fp32 target to accumulate into; the rotary kernel reads that and leaves q in the model dtype.
-        // (With the split count chosen against the partial sums' traffic this still pays at M = 256:
-        // 27 + 4 us for the product and the clearing against 39 us for the plain bf16 product.)
-        float* q32 = (float*)(ws + p.qkv32);
-        if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, qkv_dim, h, ws + p.xn, w.wqkv, q32))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * (4 + e),
-                rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv, q32));
+    float* parts = (float*)(ws + p.parts);
+    int n_parts = 1;
+    if ((rc = norm_x(ctx, s, M, w.attn_norm, ws + p.xn))) return rc;
+    if (dt == TLT_BF16 && M <= 256 && qkv_dim % 128 == 0) {
+        // one row of tiles: the projection has too few tiles for the chip unless it splits K, which leaves
+        // fp32 partial products; the rotary kernel sums them and leaves q in the model dtype.
+        if ((rc = run_gemm_parts(ctx, s, M, qkv_dim, h, ws + p.xn, w.wqkv, &n_parts))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * (4 * n_parts + e),
+                rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv, parts, n_parts));
     } else {
         if ((rc = run_gemm(ctx, s, OUT_T, M, qkv_dim, h, ws + p.xn, w.wqkv, ws + p.qkv))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * e * 2,
@@ -239,20 +281,18 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
                 attention(s, dt, rows, kv, ws + p.qkv, ws + p.att, c.n_q_heads, ws + p.attn_ws, p.attn_ws_bytes, ctx->attn_impl,
                           reuse_attn_plan, ctx->status_ready ? status_word(ctx) : nullptr));
     }
-    // the output projection's product goes to a buffer of its own (in the model dtype) and joins the
-    // residual stream inside the norm kernel that follows: a plain store in the GEMM's epilogue instead of
-    // a read-modify-write of the fp32 stream by every tile
-    // (with few rows the GEMM instead accumulates into x directly: that lets it split K over the chip)
-    if (M > 256) {
-        // (the product stays fp32 on its way into the fp32 residual stream unless the caller asked for
-        // the model dtype: rounding it would be the only rounding of a residual addend in the block)
-        const bool f32 = ctx->oproj_f32 || dt == TLT_F32;
-        if ((rc = run_gemm(ctx, s, f32 ? OUT_F32 : OUT_T, M, h, q_dim, ws + p.att, w.wo, ws + p.oproj))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + (f32 ? 4 : e) + e),
-                rmsnorm_add(s, dt, M, h, x, ws + p.oproj, f32, w.mlp_norm, c.rms_eps, ws + p.xn));
+    // the output projection's product (fp32, possibly several partial products of a K split) joins the
+    // residual stream inside the norm kernel that follows: plain stores in the GEMM's epilogue instead of
+    // a read-modify-write of the stream by every tile, and a sum formed in a fixed order
+    if (dt == TLT_BF16 && !ctx->oproj_f32 && M > 256) {   // (measurement switch: the product rounded to the model dtype)
+        if ((rc = run_gemm(ctx, s, OUT_T, M, h, q_dim, ws + p.att, w.wo, parts))) return rc;
+        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (8 + 2 * e),
+                rmsnorm_add(s, dt, M, h, x, parts, false, w.mlp_norm, c.rms_eps, ws + p.xn));
     } else {
-        if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, q_dim, ws + p.att, w.wo, x))) return rc;
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e), rmsnorm(s, dt, M, h, x, w.mlp_norm, c.rms_eps, ws + p.xn, nullptr));
+        if ((rc = run_gemm_parts(ctx, s, M, h, q_dim, ws + p.att, w.wo, &n_parts))) return rc;
+        ctx->pending_parts = n_parts;
+        ctx->pending_assign = false;
+        if ((rc = norm_x(ctx, s, M, w.mlp_norm, ws + p.xn))) return rc;
     }
     if (gemm_glu_supported(dt, M, F, h, ws + p.xn, w.wg, w.wu)) {
         TLT_RUN(ctx, s, ctx->in_draft ? CLS_GEMM_DRAFT : CLS_GEMM, 4.0 * M * F * h,
@@ -262,7 +302,10 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
         if ((rc = run_gemm(ctx, s, OUT_T, M, F, h, ws + p.xn, w.wu, ws + p.u))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * F * e * 3, swiglu(s, dt, (int64_t)M * F, ws + p.g, ws + p.u, ws + p.act));
     }
-    if ((rc = run_gemm(ctx, s, OUT_ADD_F32, M, h, F, ws + p.act, w.wd, x))) return rc;
+    // the down projection's product stays pending: the next kernel that reads the stream absorbs it
+    if ((rc = run_gemm_parts(ctx, s, M, h, F, ws + p.act, w.wd, &n_parts))) return rc;
+    ctx->pending_parts = n_parts;
+    ctx->pending_assign = false;
     return TLT_OK;
 }
 
@@ -394,6 +437,7 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_status(ctx, s))) return rc;
+    ctx->pending_parts = 0;   // (nothing of an earlier call is pending: every call absorbs what it leaves)
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -413,11 +457,12 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
         rc = layer_forward(ctx, s, ctx->target.layers[l], rows, kv_layer(ctx, kv, l), l > 0);
         if (rc) return rc;
     }
-    if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));
+    // (the last block's down projection is still pending: the final norm absorbs it into x, or, when no logits
+    // are wanted, a plain add)
     if (out_logits || out_argmax || out_lse) {
         float* logits = out_logits ? out_logits : (float*)(ws + p.logits);
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
-                rmsnorm(s, c.dtype, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
+        if ((rc = norm_x(ctx, s, M, ctx->target.final_norm, ws + p.xn))) return rc;
+        if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));
         if (!out_logits && !out_lse && gemm_argmax_supported(c.dtype, M, V, h, ws + p.xn, ctx->target.lm_head)) {
             // only the most likely tokens are wanted: the logits never leave the LM head's registers
             // (block partials go where the logits would have gone: M * V/128 * 8 bytes of M * V * 4)
@@ -428,20 +473,23 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
             if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
             if (out_lse) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 8, row_lse(s, M, V, logits, out_lse));
         }
+    } else {
+        if ((rc = fold_pending(ctx, s, M))) return rc;
+        if (out_hidden) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, copy_f32(s, (int64_t)M * h, x, out_hidden));
     }
     return TLT_OK;
 }
 
-// x = fc([embedding ; hidden]) of the drafter (2h -> h).  With few rows the product has far fewer tiles
-// than the chip has CUs while K = 2h is long, so x is cleared and the GEMM accumulates into it, which
-// lets it split K over many workgroups; with many rows it is a plain store.
-static int draft_fc(tlt_ctx* ctx, hipStream_t s, int M, const void* xin, float* x) {
-    const int h = ctx->cfg.hidden;
-    if (ctx->cfg.dtype == TLT_BF16 && M <= 256 && h % 4 == 0) {
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 4, zero_f32(s, (int64_t)M * h, x));
-        return run_gemm(ctx, s, OUT_ADD_F32, M, h, 2 * h, xin, ctx->draft.fc, x);
-    }
-    return run_gemm(ctx, s, OUT_F32, M, h, 2 * h, xin, ctx->draft.fc, x);
+// x = fc([embedding ; hidden]) of the drafter (2h -> h), left pending as partial products: with few rows the
+// product has far fewer tiles than the chip has CUs while K = 2h is long, so it is cut along K; the
+// drafter block's first norm kernel forms x from the slices.
+static int draft_fc(tlt_ctx* ctx, hipStream_t s, int M, const void* xin) {
+    int n_parts = 1;
+    int rc = run_gemm_parts(ctx, s, M, ctx->cfg.hidden, 2 * ctx->cfg.hidden, xin, ctx->draft.fc, &n_parts);
+    if (rc) return rc;
+    ctx->pending_parts = n_parts;
+    ctx->pending_assign = true;
+    return TLT_OK;
 }
 
 // Drafter catch-up shared by both expansion modes: entries for the newly committed positions, the
@@ -462,7 +510,7 @@ static int draft_extend_rows(tlt_ctx* ctx, hipStream_t s, int B, const int32_t* 
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
             draft_input(s, dt, B, new_stride, h, V, new_tokens, new_src, n_new, hidden_n, (int64_t)B * hidden_n, hidden,
                         ctx->target.embed, ws + p.xn));
-    if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
+    if ((rc = draft_fc(ctx, s, M, ws + p.xn))) return rc;
     Rows rows;
     rows.B = B;
     rows.n = new_stride;
@@ -470,6 +518,7 @@ static int draft_extend_rows(tlt_ctx* ctx, hipStream_t s, int B, const int32_t* 
     rows.pos_stride = 1;
     rows.n_region = new_stride;
     if ((rc = layer_forward(ctx, s, ctx->draft.layers[0], rows, kvl))) return rc;
+    if ((rc = fold_pending(ctx, s, M))) return rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * h * 8, gather_last_rows(s, B, new_stride, h, n_new, x, feat, FR));
     TLT_RUN(ctx, s, CLS_OTHER, 0, 0, add_i32(s, B, draft_kv->seq_len, n_new, 0));
     kvl.seq_len_bound += new_stride;
@@ -503,6 +552,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     } draft_flag(ctx);
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_status(ctx, s))) return rc;
+    ctx->pending_parts = 0;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -547,7 +597,7 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
                 draft_input(s, dt, B, topk, h, V, st.fr_token, st.fr_src, nullptr, FR, (int64_t)B * FR, feat,
                             ctx->target.embed, ws + p.xn));
-        if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
+        if ((rc = draft_fc(ctx, s, M, ws + p.xn))) return rc;
         Rows rows;
         rows.B = B;
         rows.n = topk;
@@ -558,9 +608,8 @@ int tlt_draft_expand(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         rows.mask_words = 2;
         rows.n_region = level * topk;
         if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
+        if ((rc = norm_x(ctx, s, M, ctx->target.final_norm, ws + p.xn))) return rc;   // (absorbs the pending down projection into x)
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, scatter_rows(s, M, topk, h, x, feat, FR, 1 + (level - 1) * topk));
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
-                rmsnorm(s, dt, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
         if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_topk_logp(s, M, V, topk, logits, top_tok, top_logp, ws + p.topk_ws));
         TLT_RUN(ctx, s, CLS_OTHER, 0, 0, draft_level_select(s, B, topk, level, top_tok, top_logp, st, FR));
@@ -622,6 +671,7 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
     } draft_flag(ctx);
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_status(ctx, s))) return rc;
+    ctx->pending_parts = 0;
     const tlt_model_cfg& c = ctx->cfg;
     const Plan& p = ctx->plan;
     char* ws = ctx->ws;
@@ -686,7 +736,7 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + 3 * e),
                 draft_input(s, dt, B, lv.R, h, V, fr_token, fr_src, nullptr, FR, (int64_t)B * FR, feat, ctx->target.embed,
                             ws + p.xn));
-        if ((rc = draft_fc(ctx, s, M, ws + p.xn, x))) return rc;
+        if ((rc = draft_fc(ctx, s, M, ws + p.xn))) return rc;
         Rows rows;
         rows.B = B;
         rows.n = lv.R;
@@ -697,9 +747,8 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         rows.mask_words = 1;
         rows.n_region = slot_base + lv.R;
         if ((rc = layer_forward(ctx, s, lw, rows, kvl))) return rc;
+        if ((rc = norm_x(ctx, s, M, ctx->target.final_norm, ws + p.xn))) return rc;   // (absorbs the pending down projection into x)
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, scatter_rows(s, M, lv.R, h, x, feat, FR, 1 + slot_base));
-        TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * (4 + e),
-                rmsnorm(s, dt, M, h, x, ctx->target.final_norm, c.rms_eps, ws + p.xn, nullptr));
         if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 12,
                 softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q));

@@ -21,7 +21,8 @@ __global__ void embed_rows_k(int M, int h, int V, const int32_t* __restrict__ to
 template <typename T, typename TA>
 __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                  float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                 const TA* __restrict__ add, float* __restrict__ zero, int zero_n) {
+                                                 const TA* __restrict__ add, float* __restrict__ zero, int zero_n, int n_add,
+                                                 int64_t add_stride, int assign) {
     __shared__ float red[4];
     int r = blockIdx.x;
     if (zero)
@@ -35,9 +36,9 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
     float* xr = x + src * h;
     float ss = 0.f;
     for (int c = threadIdx.x; c < h; c += 256) {
-        float v = xr[c];
+        float v = (add && assign) ? 0.f : xr[c];
         if (add) {   // (each element is read, updated and later re-read by the same thread)
-            v += to_float(add[src * h + c]);
+            for (int k = 0; k < n_add; ++k) v += to_float(add[k * add_stride + src * h + c]);
             xr[c] = v;
         }
         ss += v * v;
@@ -52,10 +53,11 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
 
 // Same, for h % 4 == 0 and h <= 1024 * NK: the row is read once with 16-byte loads and stays in
 // registers (NK float4 per thread) between the reduction and the scaling.
-template <typename T, int NK, typename TA>
+template <typename T, int NK, typename TA, int NB = 4>   // NB: slices of `add` whose loads are issued together
 __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                      float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
-                                                     const TA* __restrict__ add, float* __restrict__ zero, int zero_n) {
+                                                     const TA* __restrict__ add, float* __restrict__ zero, int zero_n, int n_add,
+                                                     int64_t add_stride, int assign) {
     __shared__ float red[4];
     const int r = blockIdx.x, h4 = h >> 2;
     if (zero)   // row r of a second buffer cleared on the way (zero_n % 4 == 0, 16-byte aligned: the launcher checks)
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
 #pragma unroll
         for (int k = 0; k < NK; ++k) {
             const int c = threadIdx.x + k * 256;
-            v[k] = c < h4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            v[k] = (c < h4 && !(add && assign)) ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
             if (add && c < h4) {
                 const TA* a = add + src * h + 4 * c;
                 if constexpr (sizeof(TA) == 2) {
@@ -80,8 +82,18 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
                     v[k].z += __uint_as_float(pk.y << 16);
                     v[k].w += __uint_as_float(pk.y & 0xffff0000u);
                 } else {
-                    const float4 av = *(const float4*)a;
-                    v[k].x += av.x; v[k].y += av.y; v[k].z += av.z; v[k].w += av.w;
+                    // partial products, summed in their fixed order; the loads of up to four slices are issued
+                    // together (one after the other they would each expose a memory latency)
+                    for (int j0 = 0; j0 < n_add; j0 += NB) {
+                        float4 av[NB];
+#pragma unroll
+                        for (int u = 0; u < NB; ++u)
+                            av[u] = j0 + u < n_add ? *(const float4*)(a + (j0 + u) * add_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                        for (int u = 0; u < NB; ++u) {
+                            v[k].x += av[u].x; v[k].y += av[u].y; v[k].z += av[u].z; v[k].w += av[u].w;
+                        }
+                    }
                 }
                 xr[c] = v[k];
             }
@@ -124,7 +136,7 @@ union Piece {   // 16 bytes of T
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T* __restrict__ qkv, int n_q_heads,
                                                        float theta, const T* __restrict__ bias,
-                                                       const float* __restrict__ src32) {
+                                                       const float* __restrict__ src32, int n_src, int64_t src_stride) {
     extern __shared__ float cs[];  // [d/2] cos, [d/2] sin
     const int d = kv.d, half = d >> 1;
     int r = blockIdx.x;
@@ -150,7 +162,17 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
         if (row32) {
 #pragma unroll
             for (int k = 0; k < 16 / (int)sizeof(T); k += 4) {
-                const float4 f = *(const float4*)(row32 + elem + k);
+                float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int j0 = 0; j0 < n_src; j0 += 8) {   // partial products of a split projection, in their fixed order
+                    float4 g[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        g[u] = j0 + u < n_src ? *(const float4*)(row32 + (j0 + u) * src_stride + elem + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        f.x += g[u].x; f.y += g[u].y; f.z += g[u].z; f.w += g[u].w;
+                    }
+                }
                 out.e[k] = from_float<T>(f.x);
                 out.e[k + 1] = from_float<T>(f.y);
                 out.e[k + 2] = from_float<T>(f.z);
@@ -306,26 +328,31 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 
 template <typename T, typename TA>
 static void rmsnorm_launch_t(hipStream_t s, int M, int h, float* x, const void* gamma, float eps, void* out,
-                             const int32_t* row_map, const void* add, float* zero, int zero_n) {
+                             const int32_t* row_map, const void* add, float* zero, int zero_n, int n_add, bool assign) {
+    const int64_t add_stride = (int64_t)M * h;
     const bool vec_ok = h % 4 == 0 && (((uintptr_t)x | (uintptr_t)add | (uintptr_t)zero) & 15) == 0 && zero_n % 4 == 0;
-    if (vec_ok && h <= 4096)
+    if (vec_ok && h <= 4096 && add && n_add > 4 && sizeof(TA) == 4)   // many slices (few rows): all their loads in flight at once
+        hipLaunchKernelGGL((rmsnorm_vec_k<T, 4, TA, 12>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
+                           (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
+    else if (vec_ok && h <= 4096)
         hipLaunchKernelGGL((rmsnorm_vec_k<T, 4, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
-                           (const TA*)add, zero, zero_n);
+                           (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
     else if (vec_ok && h <= 8192)   // (the 32B and 70B widths)
         hipLaunchKernelGGL((rmsnorm_vec_k<T, 8, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
-                           (const TA*)add, zero, zero_n);
+                           (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
     else
         hipLaunchKernelGGL((rmsnorm_k<T, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
-                           (const TA*)add, zero, zero_n);
+                           (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
 }
 
 static hipError_t rmsnorm_launch(hipStream_t s, int dtype, int M, int h, float* x, const void* gamma, float eps, void* out,
                                  const int32_t* row_map, const void* add, bool add_f32 = false, float* zero = nullptr,
-                                 int zero_n = 0) {
+                                 int zero_n = 0, int n_add = 1, bool assign = false) {
     if (M <= 0) return hipSuccess;
-    if (dtype == F32) rmsnorm_launch_t<float, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
-    else if (add_f32) rmsnorm_launch_t<bf16, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
-    else rmsnorm_launch_t<bf16, bf16>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n);
+    if (add && !add_f32 && dtype != F32 && n_add != 1) return hipErrorInvalidValue;   // several addends: fp32 partial products only
+    if (dtype == F32) rmsnorm_launch_t<float, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n, n_add, assign);
+    else if (add_f32) rmsnorm_launch_t<bf16, float>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n, n_add, assign);
+    else rmsnorm_launch_t<bf16, bf16>(s, M, h, x, gamma, eps, out, row_map, add, zero, zero_n, n_add, assign);
     return hipGetLastError();
 }
 
@@ -335,12 +362,39 @@ hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const
 }
 
 hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, bool add_f32, const void* gamma,
-                       float eps, void* out) {
-    return rmsnorm_launch(s, dtype, M, h, x, gamma, eps, out, nullptr, add, add_f32);
+                       float eps, void* out, int n_add, bool assign) {
+    return rmsnorm_launch(s, dtype, M, h, x, gamma, eps, out, nullptr, add, add_f32, nullptr, 0, n_add, assign);
+}
+
+__global__ void add_parts_k(int64_t count4, float4* __restrict__ x, const float4* __restrict__ parts, int n_parts, int assign) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count4; i += stride) {
+        float4 v = assign ? make_float4(0.f, 0.f, 0.f, 0.f) : x[i];
+        for (int k0 = 0; k0 < n_parts; k0 += 4) {
+            float4 p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = k0 + u < n_parts ? parts[(k0 + u) * count4 + i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w;
+            }
+        }
+        x[i] = v;
+    }
+}
+
+hipError_t add_parts(hipStream_t s, int64_t count, float* x, const float* parts, int n_parts, bool assign) {
+    if (count <= 0 || n_parts <= 0) return hipSuccess;
+    const int64_t c4 = count / 4;
+    int blocks = (int)((c4 + 255) / 256);
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(add_parts_k, dim3(blocks), dim3(256), 0, s, c4, (float4*)x, (const float4*)parts, n_parts, (int)assign);
+    return hipGetLastError();
 }
 
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta, const void* bias, const float* src32) {
+                         float theta, const void* bias, const float* src32, int n_src) {
     int M = rows.B * rows.n;
     if (M <= 0) return hipSuccess;
     // the kernel moves 16-byte pieces: rows of qkv and of the cache are multiples of 16 bytes by the
@@ -348,8 +402,9 @@ hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLay
     if ((((uintptr_t)qkv | (uintptr_t)bias | (uintptr_t)kv.k | (uintptr_t)kv.v | (uintptr_t)src32) & 15) != 0)
         return hipErrorInvalidValue;
     size_t lds = sizeof(float) * kv.d;
+    const int64_t src_stride = (int64_t)M * (n_q_heads + 2 * kv.n_kv) * kv.d;
     DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta,
-                                         (const T*)bias, src32));
+                                         (const T*)bias, src32, n_src, src_stride));
     return hipGetLastError();
 }
 

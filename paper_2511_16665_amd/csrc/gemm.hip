@@ -36,7 +36,7 @@ template <int OUT>
 __device__ __forceinline__ void store_out(void* C, int64_t idx, float v) {
     if (OUT == OUT_T)
         ((bf16*)C)[idx] = from_float<bf16>(v);
-    else if (OUT == OUT_F32)
+    else if (OUT == OUT_F32 || OUT == OUT_SPLIT_F32)
         ((float*)C)[idx] = v;
     else if (OUT == OUT_ADD_F32)
         ((float*)C)[idx] += v;
@@ -88,7 +88,8 @@ template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU 
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
-                                                        int ksplit, int wg_per_xcd, int32_t* __restrict__ C2, int kskew) {
+                                                        int ksplit, int wg_per_xcd, int32_t* __restrict__ C2, int kskew,
+                                                        int64_t split_stride) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     const bool up_wave = GLU && wave >= NW / 2;
 
     // tile j of this workgroup: M fastest, then the K split, then N
-    struct TileInfo { int m0, n0, kt0, nt; };
+    struct TileInfo { int m0, n0, kt0, nt, split; };
     auto tile_info = [&](int j) {
         const int logical = first + j * wg_per_xcd;
         const int tile_m = logical % nbm, split = (logical / nbm) % ksplit, tile_n = logical / (nbm * ksplit);
@@ -145,6 +146,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
         };
         ti.kt0 = __builtin_amdgcn_readfirstlane(kbound(split));
         ti.nt = __builtin_amdgcn_readfirstlane(kbound(split + 1)) - ti.kt0;
+        ti.split = __builtin_amdgcn_readfirstlane(split);
         return ti;
     };
     // raw buffer descriptors (four scalar words: base, base high bits, size in bytes, format) over a
@@ -407,7 +409,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
                         for (int jj = 0; jj < WTN; ++jj) {
                             int col = ti.n0 + wn * (WTN * 32) + jj * 32 + l32;
-                            store_out<OUT>(C, (int64_t)row * N + col, acc[i][jj][v]);
+                            store_out<OUT>(C, (OUT == OUT_SPLIT_F32 ? (int64_t)ti.split * split_stride : (int64_t)0) + (int64_t)row * N + col,
+                                           acc[i][jj][v]);
                         }
                     }
                 }
@@ -508,10 +511,12 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
             attr_set = true;                                                                                          \
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
-                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr, kskew);                                           \
+                           (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr, kskew,              \
+                           (int64_t)M * ldc);                                                                        \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
+    else if (out_mode == OUT_SPLIT_F32) LAUNCH(OUT_SPLIT_F32)
     else if (ksplit == 1) LAUNCH(OUT_ADD_F32)
     else LAUNCH(OUT_ATOMIC_ADD_F32)
 #undef LAUNCH
@@ -580,71 +585,108 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     return small(rest_cols, main_nbn * bno256);
 }
 
+// How a product that accumulates into fp32 is cut along K (bf16 MFMA path).  kind 0: not at all; 1: 256x128
+// tiles (few rows); 2: 256x256 tiles.
+struct SplitPlan {
+    int kind = 0, ks = 1, skew = 0;
+};
+static SplitPlan plan_split(int M, int N, int K) {
+    SplitPlan sp;
+    const int tiles256 = ((M + 255) / 256) * (N / 256);
+    // too few 256x256 tiles for the chip but a long K and an fp32 sum as output: split K over several
+    // workgroups per tile.
+    // few rows (M <= 256 is one row of tiles: the drafter's projections, a verification forward over a
+    // handful of tree nodes; up to a few hundred rows the picture is the same): the weights stream from HBM,
+    // so what counts is how many workgroups pull on them and how little partial-sum traffic the split costs.
+    // 256x128 tiles halve both the tile count needed per split and the bytes of every partial tile.
+    if (N % 128 == 0) {
+        const int nk = K / kBK, tiles = ((M + 255) / 256) * (N / 128);
+        if (tiles < 200) {
+            int ks = 256 / tiles;
+            if (ks > nk / 8) ks = nk / 8;
+            // fewer splits when the partial tiles weigh more than the K steps they save: a workgroup
+            // alone on its CU takes ~0.6 us per K step, a split adds M*N*4 bytes of partial-sum traffic at
+            // ~1.75 TB/s; the sum nk*0.6/ks + ks*M*N*4/1.75e6 us is smallest at the square root of the ratio
+            // (qkv-sized product at M = 256: 37 us with 7 splits, 27 with 3-4; the down projection keeps its 9)
+            {
+                const double per_split_us = (double)M * N * 4.0 / 1.75e6;
+                const int best = (int)(sqrt(0.6 * nk / per_split_us) + 0.5);
+                if (best < ks) ks = best < 1 ? 1 : best;
+            }
+            // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
+            // the deeper ring keeps more of it in flight (31.7 against 39.5 us on the down projection at M = 32)
+            if (ks >= 2) {
+                // uneven splits once the partial tiles weigh something (down projection at M = 256:
+                // 60 -> 54 us; at M = 32 the even cut is better, 32 against 36 us)
+                int skew = M >= 128 ? 8 : 0;
+                if (skew > nk / ks / 4) skew = nk / ks / 4;
+                sp.kind = 1, sp.ks = ks, sp.skew = skew;
+                return sp;
+            }
+        }
+    }
+    if (N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
+        const int nk = K / kBK;
+        int ks = 256 / tiles256;
+        // at least 16 K tiles per split (8 when M is small: the weights then stream from HBM and the
+        // number of workgroups pulling on them matters more than the partial tiles' epilogues)
+        const int min_k_tiles = M <= 256 ? 8 : 16;
+        if (ks > nk / min_k_tiles) ks = nk / min_k_tiles;
+        // every split ends with a 256x256 partial tile: worth it for a long K only, or when M is
+        // small and the alternative leaves most of the chip idle while the weights stream in
+        const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
+        if (pays && tiles256 * ks >= 128) {
+            // all splits of a one-round launch would end together and store their partial tiles in one
+            // burst with the matrix pipes idle: K is cut unevenly (lengths mean -+ 10 K tiles) so that the
+            // early splits store theirs under the others' products (down projection at M = 1536, 3 splits
+            // of 90 / 99 / 107 K tiles)
+            int skew = 10;
+            if (skew > nk / ks / 4) skew = nk / ks / 4;
+            sp.kind = 2, sp.ks = ks, sp.skew = skew;
+        }
+    }
+    return sp;
+}
+
+static bool pipe_ok(int N, int K, const void* A, const void* W) {
+    const bool aligned = (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
+    // per-lane DMA offsets are 32-bit byte offsets inside a 256-row panel
+    return aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)258 * K * 2 < ((int64_t)1 << 31);
+}
+
 hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C) {
     if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
     if (dtype == F32) return launch_generic<float>(s, out_mode, M, N, K, A, W, C);
-    const bool aligned = (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
-    // per-lane DMA offsets are 32-bit byte offsets inside a 256-row panel
-    if (aligned && K % kBK == 0 && N % 128 == 0 && (int64_t)258 * K * 2 < ((int64_t)1 << 31)) {
-        const int tiles256 = ((M + 255) / 256) * (N / 256);
-        // too few 256x256 tiles for the chip but a long K and an accumulating fp32 output: split K
-        // over several workgroups per tile, which add their partial sums with fp32 atomics (the
-        // order of those additions, and so the last bit of the result, is not fixed)
-        // few rows accumulating into fp32 (M <= 256 is one row of tiles: the drafter's projections, a
-        // verification forward over a handful of tree nodes; up to a few hundred rows the picture is the
-        // same): the weights stream from HBM, so what counts is how many workgroups pull on them and how
-        // little partial-sum traffic the split costs.  256x128 tiles halve both the tile count needed per
-        // split and the bytes of every partial tile.
-        if (out_mode == OUT_ADD_F32 && N % 128 == 0) {
-            const int nk = K / kBK, tiles = ((M + 255) / 256) * (N / 128);
-            if (tiles < 200) {
-                int ks = 256 / tiles;
-                if (ks > nk / 8) ks = nk / 8;
-                // fewer splits when the partial tiles weigh more than the K steps they save: a workgroup
-                // alone on its CU takes ~0.6 us per K step, a split adds M*N*4 bytes of atomic traffic at
-                // ~1.75 TB/s; the sum nk*0.6/ks + ks*M*N*4/1.75e6 us is smallest at the square root of the ratio
-                // (qkv-sized product at M = 256: 37 us with 7 splits, 27 with 3-4; the down projection keeps its 9)
-                {
-                    const double per_split_us = (double)M * N * 4.0 / 1.75e6;
-                    const int best = (int)(sqrt(0.6 * nk / per_split_us) + 0.5);
-                    if (best < ks) ks = best < 1 ? 1 : best;
-                }
-                // (what is left after this is the atomic traffic of the partial tiles, ks * M * N * 4 bytes at
-                // 1.5-2 TB/s: deeper weight rings, 128x128 tiles with twice the workgroups -- all measured the same)
-                // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
-                // the deeper ring keeps more of it in flight (31.7 against 39.5 us on the down projection at M = 32)
-                if (ks >= 2) {
-                    // uneven splits once the partial tiles weigh something (down projection at M = 256:
-                    // 60 -> 54 us; at M = 32 the even cut is better, 32 against 36 us)
-                    int skew = M >= 128 ? 8 : 0;
-                    if (skew > nk / ks / 4) skew = nk / ks / 4;
-                    return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N, K, A, W, C, nullptr, ks, 0, skew);
-                }
-            }
-        }
-        if (out_mode == OUT_ADD_F32 && N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
-            const int nk = K / kBK;
-            int ks = 256 / tiles256;
-            // at least 16 K tiles per split (8 when M is small: the weights then stream from HBM and the
-            // number of workgroups pulling on them matters more than the partial tiles' epilogues)
-            const int min_k_tiles = M <= 256 ? 8 : 16;
-            if (ks > nk / min_k_tiles) ks = nk / min_k_tiles;
-            // every split ends with a 256x256 tile of atomics: worth it for a long K only, or when M is
-            // small and the alternative leaves most of the chip idle while the weights stream in
-            const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
-            if (pays && tiles256 * ks >= 128) {
-                // all splits of a one-round launch would end together and add 64 MB of partial tiles in one
-                // burst with the matrix pipes idle: K is cut unevenly (lengths mean -+ 10 K tiles) so that the
-                // early splits add theirs under the others' products (down projection at M = 1536, 3 splits
-                // of 90 / 99 / 107 K tiles: 196 -> 187 us; mean -+ 16 and more lose it again)
-                int skew = 10;
-                if (skew > nk / ks / 4) skew = nk / ks / 4;
-                return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, ks, 0, skew);
-            }
+    if (pipe_ok(N, K, A, W)) {
+        // (accumulating into C: the K splits add their partial sums with fp32 atomics, in any order, so the
+        // last bit of the result is not fixed.  The step itself uses gemm_parts, which is reproducible.)
+        if (out_mode == OUT_ADD_F32) {
+            const SplitPlan sp = plan_split(M, N, K);
+            if (sp.kind == 1) return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N, K, A, W, C, nullptr, sp.ks, 0, sp.skew);
+            if (sp.kind == 2) return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, N, K, A, W, C, nullptr, sp.ks, 0, sp.skew);
         }
         return launch_tiled(s, out_mode, M, N, K, A, W, nullptr, C, false);
     }
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
+}
+
+// ks * M * N <= 256 / tiles * M * N with tiles >= M * N / (256 * 256): at most 256 * 65536 floats
+size_t gemm_parts_max_bytes() { return (size_t)256 * 65536 * 4 + 4096; }
+
+hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void* A, const void* W, float* parts,
+                      size_t parts_bytes, int* n_parts) {
+    *n_parts = 1;
+    if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
+    if ((size_t)M * N * 4 > parts_bytes) return hipErrorInvalidValue;
+    if (dtype == BF16 && pipe_ok(N, K, A, W)) {
+        const SplitPlan sp = plan_split(M, N, K);
+        if (sp.kind != 0 && (size_t)sp.ks * M * N * 4 <= parts_bytes) {
+            *n_parts = sp.ks;
+            if (sp.kind == 1) return launch_pipe<2, 2, 4, 2, 3, 4>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
+            return launch_pipe<2, 2, 4, 4, 3, 2>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
+        }
+    }
+    return gemm(s, dtype, OUT_F32, M, N, K, A, W, parts);
 }
 
 // ---- fused row argmax (big tiles only: every 256-row weight tile yields two 128-column blocks)
@@ -698,7 +740,7 @@ hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const 
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(wg_per_xcd * 8), dim3(256), lds, s, M, P, K, (const uint16_t*)A, (const uint16_t*)W,
-                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi, 0);
+                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi, 0, (int64_t)0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(argmax_blocks_k, dim3((M + 3) / 4), dim3(256), 0, s, M, P, pv, pi, out);

@@ -12,7 +12,8 @@ enum {
     OUT_F32 = 1,
     OUT_ADD_F32 = 2,
     OUT_ATOMIC_ADD_F32 = 3, /* internal: split-K partial sums */
-    OUT_ROWMAX = 4          /* internal: per-row (max, argmax) of every 128-column block instead of C */
+    OUT_ROWMAX = 4,         /* internal: per-row (max, argmax) of every 128-column block instead of C */
+    OUT_SPLIT_F32 = 5       /* internal: every K split stores its fp32 partial product to a slice of its own */
 };
 
 // Rows of a layer forward, laid out [B][n].  Row (b, i) is active when i < n_valid[b] (all rows
@@ -43,6 +44,15 @@ struct KVLayer {
 
 // ---- gemm.hip
 hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, const void* A, const void* W, void* C);
+// The product as a sum of partial products: parts [n][M][N] fp32 with sum_k parts[k] = A W^T, n >= 1 returned in
+// *n_parts.  Products with too few tiles for the chip and a long K are cut along K over several workgroups
+// per tile, each storing its partial product to a slice of its own (plain stores, every element of every
+// slice is written: nothing has to be cleared, and the sum the consumer forms is the same on every run);
+// all others are one plain fp32 product (n = 1).  parts_bytes bounds n * M * N * 4.
+hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void* A, const void* W, float* parts,
+                      size_t parts_bytes, int* n_parts);
+// upper bound of n * M * N * 4 over every shape (see gemm.hip)
+size_t gemm_parts_max_bytes();
 // fused gate/up projection of the SwiGLU MLP (bf16 MFMA path only): act = silu(A Wg^T) * (A Wu^T)
 bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu);
 hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act);
@@ -61,13 +71,17 @@ hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32
 // zero (optional): a second fp32 buffer [M][zero_n] cleared row by row in the same launch.
 hipError_t rmsnorm(hipStream_t s, int dtype, int M, int h, const float* x, const void* gamma, float eps, void* out,
                    const int32_t* row_map, float* zero = nullptr, int zero_n = 0);
-// x[r] += add[r] (add [M][h] in dtype, or in fp32 when add_f32), then out[r] = rmsnorm(x[r]) * gamma.
+// x[r] += sum_k add[k][r] (add [n_add][M][h] in fp32 when add_f32, else one [M][h] in dtype; assign: x[r] = that sum
+// instead), then out[r] = rmsnorm(x[r]) * gamma.  The sum runs in the order k = 0, 1, ...: reproducible.
 hipError_t rmsnorm_add(hipStream_t s, int dtype, int M, int h, float* x, const void* add, bool add_f32, const void* gamma,
-                       float eps, void* out);
+                       float eps, void* out, int n_add = 1, bool assign = false);
+// x += sum_k parts[k] (or x = with assign), count floats each (a multiple of 4)
+hipError_t add_parts(hipStream_t s, int64_t count, float* x, const float* parts, int n_parts, bool assign);
 // (bias: optional [(Hq+2Hkv)*d] in dtype, added to q, k and v before the rotation; src32: optional
 // fp32 copy of the projection to read instead of qkv, which then only receives the rotated q)
+// (src32 may hold n_src partial products [n_src][M][qkv_dim], which are summed in order)
 hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLayer& kv, void* qkv, int n_q_heads,
-                         float theta, const void* bias, const float* src32 = nullptr);
+                         float theta, const void* bias, const float* src32 = nullptr, int n_src = 1);
 hipError_t swiglu(hipStream_t s, int dtype, int64_t count, const void* g, const void* u, void* out);
 // Rows [B][n]: xin[r] = [embed[tok[r]] ; hidden[src row]] in dtype (2h wide).  The hidden row is
 // b*src_seq_stride + src[r] when src_seq_stride > 0, else src[r].  Rows with tok < 0, src < 0,
