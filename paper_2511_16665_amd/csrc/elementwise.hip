@@ -53,15 +53,15 @@ __global__ __launch_bounds__(256) void rmsnorm_k(int h, float* __restrict__ x, c
 
 // Same, for h % 4 == 0 and h <= 1024 * NK: the row is read once with 16-byte loads and stays in
 // registers (NK float4 per thread) between the reduction and the scaling.
-template <typename T, int NK, typename TA, int NB = 4>   // NB: slices of `add` whose loads are issued together
-__global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
+template <typename T, int NK, typename TA, int NB = 4, int NTHR = 256>   // NB: slices of `add` whose loads are issued together
+__global__ __launch_bounds__(NTHR) void rmsnorm_vec_k(int h, float* __restrict__ x, const T* __restrict__ gamma,
                                                      float eps, T* __restrict__ out, const int32_t* __restrict__ row_map,
                                                      const TA* __restrict__ add, float* __restrict__ zero, int zero_n, int n_add,
                                                      int64_t add_stride, int assign) {
-    __shared__ float red[4];
+    __shared__ float red[NTHR / 64];
     const int r = blockIdx.x, h4 = h >> 2;
     if (zero)   // row r of a second buffer cleared on the way (zero_n % 4 == 0, 16-byte aligned: the launcher checks)
-        for (int c = threadIdx.x; c < (zero_n >> 2); c += 256)
+        for (int c = threadIdx.x; c < (zero_n >> 2); c += NTHR)
             ((float4*)(zero + (int64_t)r * zero_n))[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int64_t src = row_map ? row_map[r] : r;
     T* o = out + (int64_t)r * h;
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
         float4* xr = (float4*)(x + src * h);
 #pragma unroll
         for (int k = 0; k < NK; ++k) {
-            const int c = threadIdx.x + k * 256;
+            const int c = threadIdx.x + k * NTHR;
             v[k] = (c < h4 && !(add && assign)) ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
             if (add && c < h4) {
                 const TA* a = add + src * h + 4 * c;
@@ -103,11 +103,13 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_k(int h, float* __restrict__ 
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NTHR / 64; ++w) tot += red[w];
     const float inv = src >= 0 ? 1.0f / sqrtf(tot / (float)h + eps) : 0.f;
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
-        const int c = threadIdx.x + k * 256;
+        const int c = threadIdx.x + k * NTHR;
         if (c >= h4) continue;
         const T* g = gamma + 4 * c;
         float y[4] = {v[k].x * inv * to_float(g[0]), v[k].y * inv * to_float(g[1]), v[k].z * inv * to_float(g[2]),
@@ -133,7 +135,7 @@ union Piece {   // 16 bytes of T
 // pos * inv_freq already carries ~1e-3 rad of rounding), once per (row, pair index), then reused by
 // every head.  q is rotated in place; k is rotated and stored with v at the row's cache slot.  An
 // optional projection bias is added first (to q, k and v).
-template <typename T>
+template <typename T, bool SRC32>   // SRC32: the projection arrives as fp32 partial products (its own instance: it needs many more registers)
 __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T* __restrict__ qkv, int n_q_heads,
                                                        float theta, const T* __restrict__ bias,
                                                        const float* __restrict__ src32, int n_src, int64_t src_stride) {
@@ -145,21 +147,13 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
     int ctx = kv.seq_len[b];
     int pos = ctx + rows.pos_base + (rows.pos_off ? rows.pos_off[r] : rows.pos_stride * i);
     int slot = ctx + rows.slot_base + i;
-    for (int j = threadIdx.x; j < half; j += 256) {
-        double inv_freq = pow((double)theta, -2.0 * (double)j / (double)d);
-        double sn, c;
-        sincos((double)pos * inv_freq, &sn, &c);
-        cs[j] = (float)c;
-        cs[half + j] = (float)sn;
-    }
-    __syncthreads();
     const int qkv_dim = (n_q_heads + 2 * kv.n_kv) * d;
     T* row = qkv + (int64_t)r * qkv_dim;
     // src32 (optional): the projection's product still in fp32 (a split-K GEMM accumulated it there);
     // q then goes to `qkv` in T for the attention kernel, exactly as when it is rotated in place
-    const float* row32 = src32 ? src32 + (int64_t)r * qkv_dim : nullptr;
+    const float* row32 = SRC32 ? src32 + (int64_t)r * qkv_dim : nullptr;
     auto load_piece = [&](int elem, Piece<T>& out) {   // VEC consecutive elements of the row, as T
-        if (row32) {
+        if constexpr (SRC32) {
 #pragma unroll
             for (int k = 0; k < 16 / (int)sizeof(T); k += 4) {
                 float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -182,6 +176,46 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
             out.v = *(const u32x4_t*)(row + elem);
         }
     };
+    // both halves of a rotation pair at once: with partial products every slice's loads for the two
+    // pieces are issued together (one memory latency instead of one per piece and slice batch)
+    auto load_pair = [&](int elem_lo, int elem_hi, Piece<T>& lo, Piece<T>& hi) {
+        if constexpr (!SRC32) {
+            lo.v = *(const u32x4_t*)(row + elem_lo);
+            hi.v = *(const u32x4_t*)(row + elem_hi);
+            return;
+        }
+        constexpr int NQ = 16 / (int)sizeof(T) / 4;   // float4 per piece
+        float4 f[2][NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) f[0][q] = f[1][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j0 = 0; j0 < n_src; j0 += 8) {   // partial products of a split projection, in their fixed order
+            float4 g[2][NQ][8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const bool on = j0 + u < n_src;
+                    g[0][q][u] = on ? *(const float4*)(row32 + (j0 + u) * src_stride + elem_lo + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    g[1][q][u] = on ? *(const float4*)(row32 + (j0 + u) * src_stride + elem_hi + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        f[hh][q].x += g[hh][q][u].x; f[hh][q].y += g[hh][q][u].y;
+                        f[hh][q].z += g[hh][q][u].z; f[hh][q].w += g[hh][q][u].w;
+                    }
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            lo.e[4 * q] = from_float<T>(f[0][q].x); lo.e[4 * q + 1] = from_float<T>(f[0][q].y);
+            lo.e[4 * q + 2] = from_float<T>(f[0][q].z); lo.e[4 * q + 3] = from_float<T>(f[0][q].w);
+            hi.e[4 * q] = from_float<T>(f[1][q].x); hi.e[4 * q + 1] = from_float<T>(f[1][q].y);
+            hi.e[4 * q + 2] = from_float<T>(f[1][q].z); hi.e[4 * q + 3] = from_float<T>(f[1][q].w);
+        }
+    };
     PageRef pr;
     bool have = locate(kv.block_table, kv.max_pages, kv.n_pages, kv.page_size, b, slot, pr);
     T* kc = (T*)kv.k;
@@ -190,13 +224,29 @@ __global__ __launch_bounds__(256) void rope_kv_write_k(Rows rows, KVLayer kv, T*
     constexpr int VEC = 16 / sizeof(T);
     const int cph = half / VEC;   // pieces per half head
     const int n_piece = (n_q_heads + kv.n_kv) * cph;
+    // the first piece's loads fly while the angles are computed
+    Piece<T> lo0, hi0;
+    lo0.v = u32x4_t{0u, 0u, 0u, 0u};
+    hi0.v = lo0.v;
+    if ((int)threadIdx.x < n_piece) {
+        const int hd = threadIdx.x / cph, j0 = (threadIdx.x - hd * cph) * VEC;
+        load_pair(hd * d + j0, hd * d + half + j0, lo0, hi0);
+    }
+    for (int j = threadIdx.x; j < half; j += 256) {
+        double inv_freq = pow((double)theta, -2.0 * (double)j / (double)d);
+        double sn, c;
+        sincos((double)pos * inv_freq, &sn, &c);
+        cs[j] = (float)c;
+        cs[half + j] = (float)sn;
+    }
+    __syncthreads();
     for (int e = threadIdx.x; e < n_piece; e += 256) {
         const int hd = e / cph, j0 = (e - hd * cph) * VEC;
         T* p = row + (int64_t)hd * d;
         Piece<T> lo, hi, blo, bhi;
-        load_piece(hd * d + j0, lo);
-        hi.v = lo.v;   // (initialised for the compiler; overwritten)
-        load_piece(hd * d + half + j0, hi);
+        lo.v = lo0.v;
+        hi.v = hi0.v;
+        if (e != (int)threadIdx.x) load_pair(hd * d + j0, hd * d + half + j0, lo, hi);
         if (bias) {
             blo.v = *(const u32x4_t*)(bias + hd * d + j0);
             bhi.v = *(const u32x4_t*)(bias + hd * d + half + j0);
@@ -331,9 +381,11 @@ static void rmsnorm_launch_t(hipStream_t s, int M, int h, float* x, const void* 
                              const int32_t* row_map, const void* add, float* zero, int zero_n, int n_add, bool assign) {
     const int64_t add_stride = (int64_t)M * h;
     const bool vec_ok = h % 4 == 0 && (((uintptr_t)x | (uintptr_t)add | (uintptr_t)zero) & 15) == 0 && zero_n % 4 == 0;
-    if (vec_ok && h <= 4096 && add && n_add > 4 && sizeof(TA) == 4)   // many slices (few rows): all their loads in flight at once
-        hipLaunchKernelGGL((rmsnorm_vec_k<T, 4, TA, 12>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
-                           (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
+    if (vec_ok && h <= 4096 && add && n_add > 4 && sizeof(TA) == 4)
+        // many slices (few rows, so few workgroups): one 16-byte position per thread and all its slices' loads in
+        // flight at once
+        hipLaunchKernelGGL((rmsnorm_vec_k<T, 1, TA, 12, 1024>), dim3(M), dim3(1024), 0, s, h, x, (const T*)gamma, eps, (T*)out,
+                           row_map, (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
     else if (vec_ok && h <= 4096)
         hipLaunchKernelGGL((rmsnorm_vec_k<T, 4, TA>), dim3(M), dim3(256), 0, s, h, x, (const T*)gamma, eps, (T*)out, row_map,
                            (const TA*)add, zero, zero_n, n_add, add_stride, (int)assign);
@@ -403,8 +455,13 @@ hipError_t rope_kv_write(hipStream_t s, int dtype, const Rows& rows, const KVLay
         return hipErrorInvalidValue;
     size_t lds = sizeof(float) * kv.d;
     const int64_t src_stride = (int64_t)M * (n_q_heads + 2 * kv.n_kv) * kv.d;
-    DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kv_write_k<T>, dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads, theta,
-                                         (const T*)bias, src32, n_src, src_stride));
+    if (src32) {
+        DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_k<T, true>), dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads,
+                                             theta, (const T*)bias, src32, n_src, src_stride));
+    } else {
+        DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_k<T, false>), dim3(M), dim3(256), lds, s, rows, kv, (T*)qkv, n_q_heads,
+                                             theta, (const T*)bias, src32, n_src, src_stride));
+    }
     return hipGetLastError();
 }
 
