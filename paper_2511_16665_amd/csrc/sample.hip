@@ -742,12 +742,13 @@ constexpr int kAcceptThreads = 256;       // multi-workgroup sampling acceptance
 constexpr int kAcceptMaxGroups = 64;      // workgroups per sequence
 constexpr int kAcceptPhases = 2 * TLT_ACCEPT_MAX_NODES + 4;   // node passes (<= stride <= nodes + 1) + rejections (< nodes) + final
 constexpr int kAcceptSlots = 5;           // per phase: S or residual total, SQ, next token's W, its R, its Qw
-constexpr unsigned kAcceptSpinLimit = 1u << 22;
+constexpr unsigned kAcceptSpinLimit = 1u << 24;
 
 struct AcceptSync {   // one per sequence, zeroed before the launch
     unsigned long long sum[kAcceptPhases][kAcceptSlots];
     unsigned long long slice_total[kAcceptMaxGroups];
     unsigned int arrived[kAcceptPhases];
+    float row_max[TLT_ACCEPT_MAX_NODES];   // largest logit of every tree node's row (written by accept_row_max_k)
 };
 
 __device__ __forceinline__ unsigned long long sync_load(const unsigned long long* p) {
@@ -763,7 +764,7 @@ __device__ __forceinline__ bool accept_meet(AcceptSync* sy, int ph, int G, unsig
         unsigned spins = 0;
         int ok = 1;
         while (__hip_atomic_load(&sy->arrived[ph], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)G) {
-            __builtin_amdgcn_s_sleep(16);
+            __builtin_amdgcn_s_sleep(2);
             if (++spins > kAcceptSpinLimit || (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 2u) != 0u) {
                 __hip_atomic_fetch_or(status, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ok = 0;
@@ -780,6 +781,27 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sync_clear_k(unsigned l
     for (int64_t i = (int64_t)blockIdx.x * kAcceptThreads + threadIdx.x; i < count; i += (int64_t)gridDim.x * kAcceptThreads) p[i] = 0ull;
 }
 
+// Largest logit of every (sequence, node) row, one workgroup per row: every node pass of the walk needs its
+// row's maximum first, and one parallel pass over all rows is cheaper than every workgroup of a sequence
+// scanning the whole row again at every node.
+__global__ __launch_bounds__(kAcceptThreads) void accept_row_max_k(int n, int V, const float* __restrict__ logits,
+                                                                   AcceptSync* __restrict__ sync) {
+    __shared__ float sf[kAcceptThreads / 64];
+    const int b = blockIdx.x / n, i = blockIdx.x - b * n, tid = threadIdx.x;
+    const float* l = logits + (int64_t)blockIdx.x * V;
+    float m = -INFINITY;
+    if (V % 4 == 0 && ((uintptr_t)l & 15) == 0) {
+        for (int j = tid * 4; j < V; j += kAcceptThreads * 4) {
+            const float4 x = *(const float4*)(l + j);
+            m = fmaxf(fmaxf(m, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
+        }
+    } else {
+        for (int j = tid; j < V; j += kAcceptThreads) m = fmaxf(m, l[j]);
+    }
+    m = block_max_f<kAcceptThreads / 64>(m, sf);
+    if (tid == 0) sync[b].row_max[i] = m;
+}
+
 __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, int stride, int G, int slice, float temperature,
                                                        const int32_t* __restrict__ token,
                                                        const int32_t* __restrict__ parent,
@@ -793,7 +815,6 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
                                                        unsigned int* __restrict__ status) {
     constexpr int NW = kAcceptThreads / 64;
     __shared__ unsigned long long su[NW];
-    __shared__ float sf[NW];
     __shared__ int ok_s, pick_s;
     const int b = blockIdx.x / G, g = blockIdx.x - b * G, tid = threadIdx.x;
     const int32_t* tok = token + (int64_t)b * n;
@@ -826,18 +847,9 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_sample_k(int n, int V, 
         const float* l = logits + ((int64_t)b * n + cur) * V;
         const float* q = draft_q + ((int64_t)b * n + cur) * V;
         // max_j (l_j / tau) = (max_j l_j) / tau: a correctly rounded division by a positive number keeps
-        // the order, so the maximum is taken on the floats and divided once.  Every workgroup scans the
-        // whole row for it (a cheap pass from the L2) rather than meeting for it.
-        float lmax = -INFINITY;
-        if (V % 4 == 0 && ((uintptr_t)l & 15) == 0) {
-            for (int j = tid * 4; j < V; j += kAcceptThreads * 4) {
-                const float4 x = *(const float4*)(l + j);
-                lmax = fmaxf(fmaxf(lmax, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
-            }
-        } else {
-            for (int j = tid; j < V; j += kAcceptThreads) lmax = fmaxf(lmax, l[j]);
-        }
-        const double m = (double)block_max_f<NW>(lmax, sf) / tau;
+        // the order, so the maximum is taken on the floats (by accept_row_max_k, before this kernel) and
+        // divided once.
+        const double m = (double)sy->row_max[cur] / tau;
         int c = a + 1 < stride ? next_child(cur) : -1;
         unsigned long long s = 0, sq = 0;
         for (int j = v0 + tid; j < v1; j += kAcceptThreads) {
@@ -1273,6 +1285,9 @@ hipError_t accept_sample(hipStream_t s, int B, int n, int V, int stride, float t
     hipLaunchKernelGGL(accept_sync_clear_k, dim3((unsigned)((words + kAcceptThreads - 1) / kAcceptThreads)), dim3(kAcceptThreads),
                        0, s, (unsigned long long*)sync, words);
     hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_row_max_k, dim3(B * n), dim3(kAcceptThreads), 0, s, n, V, logits, sync);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(accept_sample_k, dim3(B * G), dim3(kAcceptThreads), 0, s, n, V, stride, G, slice, temperature, token,
                        parent, logits, draft_q, u_accept, u_final, accept_len, path_idx, out_tokens, n_out,
