@@ -649,8 +649,9 @@ def graph_pool_report(args):
         torch.cuda.empty_cache()
         return torch.cuda.mem_get_info()[0]
 
-    # --- the pool
-    pool = e.graph_pool()
+    # --- the pool (the library's own: tlt_graph_pool_*)
+    pool = e.graph_pool(native=True)
+    torch_capture = e.graph_pool()                       # only its capture routine is used, for the naive scheme below
     f0, t0 = free(), time.perf_counter()
     for B in batches:
         for (D, K, N) in strategies:
@@ -672,7 +673,7 @@ def graph_pool_report(args):
                 e.ctx.verify_forward(B, t, e.kv, out_logits=None, out_argmax=am, out_hidden=hid)
                 e.ctx.accept(B, 0, 1.0, t, None, am, None, None, None, e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
                 e.ctx.kv_commit(B, e.kv, e.accept_len, e.path_idx, e.stride)
-            naive[(B, D, K, N)] = pool._capture(whole, also_keep=(hid_prev,))
+            naive[(B, D, K, N)] = torch_capture._capture(whole, also_keep=(hid_prev,))
     naive_s, naive_bytes = time.perf_counter() - t0, f0 - free()
     # --- latency at small batches: eager launches against one replay of the two pool graphs
     lat = {}
@@ -701,7 +702,7 @@ def graph_pool_report(args):
             lat[f"batch {B} {mode}"] = round(float(np.median(ts[1:])), 3)
     print(json.dumps({"metric": "HIP-graph pool against naive per-(batch, strategy) capture", "unit": "MiB of device memory",
                       "batch_sizes": [batches[0], batches[-1]], "strategies": [list(x) for x in strategies],
-                      "pool": {"graphs": n_draft + n_target, "drafter_graphs": n_draft, "target_graphs": n_target,
+                      "pool": {"implementation": "tlt_graph_pool (C ABI)", "graphs": n_draft + n_target, "drafter_graphs": n_draft, "target_graphs": n_target,
                                "MiB": round(pool_bytes / 2 ** 20, 1), "capture_s": round(pool_s, 2), "buckets": list(pool.buckets)},
                       "naive": {"graphs": len(naive), "MiB": round(naive_bytes / 2 ** 20, 1), "capture_s": round(naive_s, 2)},
                       "step_latency_ms_D7_K8_N8": lat,

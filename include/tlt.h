@@ -235,6 +235,42 @@ int tlt_accept_sample_static(void *stream, int B, int vocab, float temperature, 
 int tlt_kv_commit(tlt_ctx *ctx, void *stream, int B, tlt_kv *kv, const int32_t *accept_len,
                   const int32_t *path_idx, int stride);
 
+/* ---- HIP-graph pool (Section 5.1 "Memory-Efficient CUDAGraph Capture": graphs captured per batch-size
+ * bucket instead of per batch size, the drafter's graph apart from the target's, one graph shared by every
+ * strategy with the same key).  tlt_graph_pool_step runs one greedy step -- tlt_draft_expand (mode 0, root =
+ * last new token), tlt_verify_forward (argmax and hidden state only), tlt_accept (mode 0), tlt_kv_commit, with
+ * exactly the arguments below -- for the first `bucket` slots of the caller's buffers, bucket = the smallest
+ * pool bucket >= B (slots B .. bucket-1 must hold valid sequences), by launching two instantiated graphs on
+ * `stream`.  A graph is captured on first use of its key: the drafter's by (bucket, depth, topk, n_verify, its
+ * pointer arguments), the target's by (bucket, tree, its pointer arguments); capturing synchronises `stream`,
+ * runs the calls once for real on a stream of the pool, puts back what that run changed, and captures them.
+ * Every graph is captured with the sequence-length bound given at creation (the grids of a graph are frozen):
+ * every sequence must stay below seq_len_bound, and seq_len_bound + tree->n within what the block tables hold.
+ * All buffers are the caller's and shared by all graphs (a graph owns kernel nodes and their arguments only);
+ * the same pointers must be passed to replay a graph.  No host synchronisation happens in a replay.  Profiling
+ * (tlt_profile_begin) records nothing inside graphs. */
+typedef struct tlt_graph_pool tlt_graph_pool;
+typedef struct tlt_step_args {
+    /* as tlt_draft_expand: the tokens committed by the step before, the rows of `hidden` they came from */
+    const int32_t *new_tokens, *new_src, *n_new;
+    int32_t new_stride;
+    const float *hidden;   /* [bucket][hidden_n][h]: out_hidden of the step before */
+    int32_t hidden_n;
+    tlt_kv *draft_kv;
+    tlt_tree *tree;        /* drafter's output, target's input */
+    tlt_kv *kv;
+    int32_t *argmax;       /* [bucket][tree->n] */
+    float *hidden_out;     /* [bucket][tree->n][h]; may be `hidden` itself */
+    int32_t stride;
+    int32_t *accept_len, *path_idx, *out_tokens, *n_out;   /* as tlt_accept */
+} tlt_step_args;
+/* buckets: HOST, strictly increasing batch sizes, each <= the context's max_batch. */
+int tlt_graph_pool_create(tlt_ctx *ctx, const int32_t *buckets, int n_buckets, int seq_len_bound, tlt_graph_pool **out);
+int tlt_graph_pool_destroy(tlt_graph_pool *pool);
+int tlt_graph_pool_step(tlt_graph_pool *pool, void *stream, int B, int depth, int topk, int n_verify,
+                        const tlt_step_args *args);
+int tlt_graph_pool_count(const tlt_graph_pool *pool, int32_t *n_draft, int32_t *n_target);
+
 /* ---- auxiliary entry points (unit tests, per-kernel measurement) ---- */
 
 /* C[M][N] (op)= A[M][K] . W[N][K]^T on DEVICE buffers of dtype (TLT_F32/TLT_BF16).

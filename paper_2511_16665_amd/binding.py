@@ -27,6 +27,7 @@ EXPORTS = [
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
     "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status", "tlt_accept_sample_static", "tlt_attention", "tlt_attention_workspace_bytes",
+    "tlt_graph_pool_create", "tlt_graph_pool_destroy", "tlt_graph_pool_step", "tlt_graph_pool_count",
 ]
 
 
@@ -64,6 +65,13 @@ class TreeC(C.Structure):
                 ("score", C.c_void_p), ("n", C.c_int32)]
 
 
+class StepArgsC(C.Structure):
+    _fields_ = [("new_tokens", C.c_void_p), ("new_src", C.c_void_p), ("n_new", C.c_void_p), ("new_stride", C.c_int32),
+                ("hidden", C.c_void_p), ("hidden_n", C.c_int32), ("draft_kv", C.POINTER(KVC)), ("tree", C.POINTER(TreeC)),
+                ("kv", C.POINTER(KVC)), ("argmax", C.c_void_p), ("hidden_out", C.c_void_p), ("stride", C.c_int32),
+                ("accept_len", C.c_void_p), ("path_idx", C.c_void_p), ("out_tokens", C.c_void_p), ("n_out", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -90,6 +98,10 @@ def load() -> C.CDLL:
     lib.tlt_draft_sample.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 3 + \
         [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(KVC), C.c_void_p, C.POINTER(TreeC), C.c_void_p]
     lib.tlt_tree_finalize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC)]
+    lib.tlt_graph_pool_create.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.POINTER(C.c_void_p)]
+    lib.tlt_graph_pool_destroy.argtypes = [C.c_void_p]
+    lib.tlt_graph_pool_step.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.POINTER(StepArgsC)]
+    lib.tlt_graph_pool_count.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.tlt_verify_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(TreeC), C.POINTER(KVC)] + [C.c_void_p] * 4
     lib.tlt_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.POINTER(TreeC)] + [C.c_void_p] * 5 + \
         [C.c_int] + [C.c_void_p] * 4
@@ -461,3 +473,46 @@ def gemm_glu(A, Wg, Wu, act):
     """act = silu(A Wg^T) * (A Wu^T) for bf16 device tensors A [M, K], Wg/Wu [N, K], act [M, N]; returns the code."""
     M, K = A.shape
     return load().tlt_gemm_glu(_stream(), M, Wg.shape[0], K, _ptr(A), _ptr(Wg), _ptr(Wu), _ptr(act))
+
+
+class GraphPool:
+    """tlt_graph_pool_*: the library's HIP-graph pool (greedy step per batch bucket, drafter and target graphs
+    apart).  The caller's tensors must stay alive and in place for as long as their graphs are replayed."""
+
+    def __init__(self, ctx: "Context", buckets, seq_len_bound: int):
+        self.ctx = ctx
+        self.lib = ctx.lib
+        arr = (C.c_int32 * len(buckets))(*buckets)
+        self.handle = C.c_void_p()
+        rc = self.lib.tlt_graph_pool_create(ctx.handle, arr, len(buckets), int(seq_len_bound), C.byref(self.handle))
+        if rc:
+            raise TltError(rc, "tlt_graph_pool_create", self.lib.tlt_last_hip_error(ctx.handle))
+
+    def step(self, B, depth, topk, n_verify, new_tokens, new_src, n_new, hidden, draft_kv: "KV", tree: "Tree", kv: "KV",
+             argmax, hidden_out, stride, accept_len, path_idx, out_tokens, n_out):
+        dkv_c, kv_c, tree_c = draft_kv.c(), kv.c(), tree.c()
+        a = StepArgsC(_ptr(new_tokens), _ptr(new_src), _ptr(n_new), new_tokens.shape[1], _ptr(hidden), hidden.shape[1],
+                      C.pointer(dkv_c), C.pointer(tree_c), C.pointer(kv_c), _ptr(argmax), _ptr(hidden_out), stride,
+                      _ptr(accept_len), _ptr(path_idx), _ptr(out_tokens), _ptr(n_out))
+        rc = self.lib.tlt_graph_pool_step(self.handle, _stream(), B, depth, topk, n_verify, C.byref(a))
+        if rc:
+            raise TltError(rc, "tlt_graph_pool_step", self.lib.tlt_last_hip_error(self.ctx.handle))
+
+    def count(self):
+        nd, nt = C.c_int32(), C.c_int32()
+        rc = self.lib.tlt_graph_pool_count(self.handle, C.byref(nd), C.byref(nt))
+        if rc:
+            raise TltError(rc, "tlt_graph_pool_count")
+        return nd.value, nt.value
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            self.lib.tlt_graph_pool_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

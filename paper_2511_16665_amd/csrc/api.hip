@@ -6,6 +6,8 @@
 
 #include <algorithm>
 #include <cstring>
+#include <functional>
+#include <map>
 #include <new>
 #include <vector>
 
@@ -952,6 +954,197 @@ int tlt_profile_read(tlt_ctx* ctx, double* ms, int64_t* launches, double* flops,
     }
     ctx->recs.clear();
     return TLT_OK;
+}
+
+
+// ---- HIP-graph pool: the greedy step captured per batch bucket, drafter and target apart ------------------
+struct tlt_graph_pool {
+    tlt_ctx* ctx = nullptr;
+    std::vector<int> buckets;
+    int bound = 0;                 // sequence-length bound frozen into every graph
+    hipStream_t cap = nullptr;     // capture stream (default priority)
+    std::map<std::vector<uint64_t>, hipGraphExec_t> draft, target;
+    char* snap = nullptr;          // device space for what a warm-up run must not change
+    size_t snap_bytes = 0;
+};
+
+namespace {
+
+struct Piece {
+    void* p;
+    size_t bytes;
+};
+
+// fn runs once for real on the pool's stream (first-use set-up such as kernel attributes must not fall into a
+// capture), the buffers in `keep` get their contents back, and then fn is captured and instantiated.
+int capture_graph(tlt_graph_pool* g, const std::vector<Piece>& keep, const std::function<int(hipStream_t)>& fn,
+                  hipGraphExec_t* out) {
+    tlt_ctx* ctx = g->ctx;
+    size_t total = 0;
+    for (const Piece& k : keep) total += (k.bytes + 255) & ~(size_t)255;
+    hipError_t e;
+    if (total > g->snap_bytes) {
+        if (g->snap) (void)hipFree(g->snap);
+        g->snap = nullptr;
+        g->snap_bytes = 0;
+        if ((e = hipMalloc((void**)&g->snap, total)) != hipSuccess) return fail(ctx, e);
+        g->snap_bytes = total;
+    }
+    size_t off = 0;
+    for (const Piece& k : keep) {
+        if ((e = hipMemcpyAsync(g->snap + off, k.p, k.bytes, hipMemcpyDeviceToDevice, g->cap)) != hipSuccess) return fail(ctx, e);
+        off += (k.bytes + 255) & ~(size_t)255;
+    }
+    const bool prof = ctx->prof_on;   // events may not be recorded into a capture
+    ctx->prof_on = false;
+    int rc = fn(g->cap);
+    if (rc == TLT_OK) {
+        off = 0;
+        for (const Piece& k : keep) {
+            if ((e = hipMemcpyAsync(k.p, g->snap + off, k.bytes, hipMemcpyDeviceToDevice, g->cap)) != hipSuccess) rc = fail(ctx, e);
+            off += (k.bytes + 255) & ~(size_t)255;
+        }
+    }
+    if (rc == TLT_OK && (e = hipStreamSynchronize(g->cap)) != hipSuccess) rc = fail(ctx, e);
+    if (rc == TLT_OK) {
+        hipGraph_t graph = nullptr;
+        if ((e = hipStreamBeginCapture(g->cap, hipStreamCaptureModeThreadLocal)) != hipSuccess) {
+            rc = fail(ctx, e);
+        } else {
+            rc = fn(g->cap);
+            e = hipStreamEndCapture(g->cap, &graph);   // always ends the capture, also after a failed call
+            if (rc == TLT_OK && e != hipSuccess) rc = fail(ctx, e);
+            if (rc == TLT_OK && (e = hipGraphInstantiate(out, graph, nullptr, nullptr, 0)) != hipSuccess) rc = fail(ctx, e);
+            if (graph) (void)hipGraphDestroy(graph);
+        }
+    }
+    ctx->prof_on = prof;
+    return rc;
+}
+
+void key_kv(std::vector<uint64_t>& k, const tlt_kv* kv) {
+    k.push_back((uint64_t)(uintptr_t)kv->k_pool);
+    k.push_back((uint64_t)(uintptr_t)kv->v_pool);
+    k.push_back((uint64_t)kv->n_pages);
+    k.push_back((uint64_t)(uintptr_t)kv->block_table);
+    k.push_back((uint64_t)(uintptr_t)kv->seq_len);
+    k.push_back((uint64_t)kv->max_pages);
+}
+
+void key_tree(std::vector<uint64_t>& k, const tlt_tree* t) {
+    k.push_back((uint64_t)(uintptr_t)t->token);
+    k.push_back((uint64_t)(uintptr_t)t->parent);
+    k.push_back((uint64_t)(uintptr_t)t->depth);
+    k.push_back((uint64_t)(uintptr_t)t->anc_mask);
+    k.push_back((uint64_t)(uintptr_t)t->score);
+    k.push_back((uint64_t)t->n);
+}
+
+}  // namespace
+
+int tlt_graph_pool_create(tlt_ctx* ctx, const int32_t* buckets, int n_buckets, int seq_len_bound, tlt_graph_pool** out) {
+    if (!ctx || !out || !buckets || n_buckets < 1 || seq_len_bound < 0) return TLT_EINVAL;
+    for (int i = 0; i < n_buckets; ++i)
+        if (buckets[i] < 1 || buckets[i] > ctx->max_batch || (i > 0 && buckets[i] <= buckets[i - 1])) return TLT_EINVAL;
+    tlt_graph_pool* g = new (std::nothrow) tlt_graph_pool();
+    if (!g) return TLT_EINVAL;
+    g->ctx = ctx;
+    g->buckets.assign(buckets, buckets + n_buckets);
+    g->bound = seq_len_bound;
+    hipError_t e = hipStreamCreateWithFlags(&g->cap, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        delete g;
+        return fail(ctx, e);
+    }
+    *out = g;
+    return TLT_OK;
+}
+
+int tlt_graph_pool_destroy(tlt_graph_pool* g) {
+    if (!g) return TLT_OK;
+    for (auto& kv : g->draft) (void)hipGraphExecDestroy(kv.second);
+    for (auto& kv : g->target) (void)hipGraphExecDestroy(kv.second);
+    if (g->snap) (void)hipFree(g->snap);
+    if (g->cap) (void)hipStreamDestroy(g->cap);
+    delete g;
+    return TLT_OK;
+}
+
+int tlt_graph_pool_count(const tlt_graph_pool* g, int32_t* n_draft, int32_t* n_target) {
+    if (!g || !n_draft || !n_target) return TLT_EINVAL;
+    *n_draft = (int32_t)g->draft.size();
+    *n_target = (int32_t)g->target.size();
+    return TLT_OK;
+}
+
+int tlt_graph_pool_step(tlt_graph_pool* g, void* stream, int B, int depth, int topk, int n_verify, const tlt_step_args* a) {
+    if (!g || !a || !a->draft_kv || !a->kv || !a->tree || B < 1) return TLT_EINVAL;
+    if (!a->new_tokens || !a->new_src || !a->n_new || !a->hidden || !a->argmax || !a->hidden_out || !a->accept_len ||
+        !a->path_idx || !a->out_tokens || !a->n_out || a->stride < 1 || a->new_stride < 1 || a->hidden_n < 1)
+        return TLT_EINVAL;
+    tlt_ctx* ctx = g->ctx;
+    int Bk = 0;
+    for (int b : g->buckets)
+        if (b >= B) {
+            Bk = b;
+            break;
+        }
+    if (Bk == 0) return TLT_ESHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    tlt_kv dkv = *a->draft_kv, kv = *a->kv;
+    dkv.seq_len_bound = kv.seq_len_bound = g->bound;
+    tlt_tree tree = *a->tree;
+    const int h = ctx->cfg.hidden;
+
+    std::vector<uint64_t> dkey = {(uint64_t)Bk, (uint64_t)depth, (uint64_t)topk, (uint64_t)n_verify,
+                                  (uint64_t)(uintptr_t)a->new_tokens, (uint64_t)(uintptr_t)a->new_src,
+                                  (uint64_t)(uintptr_t)a->n_new, (uint64_t)a->new_stride,
+                                  (uint64_t)(uintptr_t)a->hidden, (uint64_t)a->hidden_n};
+    key_kv(dkey, &dkv);
+    key_tree(dkey, &tree);
+    std::vector<uint64_t> tkey = {(uint64_t)Bk, (uint64_t)(uintptr_t)a->argmax, (uint64_t)(uintptr_t)a->hidden_out,
+                                  (uint64_t)a->stride, (uint64_t)(uintptr_t)a->accept_len, (uint64_t)(uintptr_t)a->path_idx,
+                                  (uint64_t)(uintptr_t)a->out_tokens, (uint64_t)(uintptr_t)a->n_out};
+    key_kv(tkey, &kv);
+    key_tree(tkey, &tree);
+
+    const bool need_draft = g->draft.find(dkey) == g->draft.end();
+    const bool need_target = g->target.find(tkey) == g->target.end();
+    if (need_draft || need_target) {
+        // captures are rare: everything the caller has queued ends first, so the warm-up runs see its state
+        hipError_t e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return fail(ctx, e);
+    }
+    if (need_draft) {
+        std::vector<Piece> keep = {{dkv.seq_len, (size_t)Bk * 4}};
+        hipGraphExec_t exec = nullptr;
+        int rc = capture_graph(g, keep, [&](hipStream_t cs) {
+            return tlt_draft_expand(ctx, cs, Bk, depth, topk, n_verify, 0, a->new_tokens, a->new_src, a->n_new, a->new_stride,
+                                    a->hidden, a->hidden_n, nullptr, &dkv, &tree);
+        }, &exec);
+        if (rc != TLT_OK) return rc;
+        g->draft[dkey] = exec;
+    }
+    if (need_target) {
+        const size_t row = (size_t)Bk * a->stride * 4;
+        std::vector<Piece> keep = {{kv.seq_len, (size_t)Bk * 4}, {a->accept_len, (size_t)Bk * 4}, {a->n_out, (size_t)Bk * 4},
+                                   {a->path_idx, row}, {a->out_tokens, row},
+                                   {(void*)a->hidden, (size_t)Bk * a->hidden_n * h * 4}};   // hidden_out may be the same buffer
+        hipGraphExec_t exec = nullptr;
+        int rc = capture_graph(g, keep, [&](hipStream_t cs) {
+            int r = tlt_verify_forward(ctx, cs, Bk, &tree, &kv, nullptr, a->argmax, nullptr, a->hidden_out);
+            if (r == TLT_OK)
+                r = tlt_accept(ctx, cs, Bk, 0, 1.0f, &tree, nullptr, a->argmax, nullptr, nullptr, nullptr, a->stride, a->accept_len,
+                               a->path_idx, a->out_tokens, a->n_out);
+            if (r == TLT_OK) r = tlt_kv_commit(ctx, cs, Bk, &kv, a->accept_len, a->path_idx, a->stride);
+            return r;
+        }, &exec);
+        if (rc != TLT_OK) return rc;
+        g->target[tkey] = exec;
+    }
+    hipError_t e = hipGraphLaunch(g->draft[dkey], s);
+    if (e == hipSuccess) e = hipGraphLaunch(g->target[tkey], s);
+    return e == hipSuccess ? TLT_OK : fail(ctx, e);
 }
 
 }  // extern "C"

@@ -261,9 +261,10 @@ class Engine:
         self.have_pending = False
 
     # -- the same step replayed from captured HIP graphs
-    def graph_pool(self, capacity_bound=None) -> "GraphPool":
-        """Graph pool over this engine's buffers (see GraphPool)."""
-        return GraphPool(self, capacity_bound)
+    def graph_pool(self, capacity_bound=None, native=False):
+        """Graph pool over this engine's buffers: the library's own (tlt_graph_pool_*, native=True) or the one
+        kept here with torch's capture (see GraphPool); same keys, buckets and step() either way."""
+        return NativeGraphPool(self, capacity_bound) if native else GraphPool(self, capacity_bound)
 
     def _buf(self, kind, n):
         key = (kind, n)
@@ -368,3 +369,42 @@ class GraphPool:
 
     def n_graphs(self):
         return len(self.draft_graphs), len(self.target_graphs)
+
+
+class NativeGraphPool:
+    """GraphPool's interface over the library's pool (tlt_graph_pool_create / _step / _count): capture, keys and
+    replay live behind the C ABI; this class only hands over the engine's buffers and keeps the host-side
+    length bounds, as GraphPool.step does."""
+
+    def __init__(self, engine: Engine, capacity_bound=None, buckets=(1, 2, 4, 8, 16, 32, 64, 128)):
+        self.e = engine
+        self.buckets = tuple(b for b in buckets if b < engine.B) + (engine.B,)
+        page = engine.cfg.page_size
+        cap = min(engine.kv.block_table.shape[1], engine.dkv.block_table.shape[1]) * page
+        self.bound = int(capacity_bound) if capacity_bound is not None else cap - 2 * engine.max_n - 64
+        self.pool = tlt.GraphPool(engine.ctx, self.buckets, self.bound)
+
+    def bucket(self, B):
+        for b in self.buckets:
+            if b >= B:
+                return b
+        raise ValueError(f"batch {B} exceeds the engine's {self.e.B}")
+
+    def step(self, B, topk, depth, n_verify):
+        e = self.e
+        assert e.have_pending and e.pending_hidden is not None
+        pool = topk + (depth - 1) * topk * topk if depth >= 1 else 0
+        n = min(n_verify, 1 + pool)
+        t = e.tree(n)
+        hid_prev = e.pending_hidden
+        hid, am = e._buf("hid", n), e._buf("am", n)
+        self.pool.step(B, depth, topk, n_verify, e.out_tokens, e.path_idx, e.n_out, hid_prev, e.dkv, t, e.kv, am, hid,
+                       e.stride, e.accept_len, e.path_idx, e.out_tokens, e.n_out)
+        e.pending_hidden = hid
+        inc = min(depth, n - 1) + 1
+        e.dkv.seq_len_bound += e.pending_max_new
+        e.kv.seq_len_bound += inc
+        e.pending_max_new = inc
+
+    def n_graphs(self):
+        return self.pool.count()

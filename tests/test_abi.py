@@ -72,4 +72,12 @@ def test_draft_expand_rejects_more_provisional_rows_than_a_mask_holds():
     assert call(10, 16) == -2            # 144 rows
     assert call(16, 16) == -2
     assert call(9, 17) == -2             # topk beyond the context's limit
+    # the graph pool's bucket list is checked on the host as well, before a stream is created
+    pool = ctypes.c_void_p()
+    mk = lambda *b: lib.tlt_graph_pool_create(h, (ctypes.c_int32 * len(b))(*b), len(b), 1000, ctypes.byref(pool))
+    assert mk() == -1                    # no bucket
+    assert mk(1, 1) == -1                # not increasing
+    assert mk(1, 4) == -1                # beyond the context's batch of 2
+    assert lib.tlt_graph_pool_step(None, None, 1, 1, 1, 2, None) == -1
+    assert lib.tlt_graph_pool_destroy(None) == 0
     assert lib.tlt_destroy(h) == 0

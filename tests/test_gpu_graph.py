@@ -1,4 +1,5 @@
-"""The HIP-graph pool (bucketed, disaggregated, merged capture of the SD step; Section 5.1): every
+"""The HIP-graph pool (bucketed, disaggregated, merged capture of the SD step; Section 5.1), the library's own
+(tlt_graph_pool_*) and the one the Python engine keeps with torch's capture: every
 replay must reproduce the eager step exactly, across several replays with other GPU work in between,
 with strategies alternating so that graphs are shared and re-used; and capturing must not cost
 device memory per graph."""
@@ -14,7 +15,8 @@ from gpu_util import make_engine, make_models
 pytestmark = pytest.mark.gpu
 
 
-def test_graph_replays_match_eager_steps_and_graphs_are_shared():
+@pytest.mark.parametrize("native", [False, True], ids=["torch-capture", "library-pool"])
+def test_graph_replays_match_eager_steps_and_graphs_are_shared(native):
     cfg = MID
     B, P = 4, 40
     tw_dev, dw_dev, _, _ = make_models(cfg, 21, "bf16", std=0.05)
@@ -27,7 +29,7 @@ def test_graph_replays_match_eager_steps_and_graphs_are_shared():
         engines.append(e)
     eager, graphed = engines
     free0 = torch.cuda.mem_get_info()[0]
-    pool = graphed.graph_pool()
+    pool = graphed.graph_pool(native=native)
     # the first step runs eagerly on both: it creates the pending hidden state the pool's steps start from
     K, D, N = strategies[0]
     a0, o0 = eager.step(K, D, N)
@@ -54,7 +56,8 @@ def test_graph_replays_match_eager_steps_and_graphs_are_shared():
         e.ctx.close()
 
 
-def test_smaller_batch_uses_the_bucket_graph():
+@pytest.mark.parametrize("native", [False, True], ids=["torch-capture", "library-pool"])
+def test_smaller_batch_uses_the_bucket_graph(native):
     cfg = MID
     B, P = 8, 24
     tw_dev, dw_dev, _, _ = make_models(cfg, 22, "bf16", std=0.05)
@@ -64,7 +67,7 @@ def test_smaller_batch_uses_the_bucket_graph():
     for x in (e, ref):
         x.prefill(pr)
         x.step(2, 3, 8)
-    pool = e.graph_pool()
+    pool = e.graph_pool(native=native)
     assert pool.bucket(3) == 4 and pool.bucket(5) == 8 and pool.bucket(1) == 1
     want_al, want_out = ref.step(2, 3, 8)
     pool.step(3, 2, 3, 8)                      # 3 running sequences -> bucket of 4: slots 0..3 advance
