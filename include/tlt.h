@@ -264,7 +264,9 @@ typedef struct tlt_step_args {
     int32_t stride;
     int32_t *accept_len, *path_idx, *out_tokens, *n_out;   /* as tlt_accept */
 } tlt_step_args;
-/* buckets: HOST, strictly increasing batch sizes, each <= the context's max_batch. */
+/* buckets: HOST, strictly increasing batch sizes, each <= the context's max_batch.  The pool refers to the
+ * context: destroy the pool first.  Errors: TLT_EINVAL (arguments), TLT_ESHAPE (B above the largest bucket),
+ * TLT_EHIP (capture, instantiation or launch failed: tlt_last_hip_error), or whatever the captured calls return. */
 int tlt_graph_pool_create(tlt_ctx *ctx, const int32_t *buckets, int n_buckets, int seq_len_bound, tlt_graph_pool **out);
 int tlt_graph_pool_destroy(tlt_graph_pool *pool);
 int tlt_graph_pool_step(tlt_graph_pool *pool, void *stream, int B, int depth, int topk, int n_verify,
