@@ -335,6 +335,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
             pa_ = sa; pb_ = sb; sa = na; sb = nb;
         }
         // the tile is complete: store it and clear the accumulators while the next tile's loads land
+        __builtin_amdgcn_sched_barrier(0);
         if constexpr (OUT == OUT_ROWMAX) {
             // best (value, column) of each of this wave's WTM*32 rows over its WTN*32 columns: first over a
             // lane's own WTN columns of the row, then across the 32 lanes that hold the row's other
@@ -414,7 +415,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                         float r[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float g = acc[i][jj][4 * vq + e], u = acc[i][jj + WTN / 2][4 * vq + e];
+                            // (the accumulators leave their registers here and nowhere earlier: left to itself the
+                            // compiler copies most of the tile out first and spills)
+                            float g, u;
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(g) : "a"(acc[i][jj][4 * vq + e]));
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(u) : "a"(acc[i][jj + WTN / 2][4 * vq + e]));
                             // (hardware reciprocal, 1 ulp: the result is rounded to bf16 anyway, and an IEEE division
                             // per element costs the tile epilogue several microseconds)
                             r[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
@@ -430,6 +435,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                         out.y = hi2 ? w23 : other;
                         const int col = ti.n0 + wn * (WTN / 2 * 32) + jj * 32 + (l32 & ~3);
                         if (row < M) *(uint2*)((bf16*)C + (int64_t)row * N + col) = out;
+                        // (keeps the compiler from fetching all accumulators first: that spills, and a reload from
+                        // scratch waits for every load in flight, the next tile's first K tiles included)
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
