@@ -623,7 +623,16 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     // weights faster)
     // one row of big tiles, a hundred or more of them, streams cold weights faster than twice as
     // many TA-bound small ones
-    if (nbm256 == 1 && M > 64 && tiles256 >= 100 && tiles256 < 256 && N % bno256 == 0) return big(N);
+    // (however many rounds: cutting the launch into whole rounds of big tiles plus a rest of small ones, as below,
+    // pays when several row tiles share a weight tile; with one row of tiles the single launch is 4-6 % faster, LM
+    // head at M = 256)
+    if (nbm256 == 1 && M > 128 && tiles256 >= 100 && N % bno256 == 0) return big(N);
+    // up to 128 rows: half of a 256-row tile would be padding, and the LDS it frees holds a third weight slot
+    // (gate/up at M = 128: 85 -> 70 us, LM head: 261 -> 251; at the 32B shape 406 -> 343)
+    if (M > 64 && M <= 128 && tiles256 >= 100 && N % bno256 == 0) {
+        if (glu) return launch_pipe<2, 2, 2, 4, 3, 3, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
+        return launch_pipe<2, 2, 2, 4, 3, 3>(s, out_mode, M, N, K, A, W, C, nullptr, 1, N);
+    }
     if (M <= 64 || tiles256 < 256) return small(N, 0);
     const int full_rounds = tiles256 / 256;
     const int main_nbn = full_rounds * 256 / nbm256;          // column tiles that make up the whole rounds

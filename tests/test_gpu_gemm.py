@@ -48,6 +48,8 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (1000, 16768, 128),   # 256x256 tiles for the whole rounds of the chip + 128x128 tiles for the remaining columns
     (200, 512, 1600),     # 25 K tiles split unevenly over 3 workgroups per tile... when the chip is under-filled
     (1500, 3584, 256),    # 192x128 tiles (more than one round of 128-row tiles, one of 192-row tiles), ragged M tail
+    (100, 25600, 192),    # one row of 128x256 tiles (at most 128 rows, a hundred column tiles or more), ragged M
+    (200, 66048, 128),    # one row of 256x256 tiles, more than a round of them, in a single launch
 ])
 def test_gemm_bf16(M, N, K, out_mode):
     _case(M, N, K, tlt.TLT_BF16, out_mode, 2)
@@ -133,10 +135,12 @@ def test_fused_row_argmax_refuses_shapes_it_does_not_cover():
     assert tlt.gemm_argmax(A, W, ws[:16], out) == -2                           # scratch too small
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1536, 18944, 256), (1000, 16512, 192), (129, 128, 640)])
+@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1536, 18944, 256), (1000, 16512, 192), (129, 128, 640),
+                                   (100, 25600, 256), (200, 33024, 128)])
 def test_fused_gate_up_projection_matches_float64(M, N, K):
     """tlt_gemm_glu: silu(A Wg^T) * (A Wu^T) in one kernel (256-row weight tiles for the whole rounds of
-    the chip, 128-row tiles for the rest, ragged M tail), against float64 on sampled rows."""
+    the chip, 128-row tiles for the rest, ragged M tail; one row of 128x256 or 256x256 tiles when M is small),
+    against float64 on sampled rows."""
     g = torch.Generator().manual_seed(M + K)
     A = torch.randn((M, K), generator=g).bfloat16()
     Wg = (torch.randn((N, K), generator=g) * 0.1).bfloat16()
