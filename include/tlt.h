@@ -283,7 +283,7 @@ int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const v
 
 /* act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 DEVICE operands and result: the fused gate/up projection of
  * the decoder block's MLP (the two products never reach memory).  TLT_ENOTIMPL when the shape is not
- * covered (N % 128, K % 64, misaligned operands). */
+ * covered (N % 128, K % 64, operands not 16-byte aligned, act not 8-byte aligned). */
 int tlt_gemm_glu(void *stream, int M, int N, int K, const void *A, const void *Wg, const void *Wu, void *act);
 
 /* out[m] = argmax_n (A W^T)[m][n] (lowest n on ties) for bf16 DEVICE operands, without storing the

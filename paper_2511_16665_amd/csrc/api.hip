@@ -907,7 +907,7 @@ int tlt_attention(void* stream, int dtype, int B, int n, int n_q_heads, int n_kv
 
 int tlt_gemm_glu(void* stream, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
     if (M < 1 || N < 1 || K < 1 || !A || !Wg || !Wu || !act) return TLT_EINVAL;
-    if (!gemm_glu_supported(TLT_BF16, M, N, K, A, Wg, Wu)) return TLT_ENOTIMPL;
+    if (!gemm_glu_supported(TLT_BF16, M, N, K, A, Wg, Wu) || ((uintptr_t)act & 7) != 0) return TLT_ENOTIMPL;   // (8-byte stores)
     return gemm_glu((hipStream_t)stream, M, N, K, A, Wg, Wu, act) == hipSuccess ? TLT_OK : TLT_EHIP;
 }
 
