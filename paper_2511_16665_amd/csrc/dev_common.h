@@ -64,6 +64,47 @@ __device__ __forceinline__ void dma_global_to_lds_16(const void* gptr, uint32_t 
 // larger value first, lower index on equal values.
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
+// The wave's best (value, index) pair in the (value desc, index asc) order, left in every lane.  The order is total,
+// so the result does not depend on how the lanes are paired; the pairing here avoids the LDS crossbar that a
+// shuffle goes through (a dozen dependent ds_bpermute of ~100 clocks each per reduction): the two half-waves and the
+// odd and even 16-lane rows trade through v_permlane32_swap / v_permlane16_swap (swapping a register with a copy of
+// itself leaves the own and the partner's value side by side), the lanes of a row through DPP rotations by 8 and 4
+// and the two quad permutations.
+__device__ __forceinline__ void wave_best(float& v, int& i) {
+    {
+        const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        const auto b = __builtin_amdgcn_permlane32_swap((uint32_t)i, (uint32_t)i, false, false);
+        const float v0 = __uint_as_float(a[0]), v1 = __uint_as_float(a[1]);
+        const int i0 = (int)b[0], i1 = (int)b[1];
+        const bool first = better(v0, i0, v1, i1);
+        v = first ? v0 : v1;
+        i = first ? i0 : i1;
+    }
+    {
+        const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        const auto b = __builtin_amdgcn_permlane16_swap((uint32_t)i, (uint32_t)i, false, false);
+        const float v0 = __uint_as_float(a[0]), v1 = __uint_as_float(a[1]);
+        const int i0 = (int)b[0], i1 = (int)b[1];
+        const bool first = better(v0, i0, v1, i1);
+        v = first ? v0 : v1;
+        i = first ? i0 : i1;
+    }
+#define TLT_BEST_DPP(ctrl)                                                                                   \
+    {                                                                                                        \
+        const float ov = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xF, 0xF, false)); \
+        const int oi = __builtin_amdgcn_update_dpp(0, i, ctrl, 0xF, 0xF, false);                             \
+        if (better(ov, oi, v, i)) {                                                                          \
+            v = ov;                                                                                          \
+            i = oi;                                                                                          \
+        }                                                                                                    \
+    }
+    TLT_BEST_DPP(0x128)   // row_ror:8
+    TLT_BEST_DPP(0x124)   // row_ror:4
+    TLT_BEST_DPP(0x4E)    // quad_perm:[2,3,0,1]
+    TLT_BEST_DPP(0xB1)    // quad_perm:[1,0,3,2]
+#undef TLT_BEST_DPP
+}
+
 // Physical row of cache slot `slot` of sequence b, or -1 when the block table cannot serve it.
 // Row index is in units of [page_size] rows of one kv head: caller multiplies out the layout.
 struct PageRef {

@@ -10,15 +10,7 @@ namespace tlt {
 // ------------------------------------------------------------------------------------------------
 // block-wide helpers (256 threads = 4 waves)
 __device__ __forceinline__ void block_best(float& v, int& i, float* sv, int* si) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(v, o, 64);
-        int oi = __shfl_xor(i, o, 64);
-        if (better(ov, oi, v, i)) {
-            v = ov;
-            i = oi;
-        }
-    }
+    wave_best(v, i);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
         sv[threadIdx.x >> 6] = v;
@@ -209,15 +201,7 @@ __global__ __launch_bounds__(256) void row_topk_seg_k(int V, int K, int n_seg, c
     for (int k = 0; k < K; ++k) {
         float wv = cv;
         int wi = ci;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(wv, off, 64);
-            const int oi = __shfl_xor(wi, off, 64);
-            if (better(ov, oi, wv, wi)) {
-                wv = ov;
-                wi = oi;
-            }
-        }
+        wave_best(wv, wi);
         if (lane == 0) {
             const bool have = wi != 0x7fffffff;
             seg_val[o * K + k] = have ? wv : -INFINITY;
@@ -266,29 +250,47 @@ __global__ __launch_bounds__(64) void row_topk_merge_k(int K, int n_seg, const f
     se = wave_sum(se);
     const float lse = mx + logf(se);
     const int n_cand = n_seg * K;
+    // the candidates are read once: a lane keeps up to kMergeRegs of them in registers (75 segments x 8 at the
+    // 152064-token vocabulary: 10 per lane); longer lists are scanned from memory in every round
+    constexpr int kMergeRegs = 20;
+    const bool in_regs = n_cand <= 64 * kMergeRegs;
+    float rv[kMergeRegs];
+    int rj[kMergeRegs];
+#pragma unroll
+    for (int r = 0; r < kMergeRegs; ++r) {
+        const int c = lane + 64 * r;
+        const bool on = in_regs && c < n_cand;
+        rv[r] = on ? seg_val[o * K + c] : -INFINITY;
+        rj[r] = on ? seg_idx[o * K + c] : 0x7fffffff;
+    }
     float pv = INFINITY;
     int pi = -1;
     for (int k = 0; k < K; ++k) {
         float cv = -INFINITY;
         int ci = 0x7fffffff;
-        for (int c = lane; c < n_cand; c += 64) {
-            float v = seg_val[o * K + c];
-            int j = seg_idx[o * K + c];
-            bool after = v < pv || (v == pv && j > pi);
-            if (j != 0x7fffffff && after && better(v, j, cv, ci)) {
-                cv = v;
-                ci = j;
-            }
-        }
+        if (in_regs) {
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            float ov = __shfl_xor(cv, off, 64);
-            int oi = __shfl_xor(ci, off, 64);
-            if (better(ov, oi, cv, ci)) {
-                cv = ov;
-                ci = oi;
+            for (int r = 0; r < kMergeRegs; ++r) {
+                const float v = rv[r];
+                const int j = rj[r];
+                const bool after = v < pv || (v == pv && j > pi);
+                if (j != 0x7fffffff && after && better(v, j, cv, ci)) {
+                    cv = v;
+                    ci = j;
+                }
+            }
+        } else {
+            for (int c = lane; c < n_cand; c += 64) {
+                float v = seg_val[o * K + c];
+                int j = seg_idx[o * K + c];
+                bool after = v < pv || (v == pv && j > pi);
+                if (j != 0x7fffffff && after && better(v, j, cv, ci)) {
+                    cv = v;
+                    ci = j;
+                }
             }
         }
+        wave_best(cv, ci);
         pv = cv;
         pi = ci;
         if (lane == 0) {
