@@ -89,6 +89,34 @@ def test_gemm_bf16_7b_layer_shape_sampled_rows():
     assert np.abs(got - want).max() <= 2e-3 * np.abs(want).max()
 
 
+@pytest.mark.parametrize("M", [40, 100, 256])
+def test_lm_head_shape_with_few_rows_sampled_entries(M):
+    """The LM head of the 7B workload at the row counts of the drafter's levels and of the long-tail verification
+    (40: K-cut-free 128x128 tiles; 100: one row of 128x256 tiles; 256: 594 tiles of 256x256 in a single launch, two
+    or three per workgroup): sampled rows against float64, every column."""
+    N, K = 152064, 3584
+    g = torch.Generator().manual_seed(40 + M)
+    A = torch.randn((M, K), generator=g).bfloat16()
+    W = torch.empty((N, K), dtype=torch.bfloat16)
+    for c0 in range(0, N, 19008):                                  # (drawn in pieces: the fp32 draws of the whole matrix are 2.2 GB)
+        W[c0:c0 + 19008] = (torch.randn((19008, K), generator=g) * 0.02).bfloat16()
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    print(f"LM-head shape M={M}", flush=True)
+    tlt.gemm(tlt.TLT_BF16, 1, A.cuda(), W.cuda(), out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all().item()
+    rows = sorted({0, 1, 31, M // 2, M - 1})
+    a = A[rows].double().numpy()
+    got = out[rows].double().cpu().numpy()
+    scale = 0.0
+    worst = 0.0
+    for c0 in range(0, N, 19008):
+        want = a @ W[c0:c0 + 19008].double().numpy().T
+        scale = max(scale, np.abs(want).max())
+        worst = max(worst, np.abs(got[:, c0:c0 + 19008] - want).max())
+    assert worst <= 2e-3 * scale
+
+
 @pytest.mark.parametrize("M,N,K,ties", [(1536, 8192, 256, False), (300, 1024, 192, False), (1000, 4096, 320, True),
                                         (129, 512, 3584, False), (1536, 152064, 256, False)])
 def test_fused_row_argmax_equals_argmax_of_the_stored_product(M, N, K, ties):
