@@ -623,10 +623,21 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     // weights faster)
     // one row of big tiles, a hundred or more of them, streams cold weights faster than twice as
     // many TA-bound small ones
-    // (however many rounds: cutting the launch into whole rounds of big tiles plus a rest of small ones, as below,
-    // pays when several row tiles share a weight tile; with one row of tiles the single launch is 4-6 % faster, LM
-    // head at M = 256)
-    if (nbm256 == 1 && M > 128 && tiles256 >= 100 && N % bno256 == 0) return big(N);
+    if (nbm256 == 1 && M > 128 && tiles256 >= 100 && N % bno256 == 0) {
+        // more than a round of them (the LM head: 594 tiles): the whole rounds, then what is left in 256x128 tiles,
+        // so that the last, partly filled round is half as long (best of four interleaved runs, M = 160 .. 256:
+        // 287-312 us in one launch, 267-296 this way, 267-311 with a rest of 128x128 tiles; 32B shape 401-436 /
+        // 372-410 / 369-435)
+        const int main_tiles = tiles256 / 256 * 256;
+        if (!glu && main_tiles > 0 && main_tiles < tiles256) {
+            hipError_t e = big(main_tiles * 256);
+            if (e != hipSuccess) return e;
+            const void* w = (const uint16_t*)W + (int64_t)main_tiles * 256 * K;
+            void* c = (char*)C + (size_t)main_tiles * 256 * c_elt;
+            return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
+        }
+        return big(N);
+    }
     // up to 128 rows: half of a 256-row tile would be padding, and the LDS it frees holds a third weight slot
     // (gate/up at M = 128: 85 -> 70 us, LM head: 261 -> 251; at the 32B shape 406 -> 343)
     if (M > 64 && M <= 128 && tiles256 >= 100 && N % bno256 == 0) {
