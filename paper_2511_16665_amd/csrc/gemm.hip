@@ -642,6 +642,15 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     // (gate/up at M = 128: 85 -> 70 us, LM head: 261 -> 251; at the 32B shape 406 -> 343)
     if (M > 64 && M <= 128 && tiles256 >= 100 && N % bno256 == 0) {
         if (glu) return launch_pipe<2, 2, 2, 4, 3, 3, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
+        // (more than a round: whole rounds, the rest in 128x128 tiles: LM head 227-250 -> 219-241 us, 32B shape 313-343 -> 297-325)
+        const int main_tiles = tiles256 / 256 * 256;
+        if (main_tiles > 0 && main_tiles < tiles256) {
+            hipError_t e = launch_pipe<2, 2, 2, 4, 3, 3>(s, out_mode, M, main_tiles * 256, K, A, W, C, nullptr, 1, N);
+            if (e != hipSuccess) return e;
+            const void* w = (const uint16_t*)W + (int64_t)main_tiles * 256 * K;
+            void* c = (char*)C + (size_t)main_tiles * 256 * c_elt;
+            return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
+        }
         return launch_pipe<2, 2, 2, 4, 3, 3>(s, out_mode, M, N, K, A, W, C, nullptr, 1, N);
     }
     if (M <= 64 || tiles256 < 256) return small(N, 0);

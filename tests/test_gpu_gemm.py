@@ -50,7 +50,8 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (1500, 3584, 256),    # 192x128 tiles (more than one round of 128-row tiles, one of 192-row tiles), ragged M tail
     (48, 3584, 2048),     # a handful of rows: 128x128 tiles, K cut four ways when accumulating (mode 2)
     (100, 25600, 192),    # one row of 128x256 tiles (at most 128 rows, a hundred column tiles or more), ragged M
-    (200, 66048, 128),    # one row of 256x256 tiles, more than a round of them, in a single launch
+    (200, 66048, 128),    # one row of 256x256 tiles, more than a round of them: whole rounds + a rest of 256x128 tiles
+    (100, 66304, 128),    # one row of 128x256 tiles, more than a round: whole rounds + a rest of 128x128 tiles
 ])
 def test_gemm_bf16(M, N, K, out_mode):
     _case(M, N, K, tlt.TLT_BF16, out_mode, 2)
@@ -92,8 +93,8 @@ def test_gemm_bf16_7b_layer_shape_sampled_rows():
 @pytest.mark.parametrize("M", [40, 100, 256])
 def test_lm_head_shape_with_few_rows_sampled_entries(M):
     """The LM head of the 7B workload at the row counts of the drafter's levels and of the long-tail verification
-    (40: K-cut-free 128x128 tiles; 100: one row of 128x256 tiles; 256: 594 tiles of 256x256 in a single launch, two
-    or three per workgroup): sampled rows against float64, every column."""
+    (40: 128x128 tiles; 100: two rounds of 128x256 tiles and a rest of 128x128 tiles; 256: two rounds of 256x256 tiles
+    and a rest of 256x128 tiles): sampled rows against float64, every column."""
     N, K = 152064, 3584
     g = torch.Generator().manual_seed(40 + M)
     A = torch.randn((M, K), generator=g).bfloat16()
