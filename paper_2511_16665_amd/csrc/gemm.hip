@@ -660,9 +660,20 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     const int rest_tiles256 = tiles256 - main_nbn * nbm256 + (N % bno256 ? nbm256 : 0);
     if (main_nbn == 0) return N % bno256 == 0 ? big(N) : small(N, 0);
     if (rest_cols == 0) return big(N);
-    if (rest_tiles256 > 160 && N % bno256 == 0) return big(N);   // the last round is well filled as it is
+    if (rest_tiles256 >= 140 && N % bno256 == 0) return big(N);   // the last round is well filled as it is
     hipError_t e = big(main_nbn * bno256);
     if (e != hipSuccess) return e;
+    // the rest in 256x128 tiles, one per CU (gate/up, best of four interleaved runs: M = 1536, a rest of 120 big
+    // tiles: 331 us with 128x128 tiles, 323 this way, 347 in one launch of big tiles; M = 1024, rest 80: 249 /
+    // 232 / 255; M = 2048, rest 160: 468 / 454 / 435)
+    if (rest_cols % bno256 == 0) {
+        const int col0 = main_nbn * bno256;
+        const void* w = (const uint16_t*)W + (int64_t)col0 * K;
+        const void* w2 = W2 ? (const uint16_t*)W2 + (int64_t)col0 * K : nullptr;
+        void* c = (char*)C + (size_t)col0 * c_elt;
+        if (glu) return launch_pipe<2, 2, 4, 2, 3, 4, true>(s, OUT_T, M, rest_cols, K, A, w, c, w2, 1, N);
+        return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, rest_cols, K, A, w, c, nullptr, 1, N);
+    }
     return small(rest_cols, main_nbn * bno256);
 }
 

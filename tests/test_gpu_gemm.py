@@ -46,6 +46,7 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (50, 200, 96),        # shape the MFMA path cannot take -> generic kernel on bf16
     (1100, 3584, 2048),   # few 256x256 tiles, long K: split-K with atomic accumulation in mode 2, ragged M tail
     (1000, 16768, 128),   # 256x256 tiles for the whole rounds of the chip + 128x128 tiles for the remaining columns
+    (1000, 16896, 128),   # 256x256 tiles for the whole rounds of the chip + 256x128 tiles for the remaining columns
     (200, 512, 1600),     # 25 K tiles split unevenly over 3 workgroups per tile... when the chip is under-filled
     (1500, 3584, 256),    # 192x128 tiles (more than one round of 128-row tiles, one of 192-row tiles), ragged M tail
     (48, 3584, 2048),     # a handful of rows: 128x128 tiles, K cut four ways when accumulating (mode 2)
