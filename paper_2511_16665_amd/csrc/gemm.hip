@@ -606,11 +606,18 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
             if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
             return launch_pipe<2, 2, 2, 2, 3, 3, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
         }
-        // more than one round of 128-row tiles at two workgroups per CU, but 192-row tiles fit the chip
-        // once: one workgroup per CU with the CU to itself (o projection at M = 1536: 336 tiles -> 224,
-        // 49.9 -> 43.0 us)
-        if (tiles > 256 && ((M + 191) / 192) * (n_cols / bno128) <= 256)
-            return launch_pipe<2, 2, 3, 2, 3, 4>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+        // more 128-row tiles than CUs (some CUs would hold two workgroups and take twice as long as the others), but
+        // 192- or 256-row tiles fit the chip once: one workgroup per CU with the CU to itself, whichever of the two
+        // fills more of the CUs (o projection at M = 1536: 336 tiles -> 224 of 192 rows, 49.9 -> 43.0 us; qkv at
+        // M = 1536: 432 -> 216 of 256 rows, 59.8 -> 54.2 us; o at M = 2048: 448 -> 224 of 256 rows, 62.4 -> 51.0 us;
+        // best of four interleaved runs on cold weights)
+        if (tiles > 256) {
+            const int t192 = ((M + 191) / 192) * (n_cols / bno128), t256 = nbm256 * (n_cols / bno128);
+            const bool fit192 = t192 <= 256, fit256 = t256 <= 256 && t256 >= 200;
+            if (fit256 && (!fit192 || t256 >= t192))
+                return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+            if (fit192) return launch_pipe<2, 2, 3, 2, 3, 4>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+        }
         if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
         return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
     };

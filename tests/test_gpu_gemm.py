@@ -49,6 +49,7 @@ def test_gemm_fp32_generic(M, N, K, out_mode):
     (1000, 16896, 128),   # 256x256 tiles for the whole rounds of the chip + 256x128 tiles for the remaining columns
     (200, 512, 1600),     # 25 K tiles split unevenly over 3 workgroups per tile... when the chip is under-filled
     (1500, 3584, 256),    # 192x128 tiles (more than one round of 128-row tiles, one of 192-row tiles), ragged M tail
+    (1530, 4608, 256),    # 256x128 tiles (432 tiles of 128 rows would oversubscribe the chip, 216 of 256 rows fill it once), ragged M tail
     (48, 3584, 2048),     # a handful of rows: 128x128 tiles, K cut four ways when accumulating (mode 2)
     (100, 25600, 192),    # one row of 128x256 tiles (at most 128 rows, a hundred column tiles or more), ragged M
     (200, 66048, 128),    # one row of 256x256 tiles, more than a round of them: whole rounds + a rest of 256x128 tiles
