@@ -709,6 +709,31 @@ static SplitPlan plan_split(int M, int N, int K) {
             return sp;
         }
     }
+    // up to 256 rows (the drafter's levels, the long-tail verification), swept over tile shape and number of cuts
+    // on cold weights, best of three interleaved runs: as many cuts as put one workgroup on every CU, at most 8,
+    // at least 8 K tiles each, no skew.  128x128 tiles up to 128 rows (q/k/v at M = 128: 17.0 -> 12.4 us, o 14.9 ->
+    // 10.2, down 41.8 -> 32.6, fc 21.2 -> 16.2) and above while a cut stays short (o at M = 256: 19.0 -> 12.5,
+    // q/k/v 21.1 -> 17.5); with a long K the 256x128 tiles below, more cuts than the square-root rule that was
+    // tuned for atomic accumulation gave them (down at M = 256: 48.3 -> 42.9 us, fc 28.0 -> 24.0)
+    if (M > 64 && M <= 256 && N % 128 == 0) {
+        const int nk = K / kBK, t128 = ((M + 127) / 128) * (N / 128);
+        if (t128 < 200) {
+            int ks3 = 256 / t128;
+            if (ks3 > nk / 8) ks3 = nk / 8;
+            if (ks3 > 8) ks3 = 8;
+            if (ks3 >= 2 && (M <= 128 || nk / ks3 <= 32)) {
+                sp.kind = 3, sp.ks = ks3, sp.skew = 0;
+                return sp;
+            }
+            int ks1 = 256 / (N / 128);
+            if (ks1 > nk / 8) ks1 = nk / 8;
+            if (ks1 > 8) ks1 = 8;
+            if (ks1 >= 2) {
+                sp.kind = 1, sp.ks = ks1, sp.skew = 0;
+                return sp;
+            }
+        }
+    }
     if (N % 128 == 0) {
         const int nk = K / kBK, tiles = ((M + 255) / 256) * (N / 128);
         if (tiles < 200) {
