@@ -57,7 +57,8 @@ bool plan_workspace(const tlt_model_cfg& c, int B, int n, int D, int K, int max_
     p.xn = take(R * 2 * h * esz);
     p.qkv = take(R * qkv_dim * esz);
     // fp32 partial products of the projections whose sum joins the fp32 residual stream (or feeds the rotary kernel)
-    p.parts_bytes = std::max(c.dtype == TLT_BF16 ? gemm_parts_max_bytes() : (size_t)0, R * std::max(h, qkv_dim) * 4);
+    // (room for four slices of the widest product at the largest row count; a plan with more cuts than fit is not taken)
+    p.parts_bytes = std::max(c.dtype == TLT_BF16 ? gemm_parts_max_bytes() : (size_t)0, (c.dtype == TLT_BF16 ? 4 : 1) * R * std::max(h, qkv_dim) * 4);
     p.parts = take(p.parts_bytes);
     p.att = take(R * (size_t)c.n_q_heads * c.head_dim * esz);
     p.g = take(R * F * esz);

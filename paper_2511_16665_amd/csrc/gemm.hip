@@ -684,100 +684,52 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
     return small(rest_cols, main_nbn * bno256);
 }
 
-// How a product that accumulates into fp32 is cut along K (bf16 MFMA path).  kind 0: not at all; 1: 256x128
-// tiles (few rows); 2: 256x256 tiles; 3: 128x128 tiles (a handful of rows).
+// How a product whose fp32 result is summed by its consumer is cut along K (bf16 MFMA path).  kind 0: not at all;
+// 1: 256x128 tiles; 2: 256x256 tiles; 3: 128x128 tiles.
+//
+// The plan is the minimum of a small cost model over (tile shape, number of cuts).  A launch takes a ramp plus, for
+// every round of workgroups the chip has to run (one per CU; 128x128 tiles past 256 workgroups share CUs in pairs and
+// run slower), the K steps of a cut at the tile shape's clocks per step plus its epilogue; every cut after the first
+// adds M*N*4 bytes that the consumer (the norm or rotary kernel that sums the slices) reads at ~4 TB/s.  The
+// constants were fitted to a sweep on the chip (nine projection shapes of the 7B / 32B / 70B models, M = 96 .. 1536,
+// kinds 1-3, 1-12 cuts, cold weights, best of three interleaved runs, even cuts): the model's pick is within 0.9 %
+// of the best measured plan on average (worst case 11 %), where the rules it replaces were 7.8 % off on average and
+// up to 49 % (M = 384 .. 1024).  Uneven cuts, which paid when the cuts accumulated with atomics, lost 3-5 % to even
+// ones in the same sweep, so the cuts are even.
 struct SplitPlan {
     int kind = 0, ks = 1, skew = 0;
 };
-static SplitPlan plan_split(int M, int N, int K) {
+static SplitPlan plan_split(int M, int N, int K, int max_ks = 12) {
     SplitPlan sp;
-    const int tiles256 = ((M + 255) / 256) * (N / 256);
-    // too few 256x256 tiles for the chip but a long K and an fp32 sum as output: split K over several
-    // workgroups per tile.
-    // few rows (M <= 256 is one row of tiles: the drafter's projections, a verification forward over a
-    // handful of tree nodes; up to a few hundred rows the picture is the same): the weights stream from HBM,
-    // so what counts is how many workgroups pull on them and how little partial-sum traffic the split costs.
-    // 256x128 tiles halve both the tile count needed per split and the bytes of every partial tile.
-    // up to 64 rows: three quarters of a 256-row tile would be padding; 128x128 tiles, as many cuts as fill the chip
-    // (M = 32: q/k/v 12.7 -> 11.6 us, o 14.2 -> 11.2, down 31.9 -> 27.9, the drafter's fc 15.6 -> 13.0)
-    if (M <= 64 && N % 128 == 0 && N / 128 < 200) {
-        const int nk = K / kBK;
-        int ks = 256 / (N / 128);
-        if (ks > nk / 8) ks = nk / 8;
-        if (ks >= 2) {
-            sp.kind = 3, sp.ks = ks, sp.skew = 0;
-            return sp;
-        }
-    }
-    // up to 256 rows (the drafter's levels, the long-tail verification), swept over tile shape and number of cuts
-    // on cold weights, best of three interleaved runs: as many cuts as put one workgroup on every CU, at most 8,
-    // at least 8 K tiles each, no skew.  128x128 tiles up to 128 rows (q/k/v at M = 128: 17.0 -> 12.4 us, o 14.9 ->
-    // 10.2, down 41.8 -> 32.6, fc 21.2 -> 16.2) and above while a cut stays short (o at M = 256: 19.0 -> 12.5,
-    // q/k/v 21.1 -> 17.5); with a long K the 256x128 tiles below, more cuts than the square-root rule that was
-    // tuned for atomic accumulation gave them (down at M = 256: 48.3 -> 42.9 us, fc 28.0 -> 24.0)
-    if (M > 64 && M <= 256 && N % 128 == 0) {
-        const int nk = K / kBK, t128 = ((M + 127) / 128) * (N / 128);
-        if (t128 < 200) {
-            int ks3 = 256 / t128;
-            if (ks3 > nk / 8) ks3 = nk / 8;
-            if (ks3 > 8) ks3 = 8;
-            if (ks3 >= 2 && (M <= 128 || nk / ks3 <= 32)) {
-                sp.kind = 3, sp.ks = ks3, sp.skew = 0;
-                return sp;
+    if (N % 128 != 0 || M < 1) return sp;
+    const int nk = K / kBK;
+    const int nbm256 = (M + 255) / 256, nbm128 = (M + 127) / 128;
+    auto cost_us = [&](int kind, int ks) -> double {
+        int tiles;
+        double step_clk, epilogue_clk;
+        if (kind == 1) tiles = nbm256 * (N / 128), step_clk = 1396, epilogue_clk = 9827;
+        else if (kind == 2) tiles = nbm256 * (N / 256), step_clk = 2266, epilogue_clk = 18240;
+        else tiles = nbm128 * (N / 128), step_clk = 988, epilogue_clk = 5754;
+        const int wgs = tiles * ks;
+        const double steps = (double)nk / ks;
+        double clk;
+        if (kind == 3 && wgs > 256) clk = (double)((wgs + 511) / 512) * (steps * 2390 + epilogue_clk);
+        else clk = (double)((wgs + 255) / 256) * (steps * step_clk + epilogue_clk);
+        return 1.6 + clk / 1800.0 + (ks - 1) * (double)M * N * 4.0 / 4.0e6;
+    };
+    // (not cut at all, the product takes the tiled launcher's own pick of a tile shape: the best of the three here)
+    double best = cost_us(1, 1);
+    if (cost_us(3, 1) < best) best = cost_us(3, 1);
+    if (N % 256 == 0 && cost_us(2, 1) < best) best = cost_us(2, 1);
+    if (max_ks > 12) max_ks = 12;
+    for (int kind = 1; kind <= 3; ++kind) {
+        if (kind == 2 && N % 256 != 0) continue;
+        for (int ks = 2; ks <= max_ks && nk / ks >= 6; ++ks) {
+            const double c = cost_us(kind, ks);
+            if (c < best) {
+                best = c;
+                sp.kind = kind, sp.ks = ks, sp.skew = 0;
             }
-            int ks1 = 256 / (N / 128);
-            if (ks1 > nk / 8) ks1 = nk / 8;
-            if (ks1 > 8) ks1 = 8;
-            if (ks1 >= 2) {
-                sp.kind = 1, sp.ks = ks1, sp.skew = 0;
-                return sp;
-            }
-        }
-    }
-    if (N % 128 == 0) {
-        const int nk = K / kBK, tiles = ((M + 255) / 256) * (N / 128);
-        if (tiles < 200) {
-            int ks = 256 / tiles;
-            if (ks > nk / 8) ks = nk / 8;
-            // fewer splits when the partial tiles weigh more than the K steps they save: a workgroup
-            // alone on its CU takes ~0.6 us per K step, a split adds M*N*4 bytes of partial-sum traffic at
-            // ~1.75 TB/s; the sum nk*0.6/ks + ks*M*N*4/1.75e6 us is smallest at the square root of the ratio
-            // (qkv-sized product at M = 256: 37 us with 7 splits, 27 with 3-4; the down projection keeps its 9)
-            {
-                const double per_split_us = (double)M * N * 4.0 / 1.75e6;
-                const int best = (int)(sqrt(0.6 * nk / per_split_us) + 0.5);
-                if (best < ks) ks = best < 1 ? 1 : best;
-            }
-            // four weight slots: with a handful of rows nothing but the cold weight stream matters, and
-            // the deeper ring keeps more of it in flight (31.7 against 39.5 us on the down projection at M = 32)
-            if (ks >= 2) {
-                // uneven splits once the partial tiles weigh something (down projection at M = 256:
-                // 60 -> 54 us; at M = 32 the even cut is better, 32 against 36 us)
-                int skew = M >= 128 ? 8 : 0;
-                if (skew > nk / ks / 4) skew = nk / ks / 4;
-                sp.kind = 1, sp.ks = ks, sp.skew = skew;
-                return sp;
-            }
-        }
-    }
-    if (N % 256 == 0 && tiles256 < 256 && tiles256 > 0) {
-        const int nk = K / kBK;
-        int ks = 256 / tiles256;
-        // at least 16 K tiles per split (8 when M is small: the weights then stream from HBM and the
-        // number of workgroups pulling on them matters more than the partial tiles' epilogues)
-        const int min_k_tiles = M <= 256 ? 8 : 16;
-        if (ks > nk / min_k_tiles) ks = nk / min_k_tiles;
-        // every split ends with a 256x256 partial tile: worth it for a long K only, or when M is
-        // small and the alternative leaves most of the chip idle while the weights stream in
-        const bool pays = ks >= 2 && (M <= 256 || nk / ks >= 48);
-        if (pays && tiles256 * ks >= 128) {
-            // all splits of a one-round launch would end together and store their partial tiles in one
-            // burst with the matrix pipes idle: K is cut unevenly (lengths mean -+ 10 K tiles) so that the
-            // early splits store theirs under the others' products (down projection at M = 1536, 3 splits
-            // of 90 / 99 / 107 K tiles)
-            int skew = 10;
-            if (skew > nk / ks / 4) skew = nk / ks / 4;
-            sp.kind = 2, sp.ks = ks, sp.skew = skew;
         }
     }
     return sp;
@@ -806,7 +758,8 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
     return launch_generic<bf16>(s, out_mode, M, N, K, A, W, C);
 }
 
-// ks * M * N <= 256 / tiles * M * N with tiles >= M * N / (256 * 256): at most 256 * 65536 floats
+// room for the slices of the few-row products (at 256 rows 8 cuts of a 4608-wide product take 38 MB); a plan that
+// does not fit the caller's buffer is cut less
 size_t gemm_parts_max_bytes() { return (size_t)256 * 65536 * 4 + 4096; }
 
 hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void* A, const void* W, float* parts,
@@ -815,7 +768,8 @@ hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void*
     if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
     if ((size_t)M * N * 4 > parts_bytes) return hipErrorInvalidValue;
     if (dtype == BF16 && pipe_ok(N, K, A, W)) {
-        const SplitPlan sp = plan_split(M, N, K);
+        const size_t room = parts_bytes / ((size_t)M * N * 4);
+        const SplitPlan sp = plan_split(M, N, K, room > 12 ? 12 : (int)room);
         if (sp.kind != 0 && (size_t)sp.ks * M * N * 4 <= parts_bytes) {
             *n_parts = sp.ks;
             if (sp.kind == 1) return launch_pipe<2, 2, 4, 2, 3, 4>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
