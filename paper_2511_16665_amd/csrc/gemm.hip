@@ -717,10 +717,16 @@ static SplitPlan plan_split(int M, int N, int K, int max_ks = 12) {
         else clk = (double)((wgs + 255) / 256) * (steps * step_clk + epilogue_clk);
         return 1.6 + clk / 1800.0 + (ks - 1) * (double)M * N * 4.0 / 4.0e6;
     };
-    // (not cut at all, the product takes the tiled launcher's own pick of a tile shape: the best of the three here)
+    // (not cut at all, the product takes the tiled launcher's own pick of a tile shape: the best of the three here
+    // and of the 192x128 tiles that launcher has besides, 1259 clocks per step and 4000 of epilogue)
     double best = cost_us(1, 1);
     if (cost_us(3, 1) < best) best = cost_us(3, 1);
     if (N % 256 == 0 && cost_us(2, 1) < best) best = cost_us(2, 1);
+    {
+        const int t192 = ((M + 191) / 192) * (N / 128);
+        const double c192 = 1.6 + (double)((t192 + 255) / 256) * (nk * 1259.0 + 4000.0) / 1800.0;
+        if (c192 < best) best = c192;
+    }
     if (max_ks > 12) max_ks = 12;
     for (int kind = 1; kind <= 3; ++kind) {
         if (kind == 2 && N % 256 != 0) continue;
