@@ -263,9 +263,11 @@ int layer_forward(tlt_ctx* ctx, hipStream_t s, const tlt_layer_weights& w, const
     float* parts = (float*)(ws + p.parts);
     int n_parts = 1;
     if ((rc = norm_x(ctx, s, M, w.attn_norm, ws + p.xn))) return rc;
-    if (dt == TLT_BF16 && M <= 256 && qkv_dim % 128 == 0) {
-        // one row of tiles: the projection has too few tiles for the chip unless it splits K, which leaves
-        // fp32 partial products; the rotary kernel sums them and leaves q in the model dtype.
+    if (dt == TLT_BF16 && qkv_dim % 128 == 0 && (size_t)M * qkv_dim * 4 * 2 <= p.parts_bytes &&
+        (M <= 256 || gemm_parts_pays(dt, M, qkv_dim, h))) {
+        // too few tiles for the chip unless the projection is cut along K, which leaves fp32 partial products;
+        // the rotary kernel sums them and leaves q in the model dtype (always up to 256 rows, one row of tiles;
+        // above where the cost model of the cuts expects it to pay: a few hundred rows).
         if ((rc = run_gemm_parts(ctx, s, M, qkv_dim, h, ws + p.xn, w.wqkv, &n_parts))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * qkv_dim * (4 * n_parts + e),
                 rope_kv_write(s, dt, rows, kv, ws + p.qkv, c.n_q_heads, c.rope_theta, w.bqkv, parts, n_parts));

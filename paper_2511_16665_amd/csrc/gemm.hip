@@ -699,7 +699,7 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
 struct SplitPlan {
     int kind = 0, ks = 1, skew = 0;
 };
-static SplitPlan plan_split(int M, int N, int K, int max_ks = 12) {
+static SplitPlan plan_split(int M, int N, int K, int max_ks = 12, double uncut_credit_us = 0.0) {
     SplitPlan sp;
     if (N % 128 != 0 || M < 1) return sp;
     const int nk = K / kBK;
@@ -727,6 +727,7 @@ static SplitPlan plan_split(int M, int N, int K, int max_ks = 12) {
         const double c192 = 1.6 + (double)((t192 + 255) / 256) * (nk * 1259.0 + 4000.0) / 1800.0;
         if (c192 < best) best = c192;
     }
+    best -= uncut_credit_us;   // (what the uncut product saves its caller besides, e.g. an output in the model dtype)
     if (max_ks > 12) max_ks = 12;
     for (int kind = 1; kind <= 3; ++kind) {
         if (kind == 2 && N % 256 != 0) continue;
@@ -766,6 +767,13 @@ hipError_t gemm(hipStream_t s, int dtype, int out_mode, int M, int N, int K, con
 
 // room for the slices of the few-row products (at 256 rows 8 cuts of a 4608-wide product take 38 MB); a plan that
 // does not fit the caller's buffer is cut less
+// Whether the product as K-cut fp32 slices (gemm_parts) is expected to beat the same product stored once in the
+// model dtype, counting the bytes the slices cost their reader and the writer over a bf16 result.
+bool gemm_parts_pays(int dtype, int M, int N, int K) {
+    if (dtype != BF16 || M < 1 || N % 128 != 0 || K % kBK != 0) return false;
+    return plan_split(M, N, K, 12, (double)M * N * 4.0 / 4.0e6).kind != 0;
+}
+
 size_t gemm_parts_max_bytes() { return (size_t)256 * 65536 * 4 + 4096; }
 
 hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void* A, const void* W, float* parts,

@@ -53,6 +53,7 @@ hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void*
                       size_t parts_bytes, int* n_parts);
 // upper bound of n * M * N * 4 over every shape (see gemm.hip)
 size_t gemm_parts_max_bytes();
+bool gemm_parts_pays(int dtype, int M, int N, int K);   // slices expected to beat one result in the model dtype
 // fused gate/up projection of the SwiGLU MLP (bf16 MFMA path only): act = silu(A Wg^T) * (A Wu^T)
 bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const void* Wg, const void* Wu);
 hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act);
