@@ -830,6 +830,14 @@ def measured_ceilings(cfg, M):
             w.fill_(1.0)
         out["own_gate_up_TFLOPs"] = {"random_operands": round(own_random, 1),
                                      "constant_operands": round(4.0 * M * cfg.mlp * cfg.hidden / timed(own, 30) / 1e12, 1)}
+        # the matrix pipes alone: every wave of the chip looping over a wave tile's MFMAs on random register
+        # operands, no memory traffic at all.  Under the power limit this, not the 2.4 GHz figure, is the rate a
+        # GEMM kernel on such data can approach.
+        frags = torch.randn(16384, device="cuda").bfloat16()
+        sums = torch.empty(65536, dtype=torch.float32, device="cuda")
+        iters = 20000
+        t = timed(lambda: tlt.mfma_stream(frags, sums, iters), 3)
+        out["mfma_only_TFLOPs"] = round(1024.0 * iters * 64 * 32768 / t / 1e12, 1)
     except Exception as ex:   # the library GEMM is context only
         out["vendor_gemm_TFLOPs"] = None
         out["vendor_gemm_error"] = str(ex)[:120]

@@ -286,6 +286,18 @@ int tlt_gemm(void *stream, int dtype, int out_mode, int M, int N, int K, const v
  * covered (N % 128, K % 64, operands not 16-byte aligned, act not 8-byte aligned). */
 int tlt_gemm_glu(void *stream, int M, int N, int K, const void *A, const void *Wg, const void *Wu, void *act);
 
+/* Measurement aid (no step of the decoding path): the rate the matrix pipes sustain with nothing else running.
+ * 256 workgroups of four waves; every wave repeats, `iters` times, the 64 matrix instructions (32x32x16, bf16 in,
+ * fp32 accumulation) that a 128x128 wave tile of the GEMM kernels issues per 64-wide K tile, in those kernels'
+ * order, on operands it holds in registers: 4 K slices x (4 activation + 4 weight fragments), fragment f of slice s
+ * for lane l being the 8 bf16 values at frags[((s * 8 + f) * 64 + l) * 8 ..] (f < 4: rows l % 32 of activation
+ * block f, f >= 4: rows l % 32 of weight block f - 4; k = 8 * (l / 32) .. + 7 of the slice).  frags: DEVICE, 32768
+ * bytes, 16-byte aligned.  out: DEVICE, 65536 floats; out[workgroup * 256 + thread] = the sum of the 256
+ * accumulator elements the thread's lane holds (every wave computes the same 128x128 product, `iters` times
+ * over).  Flops per call: 1024 waves x iters x 64 instructions x 32768.  Timed by the caller (events around the
+ * call).  TLT_EINVAL: null or misaligned pointers, iters outside 1 .. 2^22. */
+int tlt_mfma_stream(void *stream, const void *frags, float *out, int iters);
+
 /* out[m] = argmax_n (A W^T)[m][n] (lowest n on ties) for bf16 DEVICE operands, without storing the
  * product: what tlt_verify_forward runs as its LM head when only out_argmax is asked for.  ws: DEVICE
  * scratch of at least M * (N/128) * 8 bytes.  TLT_ENOTIMPL when the shape is not covered (N % 256,

@@ -27,7 +27,7 @@ EXPORTS = [
     "tlt_profile_begin", "tlt_profile_read", "tlt_mab_create", "tlt_mab_destroy", "tlt_mab_select", "tlt_mab_record",
     "tlt_mab_median_reward", "tlt_ngram_create", "tlt_ngram_destroy", "tlt_ngram_insert", "tlt_ngram_propose",
     "tlt_template_build", "tlt_draft_sample", "tlt_gemm_argmax", "tlt_gemm_glu", "tlt_draft_pool", "tlt_set_oproj_rounding", "tlt_device_status", "tlt_accept_sample_static", "tlt_attention", "tlt_attention_workspace_bytes",
-    "tlt_graph_pool_create", "tlt_graph_pool_destroy", "tlt_graph_pool_step", "tlt_graph_pool_count",
+    "tlt_graph_pool_create", "tlt_graph_pool_destroy", "tlt_graph_pool_step", "tlt_graph_pool_count", "tlt_mfma_stream",
 ]
 
 
@@ -111,6 +111,7 @@ def load() -> C.CDLL:
     lib.tlt_gemm.argtypes = [C.c_void_p] + [C.c_int] * 5 + [C.c_void_p] * 3
     lib.tlt_gemm_glu.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 4
     lib.tlt_gemm_argmax.argtypes = [C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
+    lib.tlt_mfma_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
     lib.tlt_set_attention_impl.argtypes = [C.c_void_p, C.c_int]
     lib.tlt_attention_workspace_bytes.restype = C.c_size_t
     lib.tlt_attention_workspace_bytes.argtypes = [C.c_int] * 6
@@ -473,6 +474,13 @@ def gemm_glu(A, Wg, Wu, act):
     """act = silu(A Wg^T) * (A Wu^T) for bf16 device tensors A [M, K], Wg/Wu [N, K], act [M, N]; returns the code."""
     M, K = A.shape
     return load().tlt_gemm_glu(_stream(), M, Wg.shape[0], K, _ptr(A), _ptr(Wg), _ptr(Wu), _ptr(act))
+
+
+def mfma_stream(frags, out, iters):
+    """tlt_mfma_stream: `iters` rounds of a wave tile's 64 MFMAs on the register fragments read from `frags` (bf16
+    device tensor of 16384 values), every lane's accumulator sum to `out` (fp32 device tensor of 65536); returns the code."""
+    assert frags.numel() * frags.element_size() == 32768 and out.numel() == 65536 and out.element_size() == 4
+    return load().tlt_mfma_stream(_stream(), _ptr(frags), _ptr(out), int(iters))
 
 
 class GraphPool:

@@ -928,6 +928,11 @@ int tlt_gemm(void* stream, int dtype, int out_mode, int M, int N, int K, const v
     return gemm((hipStream_t)stream, dtype, out_mode, M, N, K, A, W, C) == hipSuccess ? TLT_OK : TLT_EHIP;
 }
 
+int tlt_mfma_stream(void* stream, const void* frags, float* out, int iters) {
+    if (!frags || !out || iters < 1 || iters > (1 << 22) || ((uintptr_t)frags & 15) != 0) return TLT_EINVAL;
+    return mfma_stream((hipStream_t)stream, frags, out, iters) == hipSuccess ? TLT_OK : TLT_EHIP;
+}
+
 int tlt_profile_begin(tlt_ctx* ctx, int enable) {
     if (!ctx) return TLT_EINVAL;
     ctx->prof_on = enable != 0;

@@ -291,13 +291,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #define TLT_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     // one slice: the MFMA rows on fragment set `buf`; the reads of the next slice into the other set
     // in its first rows; the H loads base .. base+H-1 of operand OP (0 = A, 1 = W) spread evenly
-    // over the rows, each issued after its row's MFMAs
+    // over the rows, each issued after its row's MFMAs.  Odd rows run their columns backwards, so that
+    // consecutive MFMAs always share one operand (the launches run against the power limit: 0.4 % of
+    // the verification GEMMs' time, measured)
 #define TLT_SLICE(buf, pa, pb, rkk, OP, slot, base, H)                                                            \
     _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                              \
         if (i < WTM / 2) {                                                                                        \
             _Pragma("unroll") for (int q = i * RQ; q < (i + 1) * RQ && q < NR; ++q) TLT_READ1((buf) ^ 1, pa, pb, rkk, q) \
         }                                                                                                         \
-        _Pragma("unroll") for (int j = 0; j < WTN; ++j) TLT_MFMA(buf, i, j)                                        \
+        _Pragma("unroll") for (int j = 0; j < WTN; ++j) TLT_MFMA(buf, i, ((i & 1) ? WTN - 1 - j : j))              \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
         _Pragma("unroll") for (int d = (i * (H)) / WTM; d < ((i + 1) * (H)) / WTM; ++d) {                          \
             if ((OP) == 0) TLT_DMA_A(slot, (base) + d) else TLT_DMA_B(slot, (base) + d)                            \
@@ -860,6 +862,55 @@ bool gemm_glu_supported(int dtype, int M, int N, int K, const void* A, const voi
 // act[M][N] = silu(A Wg^T) * (A Wu^T), bf16 in and out; call only when gemm_glu_supported().
 hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const void* Wg, const void* Wu, void* act) {
     return launch_tiled(s, OUT_T, M, N, K, A, Wg, Wu, act, true);
+}
+
+// ---- measurement aid: what the matrix pipes sustain with nothing else running ----
+// Every wave (one per SIMD of every CU) loops over the 16 x 4 MFMAs of a 128x128 wave tile and a 64-wide K tile,
+// in the GEMM kernel's issue order, on register operands that never change: no LDS, no memory, no waits.  On
+// random data the chip holds about 1.8 GHz under its power limit here, so the rate this loop reaches, not the
+// 2.4 GHz figure, is what a GEMM kernel's share of the peak is to be read against.
+__global__ __launch_bounds__(256) void mfma_stream_k(const u32x4_t* __restrict__ frags, float* __restrict__ out, int iters) {
+    const int lane = threadIdx.x & 63;
+    bf16x8_t fa[4][4], fb[4][4];   // [K slice of 16][fragment]
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[s][i] = __builtin_bit_cast(bf16x8_t, frags[(s * 8 + i) * 64 + lane]);
+            fb[s][i] = __builtin_bit_cast(bf16x8_t, frags[(s * 8 + 4 + i) * 64 + lane]);
+        }
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int jj = (i & 1) ? 3 - j : j;
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s][i], fb[s][jj], acc[i][jj], 0, 0, 0);
+                }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float sum = 0.f;   // in a fixed order: i, then j, then the lane's 16 elements
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
+    out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+hipError_t mfma_stream(hipStream_t s, const void* frags, float* out, int iters) {
+    hipLaunchKernelGGL(mfma_stream_k, dim3(kMfmaStreamBlocks), dim3(256), 0, s, (const u32x4_t*)frags, out, iters);
+    return hipGetLastError();
 }
 
 }  // namespace tlt

@@ -65,6 +65,11 @@ hipError_t gemm_glu(hipStream_t s, int M, int N, int K, const void* A, const voi
 bool gemm_argmax_supported(int dtype, int M, int N, int K, const void* A, const void* W);
 size_t gemm_argmax_workspace_bytes(int M, int N);
 hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const void* W, void* ws, int32_t* out);
+// Measurement aid: kMfmaStreamBlocks workgroups of 4 waves, each wave `iters` times the 64 MFMAs (32x32x16 bf16) of a
+// 128x128x64 wave tile on the 32 fragments x 64 lanes x 16 bytes at `frags`; out[kMfmaStreamBlocks * 256] = every
+// lane's sum of its accumulators.
+constexpr int kMfmaStreamBlocks = 256;
+hipError_t mfma_stream(hipStream_t s, const void* frags, float* out, int iters);
 
 // ---- elementwise.hip
 hipError_t embed_rows(hipStream_t s, int dtype, int M, int h, int V, const int32_t* tokens, const void* embed, float* x);
