@@ -83,13 +83,14 @@ __device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, ui
 // followed by the same BN/2 rows of W2 (up); each wave multiplies both halves for its columns and
 // the epilogue stores silu(gate) * up, so C is [M][N] with N counting gate columns and the two
 // intermediate matrices never exist.
-// (The kernel's N is only the row stride of C: which column tiles exist is decided by total_tiles.)
+// (The kernel's N is only the row stride of C: which column tiles exist is decided by total_tiles, and ncols,
+// a multiple of 32, is where the launch's output columns end: the last column tile may reach past it.)
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
                                                         int ksplit, int wg_per_xcd, int32_t* __restrict__ C2, int kskew,
-                                                        int64_t split_stride) {
+                                                        int64_t split_stride, int ncols) {
     constexpr int NW = WGM * WGN;
     constexpr int BKS = 64;
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
@@ -169,8 +170,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     };
     // (GLU: the first half of the waves fetch the gate rows, the second half the up rows; a wave's
     // LB blocks are BN / NW consecutive tile rows, so they never straddle the two halves)
+    // The weight panel's size is its valid rows as well (the last column tile of a launch may be partial): rows
+    // past ncols fetch nothing, and the columns they would make are never stored.
     auto desc_b = [&](const TileInfo& ti) {
-        return desc(up_wave ? W2 + ((int64_t)ti.n0 - BN / 2) * K : W + (int64_t)ti.n0 * K, 0x7fffffffu);
+        int cols = ncols - ti.n0;
+        cols = cols < BNO ? cols : BNO;
+        if (up_wave) return desc(W2 + ((int64_t)ti.n0 - BN / 2) * K, (uint32_t)((BN / 2 + cols) * K * 2));
+        return desc(W + (int64_t)ti.n0 * K, (uint32_t)(cols * K * 2));
     };
 
     // DMA addressing: wave w fills 1 KB blocks w*LA .. of an A slot (8 tile rows each) and w*LB .. of
@@ -435,8 +441,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                         uint2 out;
                         out.x = hi2 ? other : w01;
                         out.y = hi2 ? w23 : other;
-                        const int col = ti.n0 + wn * (WTN / 2 * 32) + jj * 32 + (l32 & ~3);
-                        if (row < M) *(uint2*)((bf16*)C + (int64_t)row * N + col) = out;
+                        const int col0 = ti.n0 + wn * (WTN / 2 * 32) + jj * 32;   // (a 32-column block is valid or not as a whole)
+                        if (row < M && col0 < ncols) *(uint2*)((bf16*)C + (int64_t)row * N + col0 + (l32 & ~3)) = out;
                         // (keeps the compiler from fetching all accumulators first: that spills, and a reload from
                         // scratch waits for every load in flight, the next tile's first K tiles included)
                         __builtin_amdgcn_sched_barrier(0);
@@ -453,7 +459,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                     if (GLU) {
 #pragma unroll
                         for (int jj = 0; jj < WTN / 2; ++jj) {
-                            int col = ti.n0 + wn * (WTN / 2 * 32) + jj * 32 + l32;
+                            const int col0 = ti.n0 + wn * (WTN / 2 * 32) + jj * 32;
+                            if (col0 >= ncols) continue;
+                            int col = col0 + l32;
                             const float g = acc[i][jj][v], u = acc[i][jj + WTN / 2][v];
                             // (hardware reciprocal, 1 ulp: the result is rounded to bf16 anyway, and an IEEE division
                             // per element costs the tile epilogue several microseconds)
@@ -462,7 +470,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                     } else {
 #pragma unroll
                         for (int jj = 0; jj < WTN; ++jj) {
-                            int col = ti.n0 + wn * (WTN * 32) + jj * 32 + l32;
+                            const int col0 = ti.n0 + wn * (WTN * 32) + jj * 32;
+                            if (col0 >= ncols) continue;
+                            int col = col0 + l32;
                             store_out<OUT>(C, (OUT == OUT_SPLIT_F32 ? (int64_t)ti.split * split_stride : (int64_t)0) + (int64_t)row * N + col,
                                            acc[i][jj][v]);
                         }
@@ -545,7 +555,8 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
     // N counts the output columns this launch covers; ldc (default N) is the row stride of C
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     if (ldc == 0) ldc = N;
-    const int nbm = (M + BM - 1) / BM, nbn = N / (GLU ? BN / 2 : BN);
+    constexpr int BNO = GLU ? BN / 2 : BN;
+    const int nbm = (M + BM - 1) / BM, nbn = (N + BNO - 1) / BNO;   // (the last column tile may be partial; N % 32 == 0)
     const int total = nbm * nbn * ksplit;
     const int per_xcd = (total + 7) / 8;
     const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
@@ -566,7 +577,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
         }                                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, s, M, ldc, K, (const uint16_t*)A, (const uint16_t*)W,              \
                            (const uint16_t*)W2, C, nbm, total, per_xcd, ksplit, wg_per_xcd, (int32_t*)nullptr, kskew,              \
-                           (int64_t)M * ldc);                                                                        \
+                           (int64_t)M * ldc, N);                                                                     \
     }
     if (GLU || out_mode == OUT_T) LAUNCH(OUT_T)
     else if (out_mode == OUT_F32) LAUNCH(OUT_F32)
@@ -645,6 +656,14 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
             void* c = (char*)C + (size_t)main_tiles * 256 * c_elt;
             return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
         }
+        // gate/up with well under a round of big tiles: 256 rows x 96 output columns per workgroup (four waves of
+        // 64 rows x 3 + 3 column blocks, the last tile partial) puts the weights on 4/3 as many CUs.  A CU pulls cold
+        // weights at ~35 GB/s at most, however many loads it keeps in flight, and the activation rows that every
+        // workgroup re-reads from L2 go through the same path, so the gain is less than the 4/3: best of four
+        // interleaved runs on cold weights, M = 144 .. 256: 7B shape (148 -> 198 tiles) 84-86 -> 80-82 us, N = 13824,
+        // K = 5120 (108 -> 144) 111 -> 102-104; with 192 -> 256 tiles (N = 24576) 102-105 -> 102-110, so not there
+        if (glu && tiles256 <= 160 && (N + 95) / 96 <= 256)
+            return launch_pipe<4, 1, 2, 6, 3, 2, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
         return big(N);
     }
     // up to 128 rows: half of a 256-row tile would be padding, and the LDS it frees holds a third weight slot
@@ -847,7 +866,7 @@ hipError_t gemm_argmax(hipStream_t s, int M, int N, int K, const void* A, const 
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(wg_per_xcd * 8), dim3(256), lds, s, M, P, K, (const uint16_t*)A, (const uint16_t*)W,
-                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi, 0, (int64_t)0);
+                       (const uint16_t*)nullptr, (void*)pv, nbm, total, per_xcd, 1, wg_per_xcd, pi, 0, (int64_t)0, nbn * 256);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(argmax_blocks_k, dim3((M + 3) / 4), dim3(256), 0, s, M, P, pv, pi, out);
