@@ -105,6 +105,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     constexpr int kInFlightA = (SA - 2) * (LA + LB), kInFlightB = (SB - 1) * LA + (SB - 2) * LB;
     constexpr int kInFlight = kInFlightA < kInFlightB ? kInFlightA : kInFlightB;
     constexpr int BNO = GLU ? BN / 2 : BN;            // output columns per workgroup
+    // widths that do not divide the 128 columns every launch is a multiple of: the last column tile may be partial
+    constexpr bool kPartialN = BNO % 64 != 0;
     static_assert(!GLU || (NW % 2 == 0 && WTN % 2 == 0), "gate and up halves split over waves and over a wave's column tiles");
     extern __shared__ __align__(16) uint16_t lds[];   // SA A slots, then SB W slots
 
@@ -170,13 +172,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     };
     // (GLU: the first half of the waves fetch the gate rows, the second half the up rows; a wave's
     // LB blocks are BN / NW consecutive tile rows, so they never straddle the two halves)
-    // The weight panel's size is its valid rows as well (the last column tile of a launch may be partial): rows
-    // past ncols fetch nothing, and the columns they would make are never stored.
+    // Where the last column tile of a launch may be partial (kPartialN), the weight panel's size is its valid rows
+    // as well: rows past ncols fetch nothing, and the columns they would make are never stored.
     auto desc_b = [&](const TileInfo& ti) {
+        const uint16_t* base = up_wave ? W2 + ((int64_t)ti.n0 - BN / 2) * K : W + (int64_t)ti.n0 * K;
+        if constexpr (!kPartialN) return desc(base, 0x7fffffffu);
         int cols = ncols - ti.n0;
         cols = cols < BNO ? cols : BNO;
-        if (up_wave) return desc(W2 + ((int64_t)ti.n0 - BN / 2) * K, (uint32_t)((BN / 2 + cols) * K * 2));
-        return desc(W + (int64_t)ti.n0 * K, (uint32_t)(cols * K * 2));
+        return desc(base, (uint32_t)(((up_wave ? BN / 2 : 0) + cols) * K * 2));
     };
 
     // DMA addressing: wave w fills 1 KB blocks w*LA .. of an A slot (8 tile rows each) and w*LB .. of
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
                         out.x = hi2 ? other : w01;
                         out.y = hi2 ? w23 : other;
                         const int col0 = ti.n0 + wn * (WTN / 2 * 32) + jj * 32;   // (a 32-column block is valid or not as a whole)
-                        if (row < M && col0 < ncols) *(uint2*)((bf16*)C + (int64_t)row * N + col0 + (l32 & ~3)) = out;
+                        if (row < M && (!kPartialN || col0 < ncols)) *(uint2*)((bf16*)C + (int64_t)row * N + col0 + (l32 & ~3)) = out;
                         // (keeps the compiler from fetching all accumulators first: that spills, and a reload from
                         // scratch waits for every load in flight, the next tile's first K tiles included)
                         __builtin_amdgcn_sched_barrier(0);
@@ -460,7 +463,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
                         for (int jj = 0; jj < WTN / 2; ++jj) {
                             const int col0 = ti.n0 + wn * (WTN / 2 * 32) + jj * 32;
-                            if (col0 >= ncols) continue;
+                            if (kPartialN && col0 >= ncols) continue;
                             int col = col0 + l32;
                             const float g = acc[i][jj][v], u = acc[i][jj + WTN / 2][v];
                             // (hardware reciprocal, 1 ulp: the result is rounded to bf16 anyway, and an IEEE division
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
 #pragma unroll
                         for (int jj = 0; jj < WTN; ++jj) {
                             const int col0 = ti.n0 + wn * (WTN * 32) + jj * 32;
-                            if (col0 >= ncols) continue;
+                            if (kPartialN && col0 >= ncols) continue;
                             int col = col0 + l32;
                             store_out<OUT>(C, (OUT == OUT_SPLIT_F32 ? (int64_t)ti.split * split_stride : (int64_t)0) + (int64_t)row * N + col,
                                            acc[i][jj][v]);
@@ -556,7 +559,9 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     if (ldc == 0) ldc = N;
     constexpr int BNO = GLU ? BN / 2 : BN;
-    const int nbm = (M + BM - 1) / BM, nbn = (N + BNO - 1) / BNO;   // (the last column tile may be partial; N % 32 == 0)
+    // (only tile widths that do not divide 64 handle a partial last column tile; N % 32 == 0 either way)
+    if ((BNO % 64 == 0 && N % BNO != 0) || N % 32 != 0) return hipErrorInvalidValue;
+    const int nbm = (M + BM - 1) / BM, nbn = (N + BNO - 1) / BNO;
     const int total = nbm * nbn * ksplit;
     const int per_xcd = (total + 7) / 8;
     const size_t lds = ((size_t)SA * BM + (size_t)SB * BN) * 64 * sizeof(uint16_t);
