@@ -1021,6 +1021,11 @@ def main():
         result["verify_latency_ms_vs_tree_size"] = verify_latency_sweep(cfg, e, [1, 8, 16, 32, 48, 64])
     if args.sweep:
         result["measured_ceilings"] = measured_ceilings(cfg, B * N)
+        # beside the fraction of the published peak: the fraction of what the matrix pipes alone sustain on
+        # random operands under this box's power limit, measured in this run
+        sustained = result["measured_ceilings"].get("mfma_only_TFLOPs")
+        if sustained and result["roofline"].get("unit") == "TFLOP/s":
+            result["roofline"]["frac_of_measured_mfma_only"] = round(result["roofline"]["achieved"] / sustained, 4)
     if args.alpha > 0 and args.mode == "greedy" and args.sweep:
         result["fixed_acceptance"] = fixed_acceptance_steps(cfg, e, K, D, N, args.alpha, steps=5)
     if not args.no_cpu_baseline and args.mode == "greedy":
