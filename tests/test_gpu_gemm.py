@@ -169,7 +169,7 @@ def test_fused_row_argmax_refuses_shapes_it_does_not_cover():
 
 @pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1536, 18944, 256), (1000, 16512, 192), (129, 128, 640),
                                    (100, 25600, 256), (200, 33024, 128), (256, 18944, 512), (200, 12928, 256),
-                                   (160, 18432, 128), (130, 24576, 64)])
+                                   (160, 18432, 128), (130, 24576, 64), (256, 18944, 3584)])
 def test_fused_gate_up_projection_matches_float64(M, N, K):
     """tlt_gemm_glu: silu(A Wg^T) * (A Wu^T) in one kernel (256-row weight tiles for the whole rounds of
     the chip, 128-row tiles for the rest, ragged M tail; one row of 128x256 or 256x256 tiles when M is small, or
