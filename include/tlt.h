@@ -295,7 +295,7 @@ int tlt_gemm_glu(void *stream, int M, int N, int K, const void *A, const void *W
  * bytes, 16-byte aligned.  out: DEVICE, 65536 floats; out[workgroup * 256 + thread] = the sum of the 256
  * accumulator elements the thread's lane holds (every wave computes the same 128x128 product, `iters` times
  * over).  Flops per call: 1024 waves x iters x 64 instructions x 32768.  Timed by the caller (events around the
- * call).  TLT_EINVAL: null or misaligned pointers, iters outside 1 .. 2^22. */
+ * call).  TLT_EINVAL: null or misaligned pointers, iters outside 1 .. 2^20 (a call then runs for about a second at most). */
 int tlt_mfma_stream(void *stream, const void *frags, float *out, int iters);
 
 /* out[m] = argmax_n (A W^T)[m][n] (lowest n on ties) for bf16 DEVICE operands, without storing the

@@ -929,7 +929,7 @@ int tlt_gemm(void* stream, int dtype, int out_mode, int M, int N, int K, const v
 }
 
 int tlt_mfma_stream(void* stream, const void* frags, float* out, int iters) {
-    if (!frags || !out || iters < 1 || iters > (1 << 22) || ((uintptr_t)frags & 15) != 0) return TLT_EINVAL;
+    if (!frags || !out || iters < 1 || iters > (1 << 20) || ((uintptr_t)frags & 15) != 0) return TLT_EINVAL;
     return mfma_stream((hipStream_t)stream, frags, out, iters) == hipSuccess ? TLT_OK : TLT_EHIP;
 }
 
