@@ -130,11 +130,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     const int nk_all = K / BKS;
     const bool up_wave = GLU && wave >= NW / 2;
 
-    // tile j of this workgroup: M fastest, then the K split, then N
+    // tile j of this workgroup: M fastest, then N, then the K split.  An XCD's run of tiles then lies in one K split
+    // (or two): its workgroups walk the same K range together and share the activation K tiles in its L2, where
+    // with the split inside N every XCD would fetch the activation rows of every K range.
     struct TileInfo { int m0, n0, kt0, nt, split; };
+    const int nbn_all = total_tiles / (nbm * ksplit);
     auto tile_info = [&](int j) {
         const int logical = first + j * wg_per_xcd;
-        const int tile_m = logical % nbm, split = (logical / nbm) % ksplit, tile_n = logical / (nbm * ksplit);
+        const int tile_m = logical % nbm, tile_n = (logical / nbm) % nbn_all, split = logical / (nbm * nbn_all);
         TileInfo ti;
         // (integer division runs on the vector ALU: pin the uniform results back into scalar registers)
         ti.m0 = __builtin_amdgcn_readfirstlane(tile_m * BM);
