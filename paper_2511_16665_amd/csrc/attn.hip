@@ -283,6 +283,18 @@ __device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, ui
 // workgroup may run different instances (a wave whose share of the row tiles is smaller skips the
 // matrix and softmax work it has no rows for; NT = 0: it only fetches its part of the K/V tiles and
 // keeps the barriers): every instance passes the same barriers in the same order.
+// Workgroup id -> (work item, kv head, row group).  Ids are dealt round-robin over the 8 XCDs, and the row groups of
+// one (item, kv head) read the same keys and values: they get ids 8 apart, so that they run on one XCD at the same
+// time and the second finds the rows in that XCD's L2.  (With one row group this is item = id / n_kv, head = id % n_kv.)
+__device__ __forceinline__ void attn_decode(int id, int heads, int n_kv, int& rank, int& kh, int& rg) {
+    const int per = 8 * (heads / n_kv);
+    const int g = id / per, within = id - g * per;
+    rg = within >> 3;
+    const int q = g * 8 + (within & 7);
+    rank = q / n_kv;
+    kh = q - rank * n_kv;
+}
+
 template <int NT>
 __device__ __forceinline__ void attn_body(const Rows& rows, const KVLayer& kv, const uint16_t* __restrict__ qkv,
                                           float* __restrict__ part_o, float* __restrict__ part_ml,
@@ -290,10 +302,10 @@ __device__ __forceinline__ void attn_body(const Rows& rows, const KVLayer& kv, c
                                           int tiles_per_group, int r_pad, float scale_log2, float lazy_raw) {
     constexpr int TPW = NT > 0 ? NT : 1;   // array extents (nothing is computed in them when NT = 0)
     extern __shared__ __align__(16) uint16_t lds[];
-    const int rank = blockIdx.x / heads, hy = blockIdx.x - rank * heads;
+    int rank, kh, rg;
+    attn_decode(blockIdx.x, heads, kv.n_kv, rank, kh, rg);
     if (rank >= work->n_items) return;  // uniform
     const AttnItem item = ((const AttnItem*)((const int*)(work + 1) + 2 * rows.B))[rank];
-    const int kh = hy % kv.n_kv, rg = hy / kv.n_kv;
     const int b = item.b;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g4 = lane >> 4;
@@ -674,7 +686,8 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
                                                    float lazy_raw) {
     // row tiles of this wave that exist (tile indices rise with t, so they are the first n_on)
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    const int rg = (int)(blockIdx.x % heads) / kv.n_kv;
+    int rank_, kh_, rg;
+    attn_decode(blockIdx.x, heads, kv.n_kv, rank_, kh_, rg);
     int n_on = 0;
 #pragma unroll
     for (int t = 0; t < TPW; ++t)
@@ -760,7 +773,9 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     if (!reuse_plan)
         hipLaunchKernelGGL(attn_plan_k, dim3(1), dim3(256), 0, s, kv.seq_len, rows.B, rows.n_region, p.heads, p.max_items, work,
                            kv.seq_len_bound, status);
-    hipLaunchKernelGGL(kern, dim3(p.max_items * p.heads), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
+    // (ids come in groups of 8 (item, kv head) pairs x row groups: see attn_decode)
+    const int id_groups = (p.max_items * kv.n_kv + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3(id_groups * 8 * p.row_groups), dim3(512), lds, s, rows, kv, (const uint16_t*)qkv, part_o,
                        part_ml, work, p.heads, n_q_heads, p.row_tiles, tiles_per_group, p.r_pad, scale_log2,
                        8.0f / scale_log2);
     hipError_t e = hipGetLastError();
