@@ -78,6 +78,14 @@ __device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, ui
                  : "v"(voff_bytes), "s"(rsrc), "s"(soff_bytes), "s"(lds_bytes)
                  : "memory", "m0");
 }
+// the same load marked non-temporal: for weight rows that no other workgroup reads, see NTW below
+__device__ __forceinline__ void dma_buf_16_nt(u32x4_t rsrc, uint32_t voff_bytes, uint32_t soff_bytes,
+                                              uint32_t lds_bytes) {
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen nt lds"
+                 :
+                 : "v"(voff_bytes), "s"(rsrc), "s"(soff_bytes), "s"(lds_bytes)
+                 : "memory", "m0");
+}
 
 // GLU = true: the fused gate/up projection.  A workgroup's BN weight rows are BN/2 rows of W (gate)
 // followed by the same BN/2 rows of W2 (up); each wave multiplies both halves for its columns and
@@ -85,7 +93,14 @@ __device__ __forceinline__ void dma_buf_16(u32x4_t rsrc, uint32_t voff_bytes, ui
 // intermediate matrices never exist.
 // (The kernel's N is only the row stride of C: which column tiles exist is decided by total_tiles, and ncols,
 // a multiple of 32, is where the launch's output columns end: the last column tile may reach past it.)
-template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false>
+// NTW = true: the weight rows are fetched with the non-temporal hint.  For a single row of tiles that is not cut
+// along K every weight row is read by one workgroup, once, and the hint keeps the stream from displacing what the
+// caches hold of the activations and of the neighbouring kernels' data: the LM head at 40-256 rows 5-8 % faster
+// (233 -> 221 us, 207 -> 193), gate/up at 256 rows 2-3 %, the small kernels around them 1-4 %.  With several row
+// tiles per weight tile, or with K cuts, the same hint costs 1-5 % (o projection at 1536 rows 46.7 -> 48.1 us, the
+// down projection's 8 cuts at 256 rows 45.2 -> 47.6): those launches do not take it.  (Kernel traces of both
+// builds on one box.)
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false, bool NTW = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
                                                         void* __restrict__ C, int nbm, int total_tiles, int per_xcd,
@@ -252,7 +267,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N,
     set_next(0, ti0);
 
 #define TLT_DMA_A(slot, d) dma_buf_16(rsA, offA[d], kA2, lds_waveA + (uint32_t)((slot) * ASZ * 2 + (d) * 1024));
-#define TLT_DMA_B(slot, d) dma_buf_16(rsB, offB[d], kB2, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));
+#define TLT_DMA_B(slot, d)                                                                                        \
+    {                                                                                                             \
+        if constexpr (NTW) dma_buf_16_nt(rsB, offB[d], kB2, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024)); \
+        else dma_buf_16(rsB, offB[d], kB2, lds_waveB + (uint32_t)((slot) * BSZ * 2 + (d) * 1024));                \
+    }
 
     f32x16_t acc[WTM][WTN];
 #pragma unroll
@@ -555,7 +574,7 @@ __global__ __launch_bounds__(256) void gemm_generic_k(int M, int N, int K, const
     }
 }
 
-template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false>
+template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, bool GLU = false, bool NTW = false>
 static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, const void* A, const void* W, void* C,
                               const void* W2 = nullptr, int ksplit = 1, int ldc = 0, int kskew = 0) {
     // N counts the output columns this launch covers; ldc (default N) is the row stride of C
@@ -576,7 +595,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
     dim3 grid(wg_per_xcd * 8), block(64 * WGM * WGN);
 #define LAUNCH(OUT)                                                                                                   \
     {                                                                                                                 \
-        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU>;                                          \
+        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU, NTW && (OUT == OUT_T || OUT == OUT_F32)>; \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -623,9 +642,18 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
         const void* w = (const uint16_t*)W + (int64_t)col0 * K;
         const void* w2 = W2 ? (const uint16_t*)W2 + (int64_t)col0 * K : nullptr;
         void* c = (char*)C + (size_t)col0 * c_elt;
+        // (a single row of tiles: every weight row is read once, by one workgroup: non-temporal loads, see NTW)
+        if (glu && nbm128 == 1) {
+            if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
+            return launch_pipe<2, 2, 2, 2, 3, 3, true, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
+        }
         if (glu) {
             if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
             return launch_pipe<2, 2, 2, 2, 3, 3, true>(s, OUT_T, M, n_cols, K, A, w, c, w2, 1, N);
+        }
+        if (nbm128 == 1) {
+            if (tiles > 256) return launch_pipe<2, 2, 2, 2, 3, 2, false, true>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
+            return launch_pipe<2, 2, 2, 2, 3, 3, false, true>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
         }
         // more 128-row tiles than CUs (some CUs would hold two workgroups and take twice as long as the others), but
         // 192- or 256-row tiles fit the chip once: one workgroup per CU with the CU to itself, whichever of the two
@@ -643,6 +671,10 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
         return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, n_cols, K, A, w, c, nullptr, 1, N);
     };
     auto big = [&](int n_cols) -> hipError_t {
+        if (nbm256 == 1) {
+            if (glu) return launch_pipe<2, 2, 4, 4, 3, 2, true, true>(s, OUT_T, M, n_cols, K, A, W, C, W2, 1, N);
+            return launch_pipe<2, 2, 4, 4, 3, 2, false, true>(s, out_mode, M, n_cols, K, A, W, C, nullptr, 1, N);
+        }
         if (glu) return launch_pipe<2, 2, 4, 4, 3, 2, true>(s, OUT_T, M, n_cols, K, A, W, C, W2, 1, N);
         return launch_pipe<2, 2, 4, 4, 3, 2>(s, out_mode, M, n_cols, K, A, W, C, nullptr, 1, N);
     };
@@ -662,7 +694,7 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
             if (e != hipSuccess) return e;
             const void* w = (const uint16_t*)W + (int64_t)main_tiles * 256 * K;
             void* c = (char*)C + (size_t)main_tiles * 256 * c_elt;
-            return launch_pipe<2, 2, 4, 2, 3, 4>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
+            return launch_pipe<2, 2, 4, 2, 3, 4, false, true>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
         }
         // gate/up with well under a round of big tiles: 256 rows x 96 output columns per workgroup (four waves of
         // 64 rows x 3 + 3 column blocks, the last tile partial) puts the weights on 4/3 as many CUs.  A CU pulls cold
@@ -671,23 +703,23 @@ static hipError_t launch_tiled(hipStream_t s, int out_mode, int M, int N, int K,
         // interleaved runs on cold weights, M = 144 .. 256: 7B shape (148 -> 198 tiles) 84-86 -> 80-82 us, N = 13824,
         // K = 5120 (108 -> 144) 111 -> 102-104; with 192 -> 256 tiles (N = 24576) 102-105 -> 102-110, so not there
         if (glu && tiles256 <= 160 && (N + 95) / 96 <= 256)
-            return launch_pipe<4, 1, 2, 6, 3, 2, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
+            return launch_pipe<4, 1, 2, 6, 3, 2, true, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
         return big(N);
     }
     // up to 128 rows: half of a 256-row tile would be padding, and the LDS it frees holds a third weight slot
     // (gate/up at M = 128: 85 -> 70 us, LM head: 261 -> 251; at the 32B shape 406 -> 343)
     if (M > 64 && M <= 128 && tiles256 >= 100 && N % bno256 == 0) {
-        if (glu) return launch_pipe<2, 2, 2, 4, 3, 3, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
+        if (glu) return launch_pipe<2, 2, 2, 4, 3, 3, true, true>(s, OUT_T, M, N, K, A, W, C, W2, 1, N);
         // (more than a round: whole rounds, the rest in 128x128 tiles: LM head 227-250 -> 219-241 us, 32B shape 313-343 -> 297-325)
         const int main_tiles = tiles256 / 256 * 256;
         if (main_tiles > 0 && main_tiles < tiles256) {
-            hipError_t e = launch_pipe<2, 2, 2, 4, 3, 3>(s, out_mode, M, main_tiles * 256, K, A, W, C, nullptr, 1, N);
+            hipError_t e = launch_pipe<2, 2, 2, 4, 3, 3, false, true>(s, out_mode, M, main_tiles * 256, K, A, W, C, nullptr, 1, N);
             if (e != hipSuccess) return e;
             const void* w = (const uint16_t*)W + (int64_t)main_tiles * 256 * K;
             void* c = (char*)C + (size_t)main_tiles * 256 * c_elt;
-            return launch_pipe<2, 2, 2, 2, 3, 3>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
+            return launch_pipe<2, 2, 2, 2, 3, 3, false, true>(s, out_mode, M, N - main_tiles * 256, K, A, w, c, nullptr, 1, N);
         }
-        return launch_pipe<2, 2, 2, 4, 3, 3>(s, out_mode, M, N, K, A, W, C, nullptr, 1, N);
+        return launch_pipe<2, 2, 2, 4, 3, 3, false, true>(s, out_mode, M, N, K, A, W, C, nullptr, 1, N);
     }
     if (M <= 64 || tiles256 < 256) return small(N, 0);
     const int full_rounds = tiles256 / 256;
