@@ -98,8 +98,9 @@ __device__ __forceinline__ void dma_buf_16_nt(u32x4_t rsrc, uint32_t voff_bytes,
 // caches hold of the activations and of the neighbouring kernels' data: the LM head at 40-256 rows 5-8 % faster
 // (233 -> 221 us, 207 -> 193), gate/up at 256 rows 2-3 %, the small kernels around them 1-4 %.  With several row
 // tiles per weight tile, or with K cuts, the same hint costs 1-5 % (o projection at 1536 rows 46.7 -> 48.1 us, the
-// down projection's 8 cuts at 256 rows 45.2 -> 47.6): those launches do not take it.  (Kernel traces of both
-// builds on one box.)
+// down projection's 8 cuts at 256 rows 45.2 -> 47.6): those launches do not take it, except the K cuts of 128x128
+// tiles at up to 128 rows (one row of tiles: 14.8 -> 14.1 us at 40 rows, plain decoding at batch 32 5.60 -> 5.56 ms).
+// (Kernel traces of both builds on one box.)
 template <int WGM, int WGN, int WTM, int WTN, int SA, int SB, int OUT, bool GLU = false, bool NTW = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_k(int M, int N, int K, const uint16_t* __restrict__ A,
                                                         const uint16_t* __restrict__ W, const uint16_t* __restrict__ W2,
@@ -595,7 +596,7 @@ static hipError_t launch_pipe(hipStream_t s, int out_mode, int M, int N, int K, 
     dim3 grid(wg_per_xcd * 8), block(64 * WGM * WGN);
 #define LAUNCH(OUT)                                                                                                   \
     {                                                                                                                 \
-        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU, NTW && (OUT == OUT_T || OUT == OUT_F32)>; \
+        auto kern = gemm_bf16_pipe_k<WGM, WGN, WTM, WTN, SA, SB, OUT, GLU, NTW && (OUT == OUT_T || OUT == OUT_F32 || OUT == OUT_SPLIT_F32)>; \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -848,6 +849,8 @@ hipError_t gemm_parts(hipStream_t s, int dtype, int M, int N, int K, const void*
         if (sp.kind != 0 && (size_t)sp.ks * M * N * 4 <= parts_bytes) {
             *n_parts = sp.ks;
             if (sp.kind == 1) return launch_pipe<2, 2, 4, 2, 3, 4>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
+            if (sp.kind == 3 && M <= 128)
+                return launch_pipe<2, 2, 2, 2, 3, 3, false, true>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
             if (sp.kind == 3) return launch_pipe<2, 2, 2, 2, 3, 3>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
             return launch_pipe<2, 2, 4, 4, 3, 2>(s, OUT_SPLIT_F32, M, N, K, A, W, parts, nullptr, sp.ks, 0, sp.skew);
         }
