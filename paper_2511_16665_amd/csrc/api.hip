@@ -715,7 +715,8 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
             rmsnorm(s, dt, B, h, feat, ctx->target.final_norm, c.rms_eps, ws + p.xn, row_map));
     if ((rc = run_gemm(ctx, s, OUT_F32, B, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
     TLT_RUN(ctx, s, CLS_OTHER, 0, (double)B * V * 12,
-            softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q));
+            softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q,
+                         ctx->pending_parts == 0 ? ws + p.parts : nullptr, p.parts_bytes));   // (the slices' buffer is idle here)
 
     // level d: the nodes of depth d that have children, one drafter row each (provisional cache row
     // and feature row 1 + its index among such nodes)
@@ -756,7 +757,8 @@ int tlt_draft_sample(tlt_ctx* ctx, void* stream, int B, int depth, int topk, int
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * h * 8, scatter_rows(s, M, lv.R, h, x, feat, FR, 1 + slot_base));
         if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
         TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 12,
-                softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q));
+                softmax_draw(s, B, n, V, temperature, lv, logits, u_draw, out_tree->token, out_draft_q,
+                         ctx->pending_parts == 0 ? ws + p.parts : nullptr, p.parts_bytes));   // (the slices' buffer is idle here)
     }
     return TLT_OK;
 }

@@ -161,8 +161,10 @@ hipError_t tmpl_level_rows(hipStream_t s, int B, int n, TmplRows rows, const int
                            uint64_t* fr_mask);
 // per row (b, r): q[b][node] = softmax(logits[b*R + r] / temperature); then the node's children are
 // drawn from it one after the other without replacement with the uniforms u_draw[b][child].
+// scratch (may be null): device memory the call may use, 8-byte aligned; with few rows and enough of it
+// (B*R * (V/256 + 32) * 8 bytes) a row's softmax is spread over several workgroups.
 hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, TmplRows rows, const float* logits,
-                        const uint32_t* u_draw, int32_t* token, float* q);
+                        const uint32_t* u_draw, int32_t* token, float* q, void* scratch, size_t scratch_bytes);
 
 hipError_t accept_greedy(hipStream_t s, int B, int n, int V, int stride, const int32_t* token, const int32_t* parent,
                          const float* logits, const int32_t* argmax, int32_t* accept_len, int32_t* path_idx,

@@ -525,11 +525,87 @@ __device__ __forceinline__ void load4(const float* __restrict__ p, int idx, int 
     }
 }
 
+// With few rows one workgroup per row leaves most of the chip idle, and a CU pulls a 600 KB row three times at the
+// rate of its own load path (81 us per level at 40 rows).  Then the row is cut into G segments: softmax_part_k takes
+// each segment's maximum and sum of exponentials, softmax_q_k combines them (in segment order), writes its segment
+// of q and the integer weight total of each of its 256-element steps, and softmax_draw_k<.., PRE = true> starts from
+// those totals and only draws.  Given q the draw is the same exact integer search either way.
 template <bool VEC4>
+__global__ __launch_bounds__(kDrawThreads) void softmax_part_k(int V, int G, int seg, float inv_temperature,
+                                                               const float* __restrict__ logits, float* __restrict__ part) {
+    __shared__ float sf[kDrawWaves];
+    const int tid = threadIdx.x;
+    const int row = blockIdx.x / G, g = blockIdx.x - row * G;
+    const float* l = logits + (int64_t)row * V;
+    const int lo = g * seg, hi = min(V, lo + seg);   // lo % 4 == 0; hi % 4 == 0 when VEC4
+    float x[4];
+    float m = -INFINITY;
+    for (int i = lo + tid * 4; i < hi; i += kDrawThreads * 4) {
+        load4<VEC4>(l, i, hi, x, -INFINITY);
+        m = fmaxf(fmaxf(m, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
+    }
+    m = block_max_f<kDrawWaves>(m, sf);
+    float sum = 0.f;
+    for (int i = lo + tid * 4; i < hi; i += kDrawThreads * 4) {
+        load4<VEC4>(l, i, hi, x, -INFINITY);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += expf((x[e] - m) * inv_temperature);   // exp(-inf) = 0 past the end
+    }
+    sum = block_sum_f<kDrawWaves>(sum, sf);
+    if (tid == 0) {
+        part[2 * (int64_t)blockIdx.x] = m;
+        part[2 * (int64_t)blockIdx.x + 1] = sum;
+    }
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(kDrawThreads) void softmax_q_k(int n, int V, int G, int seg, int n_steps_all, float inv_temperature,
+                                                            TmplRows rows, const float* __restrict__ logits,
+                                                            const float* __restrict__ part, float* __restrict__ q_out,
+                                                            unsigned long long* __restrict__ step_tot) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x / G, g = blockIdx.x - row * G;
+    const int b = row / rows.R, r = row - b * rows.R;
+    const float* l = logits + (int64_t)row * V;
+    float* q = q_out + ((int64_t)b * n + rows.node[r]) * V;
+    const float* pr = part + 2 * (int64_t)row * G;
+    float m = -INFINITY;
+    for (int k = 0; k < G; ++k) m = fmaxf(m, pr[2 * k]);
+    float z = 0.f;
+    for (int k = 0; k < G; ++k) z += pr[2 * k + 1] * expf((pr[2 * k] - m) * inv_temperature);
+    const float inv = 1.0f / z;
+    const int lo = g * seg, hi = min(V, lo + seg);
+    float x[4];
+    for (int i0 = lo + wave * 256; i0 < hi; i0 += kDrawWaves * 256) {
+        const int i = i0 + lane * 4;
+        load4<VEC4>(l, i, V, x, -INFINITY);
+        float qv[4];
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            qv[e] = expf((x[e] - m) * inv_temperature) * inv;
+            if (i + e < V) mine += q_weight(qv[e]);
+        }
+        if (VEC4) {
+            if (i < V) *(float4*)(q + i) = make_float4(qv[0], qv[1], qv[2], qv[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i + e < V) q[i + e] = qv[e];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+        if (lane == 0) step_tot[(int64_t)row * n_steps_all + (i0 >> 8)] = mine;
+    }
+}
+
+template <bool VEC4, bool PRE = false>
 __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, float inv_temperature, TmplRows rows,
                                                                const float* __restrict__ logits,
                                                                const uint32_t* __restrict__ u_draw,
-                                                               int32_t* __restrict__ token, float* __restrict__ q_out) {
+                                                               int32_t* __restrict__ token, float* __restrict__ q_out,
+                                                               const unsigned long long* __restrict__ step_tot,
+                                                               int n_steps_all) {
     __shared__ float sf[kDrawWaves];
     __shared__ unsigned long long wsum[kDrawWaves];
     __shared__ unsigned long long step_sum[kDrawWaves][kDrawMaxSteps];   // totals of each wave's 256-element steps
@@ -542,7 +618,8 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
     float* q = q_out + ((int64_t)b * n + node) * V;
     float x[4];
 
-    float m = -INFINITY;
+    float m = -INFINITY, inv = 0.f;
+    if constexpr (!PRE) {
     for (int i = tid * 4; i < V; i += kDrawThreads * 4) {
         load4<VEC4>(l, i, V, x, -INFINITY);
         m = fmaxf(fmaxf(m, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
@@ -554,15 +631,23 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
 #pragma unroll
         for (int e = 0; e < 4; ++e) part += expf((x[e] - m) * inv_temperature);   // exp(-inf) = 0 past the end
     }
-    const float inv = 1.0f / block_sum_f<kDrawWaves>(part, sf);
+    inv = 1.0f / block_sum_f<kDrawWaves>(part, sf);
+    }
 
     // q, each wave's integer weight total over its own range, and the totals of its 256-element steps
     const int Vw = (V + kDrawWaves * 256 - 1) / (kDrawWaves * 256) * 256;
     const int w0 = wave * Vw, w1 = min(V, w0 + Vw);
     const int n_steps = Vw / 256;
-    const bool fast = n_steps <= kDrawMaxSteps;   // (else the search walks a wave's range step by step)
+    const bool fast = PRE || n_steps <= kDrawMaxSteps;   // (else the search walks a wave's range step by step; PRE: the launcher checks)
     unsigned long long acc = 0;
-    for (int i0 = w0, k = 0; i0 < w1; i0 += 256, ++k) {
+    if constexpr (PRE) {
+        // the step totals of this wave's range, as softmax_q_k left them (one per lane: n_steps <= 64)
+        const int k = lane;
+        const unsigned long long mine = (k < n_steps && w0 + k * 256 < w1) ? step_tot[(int64_t)blockIdx.x * n_steps_all + (w0 >> 8) + k] : 0ull;
+        if (k < kDrawMaxSteps) step_sum[wave][k] = mine;
+        acc = mine;
+    }
+    for (int i0 = w0, k = 0; !PRE && i0 < w1; i0 += 256, ++k) {
         const int i = i0 + lane * 4;
         load4<VEC4>(l, i, V, x, -INFINITY);
         float qv[4];
@@ -586,7 +671,7 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_draw_k(int n, int V, flo
             if (lane == 0) step_sum[wave][k] = mine;
         }
     }
-    if (fast)
+    if (fast && !PRE)
         for (int k = (w1 > w0 ? (w1 - w0 + 255) / 256 : 0) + lane; k < kDrawMaxSteps; k += 64) step_sum[wave][k] = 0;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
@@ -1245,15 +1330,43 @@ hipError_t tmpl_level_rows(hipStream_t s, int B, int n, TmplRows rows, const int
 }
 
 hipError_t softmax_draw(hipStream_t s, int B, int n, int V, float temperature, TmplRows rows, const float* logits,
-                        const uint32_t* u_draw, int32_t* token, float* q) {
+                        const uint32_t* u_draw, int32_t* token, float* q, void* scratch, size_t scratch_bytes) {
     // 16-byte accesses need every row of the logits and of q to start on a 16-byte boundary
     const bool vec4 = V % 4 == 0 && (((uintptr_t)logits | (uintptr_t)q) & 15) == 0;
+    const int M = B * rows.R;
+    // few rows: each row's softmax over several workgroups (see softmax_part_k), as many as fill most of the chip
+    const int n_steps_all = (V + 255) / 256;
+    const int Vw = (V + kDrawWaves * 256 - 1) / (kDrawWaves * 256) * 256;
+    int G = M >= 96 ? 1 : 192 / M;
+    G = G > 16 ? 16 : G;
+    const int seg = G > 1 ? ((V + G - 1) / G + 1023) / 1024 * 1024 : V;
+    if (G > 1) G = (V + seg - 1) / seg;   // (no empty segment)
+    const size_t part_bytes = ((size_t)M * G * 2 * sizeof(float) + 255) / 256 * 256;
+    const size_t need = part_bytes + (size_t)M * n_steps_all * sizeof(unsigned long long);
+    if (G > 1 && scratch && need <= scratch_bytes && Vw / 256 <= kDrawMaxSteps && ((uintptr_t)scratch & 7) == 0) {
+        float* part = (float*)scratch;
+        unsigned long long* step_tot = (unsigned long long*)((char*)scratch + part_bytes);
+        if (vec4) {
+            hipLaunchKernelGGL(softmax_part_k<true>, dim3(M * G), dim3(kDrawThreads), 0, s, V, G, seg, 1.0f / temperature, logits, part);
+            hipLaunchKernelGGL(softmax_q_k<true>, dim3(M * G), dim3(kDrawThreads), 0, s, n, V, G, seg, n_steps_all, 1.0f / temperature,
+                               rows, logits, part, q, step_tot);
+            hipLaunchKernelGGL((softmax_draw_k<true, true>), dim3(M), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                               logits, u_draw, token, q, step_tot, n_steps_all);
+        } else {
+            hipLaunchKernelGGL(softmax_part_k<false>, dim3(M * G), dim3(kDrawThreads), 0, s, V, G, seg, 1.0f / temperature, logits, part);
+            hipLaunchKernelGGL(softmax_q_k<false>, dim3(M * G), dim3(kDrawThreads), 0, s, n, V, G, seg, n_steps_all, 1.0f / temperature,
+                               rows, logits, part, q, step_tot);
+            hipLaunchKernelGGL((softmax_draw_k<false, true>), dim3(M), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                               logits, u_draw, token, q, step_tot, n_steps_all);
+        }
+        return hipGetLastError();
+    }
     if (vec4)
-        hipLaunchKernelGGL(softmax_draw_k<true>, dim3(B * rows.R), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
-                           logits, u_draw, token, q);
+        hipLaunchKernelGGL((softmax_draw_k<true, false>), dim3(M), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                           logits, u_draw, token, q, (const unsigned long long*)nullptr, 0);
     else
-        hipLaunchKernelGGL(softmax_draw_k<false>, dim3(B * rows.R), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
-                           logits, u_draw, token, q);
+        hipLaunchKernelGGL((softmax_draw_k<false, false>), dim3(M), dim3(kDrawThreads), 0, s, n, V, 1.0f / temperature, rows,
+                           logits, u_draw, token, q, (const unsigned long long*)nullptr, 0);
     return hipGetLastError();
 }
 
