@@ -706,6 +706,11 @@ __global__ __launch_bounds__(512) void attn_mfma_k(Rows rows, KVLayer kv, const 
 
 // One wave per (b, kv head, row), four rows per workgroup: merges the chunks' partial outputs
 // (running max in raw score units).
+// BATCH: the loads of four chunks are issued before any of them is used.  With few rows in all (plain decoding, small
+// batches) a wave's chunks, one load latency each, are the whole kernel (12 -> 5 us at batch 1, 16 chunks); with the
+// chip full of waves the plain loop is the faster one (14 against 16 us at the benchmark shape).  The sums run in
+// chunk order either way.
+template <bool BATCH>
 __global__ __launch_bounds__(256) void attn_combine_k(Rows rows, KVLayer kv, const float* __restrict__ part_o,
                                                      const float* __restrict__ part_ml, uint16_t* __restrict__ out,
                                                      const AttnWork* __restrict__ work, int n_q_heads, int max_items,
@@ -728,8 +733,36 @@ __global__ __launch_bounds__(256) void attn_combine_k(Rows rows, KVLayer kv, con
     const int64_t pbase = ((int64_t)first * kv.n_kv + kh) * r_pad + r;
     const int64_t pstride = (int64_t)kv.n_kv * r_pad;
     float M = kNegBig;
-    for (int c = 0; c < used; ++c) M = fmaxf(M, part_ml[(pbase + c * pstride) * 2]);
     float a0 = 0.f, a1 = 0.f, L = 0.f;
+    if constexpr (BATCH) {
+        for (int c0 = 0; c0 < used; c0 += 4) {
+            float m4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) m4[u] = c0 + u < used ? part_ml[(pbase + (c0 + u) * pstride) * 2] : kNegBig;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) M = fmaxf(M, m4[u]);
+        }
+        for (int c0 = 0; c0 < used; c0 += 4) {
+            float2 ml4[4], v4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t pr = pbase + (c0 + u) * pstride;
+                const bool on = c0 + u < used;
+                ml4[u] = on ? *(const float2*)(part_ml + pr * 2) : make_float2(kNegBig, 0.f);
+                v4[u] = on ? *(const float2*)(part_o + pr * kD + lane * 2) : make_float2(0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (c0 + u < used) {   // wave-uniform
+                    const float w = exp2f((ml4[u].x - M) * scale_log2);
+                    L += ml4[u].y * w;
+                    a0 += v4[u].x * w;
+                    a1 += v4[u].y * w;
+                }
+            }
+        }
+    } else {
+    for (int c = 0; c < used; ++c) M = fmaxf(M, part_ml[(pbase + c * pstride) * 2]);
     for (int c = 0; c < used; ++c) {
         const int64_t pr = pbase + c * pstride;
         const float w = exp2f((part_ml[pr * 2] - M) * scale_log2);
@@ -737,6 +770,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(Rows rows, KVLayer kv, con
         const float2 v = *(const float2*)(part_o + pr * kD + lane * 2);
         a0 += v.x * w;
         a1 += v.y * w;
+    }
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
     o[lane] = pack_bf16x2(a0 * inv, a1 * inv);
@@ -785,8 +819,12 @@ static hipError_t launch_attn_mfma(hipStream_t s, const Rows& rows, const KVLaye
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int R = rows.n * (n_q_heads / kv.n_kv);
-    hipLaunchKernelGGL(attn_combine_k, dim3((R + 3) / 4, kv.n_kv, rows.B), dim3(256), 0, s, rows, kv, part_o, part_ml,
-                       (uint16_t*)out, work, n_q_heads, p.max_items, p.r_pad, scale_log2);
+    if ((int64_t)R * kv.n_kv * rows.B <= 4096)   // (waves: half of what the chip holds at once)
+        hipLaunchKernelGGL(attn_combine_k<true>, dim3((R + 3) / 4, kv.n_kv, rows.B), dim3(256), 0, s, rows, kv, part_o, part_ml,
+                           (uint16_t*)out, work, n_q_heads, p.max_items, p.r_pad, scale_log2);
+    else
+        hipLaunchKernelGGL(attn_combine_k<false>, dim3((R + 3) / 4, kv.n_kv, rows.B), dim3(256), 0, s, rows, kv, part_o, part_ml,
+                           (uint16_t*)out, work, n_q_heads, p.max_items, p.r_pad, scale_log2);
     return hipGetLastError();
 }
 
