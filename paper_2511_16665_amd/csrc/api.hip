@@ -475,7 +475,7 @@ int tlt_verify_forward(tlt_ctx* ctx, void* stream, int B, const tlt_tree* tree, 
                     gemm_argmax(s, M, V, h, ws + p.xn, ctx->target.lm_head, logits, out_argmax));
         } else {
             if ((rc = run_gemm(ctx, s, OUT_F32, M, V, h, ws + p.xn, ctx->target.lm_head, logits))) return rc;
-            if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax));
+            if (out_argmax) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 4, row_argmax(s, M, V, logits, out_argmax, ws + p.parts, p.parts_bytes));   // (nothing is pending: the slices' buffer is idle)
             if (out_lse) TLT_RUN(ctx, s, CLS_OTHER, 0, (double)M * V * 8, row_lse(s, M, V, logits, out_lse));
         }
     } else {

@@ -112,7 +112,9 @@ hipError_t attention(hipStream_t s, int dtype, const Rows& rows, const KVLayer& 
                      unsigned int* status = nullptr);
 
 // ---- sample.hip
-hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out);
+// (scratch, may be null: 8-byte aligned device memory the call may use, M * 256 bytes at most, to spread few rows over the chip)
+hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out, void* scratch = nullptr,
+                      size_t scratch_bytes = 0);
 // out [M][2]: (max, log-sum-exp) of every row
 hipError_t row_lse(hipStream_t s, int M, int V, const float* logits, float* out);
 // per row: log-softmax statistics and the K best (token, log-prob) pairs, best first.

@@ -109,6 +109,57 @@ __global__ __launch_bounds__(256) void row_argmax_k(int V, const float* __restri
     if (threadIdx.x == 0) out[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
 }
 
+// The same over one segment of a row (grid: segments x rows), for when there are too few rows to fill the chip with
+// one workgroup each: (value, index) of the segment's best entry, index 0x7fffffff for an empty segment; and the
+// merge of a row's segments, one wave per row (lowest index on ties, as in the single pass).
+__global__ __launch_bounds__(256) void row_argmax_seg_k(int V, int seg, int S, const float* __restrict__ logits,
+                                                        float* __restrict__ pv, int32_t* __restrict__ pi) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int sg = blockIdx.x, r = blockIdx.y;
+    const float* row = logits + (int64_t)r * V;
+    const int lo = sg * seg, hi = min(V, lo + seg);   // seg % 4 == 0
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    int j = lo + threadIdx.x;
+    if (V % 4 == 0 && ((uintptr_t)logits & 15) == 0) {
+        for (int q = lo + threadIdx.x * 4; q < hi; q += 1024) {
+            const float4 x = *(const float4*)(row + q);
+            if (x.x > bv || bi == 0x7fffffff) bv = x.x, bi = q;
+            if (x.y > bv) bv = x.y, bi = q + 1;
+            if (x.z > bv) bv = x.z, bi = q + 2;
+            if (x.w > bv) bv = x.w, bi = q + 3;
+        }
+        j = hi;
+    }
+    for (; j < hi; j += 256) {
+        const float v = row[j];
+        if (better(v, j, bv, bi)) {
+            bv = v;
+            bi = j;
+        }
+    }
+    block_best(bv, bi, sv, si);
+    if (threadIdx.x == 0) {
+        pv[(int64_t)r * S + sg] = bv;
+        pi[(int64_t)r * S + sg] = bi;
+    }
+}
+
+__global__ __launch_bounds__(64) void row_argmax_merge_k(int S, const float* __restrict__ pv, const int32_t* __restrict__ pi,
+                                                         int32_t* __restrict__ out) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int k = lane; k < S; k += 64) {
+        const float v = pv[(int64_t)r * S + k];
+        const int i = pi[(int64_t)r * S + k];
+        if (i != 0x7fffffff && (bi == 0x7fffffff || better(v, i, bv, bi))) bv = v, bi = i;
+    }
+    wave_best(bv, bi);
+    if (lane == 0) out[r] = bi == 0x7fffffff ? 0 : bi;
+}
+
 // (max, log-sum-exp) of every logits row: out[2r] = max_j l_j, out[2r+1] = max + log(sum_j exp(l_j - max)).
 __global__ __launch_bounds__(256) void row_lse_k(int V, const float* __restrict__ logits, float* __restrict__ out) {
     __shared__ float sf[4];
@@ -1254,8 +1305,19 @@ __global__ void seq_len_advance_k(int B, int32_t* seq_len, const int32_t* accept
 }
 
 // ------------------------------------------------------------------------------------------------
-hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out) {
+hipError_t row_argmax(hipStream_t s, int M, int V, const float* logits, int32_t* out, void* scratch, size_t scratch_bytes) {
     if (M <= 0) return hipSuccess;
+    // few rows: a row's scan over several workgroups (a single one pulls the 600 KB row through one CU's load path: 45 us)
+    int S = M < 128 ? 256 / M : 1;
+    S = S > 32 ? 32 : S;
+    if (S >= 2 && scratch && ((uintptr_t)scratch & 7) == 0 && (size_t)M * S * 8 <= scratch_bytes) {
+        const int seg = ((V + S - 1) / S + 3) / 4 * 4;
+        float* pv = (float*)scratch;
+        int32_t* pi = (int32_t*)(pv + (size_t)M * S);
+        hipLaunchKernelGGL(row_argmax_seg_k, dim3(S, M), dim3(256), 0, s, V, seg, S, logits, pv, pi);
+        hipLaunchKernelGGL(row_argmax_merge_k, dim3(M), dim3(64), 0, s, S, pv, pi, out);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(row_argmax_k, dim3(M), dim3(256), 0, s, V, logits, out);
     return hipGetLastError();
 }
